@@ -1,0 +1,121 @@
+/*
+ * qqq.h — C ABI of the MI355X (gfx950) W4A8 GEMM hot path of QQQ (arXiv 2406.09904).
+ *
+ * The path:  fp16 activations --qqq_quant_act--> int8 codes + per-token scale
+ *            int4 weight codes --qqq_pack_w4 (offline)--> device tile layout
+ *            qqq_gemm_w4a8_{perchannel,pergroup}:  Y[m,n] = fp16( acc[m,n] * s_a[m] * s_w[n] ),
+ *            acc[m,n] = sum_k A_q[m,k] * W8[n,k]  (int32, exact)
+ *
+ * Conventions common to every entry point
+ *   - Every pointer is a DEVICE pointer owned by the caller, 16-byte aligned, unless a
+ *     comment says "host".  The library never allocates, frees, synchronises or throws.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  A call only
+ *     enqueues kernels on it; ordering on that stream is the only synchronisation.
+ *   - Matrices are row-major and dense unless a leading dimension is given.
+ *   - Supported shapes: 1 <= M, N % 16 == 0, K % 128 == 0, 128 <= K <= 131072
+ *     (the worst-case |acc| = 127*128*K must stay below 2^31).  M == 0 is a no-op.
+ *   - Return value: QQQ_OK, or an error code; on any error nothing was enqueued and
+ *     no output was touched.  qqq_last_error() returns a static host string describing
+ *     the most recent error on the calling thread.
+ *   - Symmetric quantisation only: there are no zero-points anywhere (Sec. 3.3, Sec. 4.1).
+ */
+#ifndef QQQ_H_
+#define QQQ_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define QQQ_OK 0
+#define QQQ_ERR_NULL 1      /* a required pointer is NULL */
+#define QQQ_ERR_SHAPE 2     /* unsupported M/N/K/lda/group, or a misaligned pointer */
+#define QQQ_ERR_WORKSPACE 3 /* workspace smaller than qqq_gemm_workspace_bytes() */
+#define QQQ_ERR_HIP 4       /* the HIP runtime refused a launch */
+
+#define QQQ_GROUP 128 /* the only group size of the per-group variant ("-g128", Table 1) */
+
+/* Library version (major*100 + minor) and the text of the last error (host string, never NULL). */
+int qqq_version(void);
+const char* qqq_last_error(void);
+
+/*
+ * Per-token dynamic symmetric int8 quantisation of activations (Sec. 4.1 "Algorithm"; s_A in Fig. 3).
+ *   for every row m:  amax = max_k |A[m,k]|
+ *                     s_a[m] = amax / 127                      (fp32, correctly rounded division)
+ *                     a_q[m,k] = clamp(rne(A[m,k] / s_a[m]), -127, 127)   (fp32 division, ties to even)
+ *   an all-zero row gives s_a[m] = 0 and a_q[m,:] = 0.  Non-finite inputs are undefined.
+ *   a_fp16: [M, lda] fp16, lda >= K, lda % 8 == 0 (elements).   a_q: [M,K] int8.   s_a: [M] fp32.
+ */
+int qqq_quant_act(const void* a_fp16, int64_t M, int64_t K, int64_t lda, int8_t* a_q, float* s_a,
+                  void* stream);
+
+/*
+ * Offline weight repack (Sec. 3.3.1: weights are prepared offline; the kernels load int4).
+ *   w_nat: [N, K/8] uint32, natural interchange format: nibble i (bits 4i..4i+3) of word j of
+ *          row n is the 4-bit two's-complement code of W[n, 8j+i].
+ *   w_packed: qqq_packed_w4_bytes(N,K) = N*K/2 bytes, opaque device tile layout: 1 KiB chunks of
+ *          16 output channels x 128 k, ordered so that each lane's 128-bit load is, after the
+ *          in-register int4->int8 conversion, its int8 MFMA operand for two consecutive K-steps.
+ *   No value changes; qqq_unpack_w4 is the exact inverse (test helper).
+ */
+size_t qqq_packed_w4_bytes(int64_t N, int64_t K); /* 0 for unsupported shapes */
+int qqq_pack_w4(const uint32_t* w_nat, int64_t N, int64_t K, void* w_packed, void* stream);
+int qqq_unpack_w4(const void* w_packed, int64_t N, int64_t K, uint32_t* w_nat, void* stream);
+
+/*
+ * Scratch for split-K partial sums and tile counters.  The caller zero-fills it ONCE after
+ * allocation; every GEMM call leaves it zero again.  One workspace must not be shared by GEMM
+ * calls that may run concurrently (different streams).  Size depends on N only through this call.
+ */
+size_t qqq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+
+/*
+ * Per-channel W4A8 GEMM (Sec. 3.3.1, Fig. 3): int4 code widened to int8 in registers
+ * (upper-nibble placement = x16, undone exactly before the scales are applied), int8 MFMA with
+ * int32 accumulation, Dequant fused:  Y[m,n] = fp16_rne( float(acc[m,n]) * s_a[m] * float(s_w[n]) ).
+ *   a_q [M,K] int8; s_a [M] fp32; w_packed from qqq_pack_w4; s_w_fp16 [N] fp16;
+ *   y_fp16 [M,N] fp16 (written); acc_out [M,N] int32 or NULL: if given, also receives the TRUE
+ *   accumulator sum_k A_q*code (parity/debug).
+ */
+int qqq_gemm_w4a8_perchannel(const int8_t* a_q, const float* s_a, const void* w_packed,
+                             const void* s_w_fp16, void* y_fp16, int32_t* acc_out, int64_t M,
+                             int64_t N, int64_t K, void* workspace, size_t workspace_bytes,
+                             void* stream);
+
+/*
+ * Per-group W4A8 GEMM (Sec. 3.3.2, Fig. 4-6): the int8 weight is code x fused group scale,
+ *   W8[n,k] = clamp(code[n,k] * s_g[k/128][n], -128, 127),   s_g integer in 0..127,
+ * then the same int8 MFMA and Dequant with the per-channel scale s_w (s_Wc in Fig. 4).
+ *   s_g [K/128, N] int8 row-major; group must be 128.
+ *   sg_max: the caller's promise that every s_g <= sg_max.  With 1 <= sg_max <= 16 the product
+ *   cannot leave int8, the clamp is dead and a cheaper conversion is used; 0 = no promise
+ *   (general saturating conversion).  A broken promise gives wrong results, not a fault.
+ */
+int qqq_gemm_w4a8_pergroup(const int8_t* a_q, const float* s_a, const void* w_packed,
+                           const int8_t* s_g, const void* s_w_fp16, int group, int sg_max,
+                           void* y_fp16, int32_t* acc_out, int64_t M, int64_t N, int64_t K,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Tuning/diagnostic knob (host state, not thread-safe): force a kernel family.
+ *   0 = automatic, 1 = skinny split-K kernel, 2 = LDS-tiled prefill kernel.
+ * Returns the previous value.  Forcing a family outside its M range gives QQQ_ERR_SHAPE.
+ */
+int qqq_set_kernel_override(int family);
+
+/*
+ * Tuning/diagnostic knob (host state, not thread-safe): force how the per-group variant turns
+ * code x s_g into int8.  0 = automatic (from sg_max and M), 1 = scale applied to each group's
+ * partial sum (valid for s_g <= 16), 2 = per-weight saturating conversion (any s_g),
+ * 3 = per-weight fp16 FMA conversion without saturation (valid for s_g <= 16).
+ * Returns the previous value.
+ */
+int qqq_set_group_mode_override(int mode);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QQQ_H_ */

@@ -1,0 +1,161 @@
+"""Thin ctypes binding over libqqq.so (the C ABI declared in include/qqq.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP kernels.  PyTorch
+supplies device memory and the stream.  There is no CPU fallback: if the library is missing or a
+tensor is not on the GPU the call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libqqq.so")
+GROUP = 128
+
+SYMBOLS = [
+    "qqq_version", "qqq_last_error", "qqq_quant_act", "qqq_packed_w4_bytes", "qqq_pack_w4",
+    "qqq_unpack_w4", "qqq_gemm_workspace_bytes", "qqq_gemm_w4a8_perchannel",
+    "qqq_gemm_w4a8_pergroup", "qqq_set_kernel_override", "qqq_set_group_mode_override",
+]
+
+_lib = None
+
+
+class QQQError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("libqqq error %d: %s" % (code, msg))
+        self.code = code
+
+
+def lib():
+    """Loads the built library; raises if it has not been built (no fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "libqqq.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                "(or python paper_2406_09904_amd/build.py) first")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64, sz, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t, ctypes.c_int
+        L.qqq_version.restype = ci
+        L.qqq_last_error.restype = ctypes.c_char_p
+        L.qqq_quant_act.argtypes = [vp, i64, i64, i64, vp, vp, vp]
+        L.qqq_packed_w4_bytes.argtypes = [i64, i64]
+        L.qqq_packed_w4_bytes.restype = sz
+        L.qqq_pack_w4.argtypes = [vp, i64, i64, vp, vp]
+        L.qqq_unpack_w4.argtypes = [vp, i64, i64, vp, vp]
+        L.qqq_gemm_workspace_bytes.argtypes = [i64, i64, i64]
+        L.qqq_gemm_workspace_bytes.restype = sz
+        L.qqq_gemm_w4a8_perchannel.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, sz, vp]
+        L.qqq_gemm_w4a8_pergroup.argtypes = [vp, vp, vp, vp, vp, ci, ci, vp, vp, i64, i64, i64,
+                                             vp, sz, vp]
+        L.qqq_set_kernel_override.argtypes = [ci]
+        L.qqq_set_group_mode_override.argtypes = [ci]
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise QQQError(rc, lib().qqq_last_error().decode())
+
+
+def _ptr(t, dtype=None):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("libqqq takes device tensors only")
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError("expected %s, got %s" % (dtype, t.dtype))
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def qqq_quant_act(a_fp16: torch.Tensor, a_q: torch.Tensor = None, s_a: torch.Tensor = None):
+    """a_fp16 [M,K] fp16 (row stride allowed) -> (a_q int8 [M,K], s_a fp32 [M])."""
+    if a_fp16.dtype != torch.float16 or a_fp16.dim() != 2 or a_fp16.stride(1) != 1:
+        raise ValueError("a_fp16 must be a 2-D fp16 tensor with unit inner stride")
+    M, K = a_fp16.shape
+    lda = a_fp16.stride(0) if M > 1 else max(K, a_fp16.stride(0))
+    if a_q is None:
+        a_q = torch.empty((M, K), dtype=torch.int8, device=a_fp16.device)
+    if s_a is None:
+        s_a = torch.empty((M,), dtype=torch.float32, device=a_fp16.device)
+    if not a_fp16.is_cuda:
+        raise ValueError("libqqq takes device tensors only")
+    _check(lib().qqq_quant_act(ctypes.c_void_p(a_fp16.data_ptr()), M, K, lda,
+                               _ptr(a_q, torch.int8), _ptr(s_a, torch.float32), _stream()))
+    return a_q, s_a
+
+
+def qqq_packed_w4_bytes(N: int, K: int) -> int:
+    return int(lib().qqq_packed_w4_bytes(N, K))
+
+
+def qqq_pack_w4(w_nat: torch.Tensor, K: int, out: torch.Tensor = None) -> torch.Tensor:
+    """w_nat [N,K/8] int32 (bit pattern of the uint32 natural words) -> opaque packed uint8 [N*K/2]."""
+    N = w_nat.shape[0]
+    nbytes = qqq_packed_w4_bytes(N, K)
+    if nbytes == 0 or w_nat.shape[1] * 8 != K:
+        raise QQQError(2, "pack: unsupported N=%d K=%d" % (N, K))
+    if out is None:
+        out = torch.empty((nbytes,), dtype=torch.uint8, device=w_nat.device)
+    _check(lib().qqq_pack_w4(_ptr(w_nat, torch.int32), N, K, _ptr(out, torch.uint8), _stream()))
+    return out
+
+
+def qqq_unpack_w4(w_packed: torch.Tensor, N: int, K: int) -> torch.Tensor:
+    out = torch.empty((N, K // 8), dtype=torch.int32, device=w_packed.device)
+    _check(lib().qqq_unpack_w4(_ptr(w_packed, torch.uint8), N, K, _ptr(out, torch.int32), _stream()))
+    return out
+
+
+def qqq_gemm_workspace_bytes(M: int, N: int, K: int) -> int:
+    return int(lib().qqq_gemm_workspace_bytes(M, N, K))
+
+
+def new_workspace(M: int, N: int, K: int, device="cuda") -> torch.Tensor:
+    """Zero-filled workspace (zeroed once here; every GEMM call leaves it zero)."""
+    return torch.zeros((max(qqq_gemm_workspace_bytes(M, N, K), 16),), dtype=torch.uint8, device=device)
+
+
+def qqq_gemm_w4a8_perchannel(a_q, s_a, w_packed, s_w, workspace, y=None, acc_out=None, N=None):
+    M, K = a_q.shape
+    N = s_w.shape[0] if N is None else N
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=a_q.device)
+    _check(lib().qqq_gemm_w4a8_perchannel(
+        _ptr(a_q, torch.int8), _ptr(s_a, torch.float32), _ptr(w_packed, torch.uint8),
+        _ptr(s_w, torch.float16), _ptr(y, torch.float16), _ptr(acc_out, torch.int32), M, N, K,
+        _ptr(workspace, torch.uint8), workspace.numel(), _stream()))
+    return y
+
+
+def qqq_gemm_w4a8_pergroup(a_q, s_a, w_packed, s_g, s_w, workspace, sg_max=0, y=None, acc_out=None,
+                           group=GROUP):
+    M, K = a_q.shape
+    N = s_w.shape[0]
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=a_q.device)
+    _check(lib().qqq_gemm_w4a8_pergroup(
+        _ptr(a_q, torch.int8), _ptr(s_a, torch.float32), _ptr(w_packed, torch.uint8),
+        _ptr(s_g, torch.int8), _ptr(s_w, torch.float16), group, sg_max, _ptr(y, torch.float16),
+        _ptr(acc_out, torch.int32), M, N, K, _ptr(workspace, torch.uint8), workspace.numel(),
+        _stream()))
+    return y
+
+
+def set_kernel_override(family: int) -> int:
+    return lib().qqq_set_kernel_override(family)
+
+
+def set_group_mode_override(mode: int) -> int:
+    return lib().qqq_set_group_mode_override(mode)

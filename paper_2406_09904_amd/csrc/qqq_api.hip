@@ -1,0 +1,170 @@
+// C-ABI entry points of libqqq: argument validation and kernel-family dispatch (host code only).
+#include <stdarg.h>
+#include <stdio.h>
+
+#include "qqq_internal.h"
+
+namespace qqq {
+
+static thread_local char g_err[256] = "no error";
+static int g_override = 0;
+static int g_group_mode = 0;
+
+int set_error(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+int num_cus() {
+  static int cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+      n = 256;
+    cached[dev] = n;
+  }
+  return cached[dev];
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static bool gemm_shape_ok(int64_t M, int64_t N, int64_t K) {
+  return M >= 0 && M <= 0x7FFFFFFF && N >= 16 && N % 16 == 0 && N <= 0x7FFFFFF0 && K >= 128 &&
+         K % 128 == 0 && K <= 131072;
+}
+
+static size_t ws_rows(int64_t M) { return (size_t)(M < kSkinnyMaxM ? M : kSkinnyMaxM); }
+
+static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed, const int8_t* s_g,
+                       const void* s_w, void* y, int32_t* acc_out, int64_t M, int64_t N, int64_t K,
+                       void* workspace, size_t workspace_bytes, void* stream, int mode) {
+  if (!gemm_shape_ok(M, N, K))
+    return set_error(QQQ_ERR_SHAPE, "gemm: unsupported shape M=%lld N=%lld K=%lld (need N%%16==0, "
+                     "K%%128==0, 128<=K<=131072)", (long long)M, (long long)N, (long long)K);
+  if (M == 0) return QQQ_OK;
+  if (!a_q || !s_a || !w_packed || !s_w || !y || (mode != kPerChannel && !s_g))
+    return set_error(QQQ_ERR_NULL, "gemm: null pointer argument");
+  if (!aligned16(a_q) || !aligned16(w_packed) || !aligned16(y) || !aligned16(workspace))
+    return set_error(QQQ_ERR_SHAPE, "gemm: a_q, w_packed, y and workspace must be 16-byte aligned");
+  int family = g_override;
+  if (family == 0) family = (M <= kSkinnyMaxM) ? 1 : 2;
+  if (family == 1 && M > kSkinnyMaxM)
+    return set_error(QQQ_ERR_SHAPE, "gemm: skinny kernel forced but M=%lld > %d", (long long)M,
+                     kSkinnyMaxM);
+  GemmParams p;
+  p.a_q = a_q;
+  p.s_a = s_a;
+  p.w = (const uint4*)w_packed;
+  p.s_g = s_g;
+  p.s_w = (const _Float16*)s_w;
+  p.y = (_Float16*)y;
+  p.acc_out = acc_out;
+  p.M = (int)M;
+  p.N = (int)N;
+  p.K = (int)K;
+  p.T = (int)(K / 128);
+  p.ws_cnt = nullptr;
+  p.ws_acc = nullptr;
+  if (family == 1) {
+    const size_t need = qqq_gemm_workspace_bytes(M, N, K);
+    if (!workspace) return set_error(QQQ_ERR_NULL, "gemm: workspace is NULL");
+    if (workspace_bytes < need)
+      return set_error(QQQ_ERR_WORKSPACE, "gemm: workspace %zu bytes < %zu needed", workspace_bytes,
+                       need);
+    p.ws_cnt = (int32_t*)workspace;
+    p.ws_acc = (int32_t*)((char*)workspace + (((size_t)(N / 16) * 4 + 255) & ~(size_t)255));
+    return launch_gemm_skinny(p, mode, (hipStream_t)stream);
+  }
+  return launch_gemm_prefill(p, mode, (hipStream_t)stream);
+}
+
+}  // namespace qqq
+
+using namespace qqq;
+
+extern "C" {
+
+int qqq_version(void) { return 100; }
+
+const char* qqq_last_error(void) { return g_err; }
+
+int qqq_set_kernel_override(int family) {
+  const int old = g_override;
+  if (family >= 0 && family <= 2) g_override = family;
+  return old;
+}
+
+int qqq_quant_act(const void* a_fp16, int64_t M, int64_t K, int64_t lda, int8_t* a_q, float* s_a,
+                  void* stream) {
+  if (M < 0 || M > 0x7FFFFFFF || K < 8 || K % 8 != 0 || K > (1 << 24) || lda < K || lda % 8 != 0)
+    return set_error(QQQ_ERR_SHAPE, "quant_act: unsupported M=%lld K=%lld lda=%lld (need K%%8==0, "
+                     "lda%%8==0, lda>=K)", (long long)M, (long long)K, (long long)lda);
+  if (M == 0) return QQQ_OK;
+  if (!a_fp16 || !a_q || !s_a) return set_error(QQQ_ERR_NULL, "quant_act: null pointer argument");
+  if (!aligned16(a_fp16) || (reinterpret_cast<uintptr_t>(a_q) & 7u))
+    return set_error(QQQ_ERR_SHAPE, "quant_act: a_fp16 must be 16-byte and a_q 8-byte aligned");
+  return launch_quant_act(a_fp16, M, K, lda, a_q, s_a, (hipStream_t)stream);
+}
+
+int qqq_set_group_mode_override(int mode) {
+  const int old = g_group_mode;
+  if (mode >= 0 && mode <= 3) g_group_mode = mode;
+  return old;
+}
+
+size_t qqq_packed_w4_bytes(int64_t N, int64_t K) {
+  if (N < 16 || N % 16 != 0 || K < 128 || K % 128 != 0 || K > 131072 || N > 0x7FFFFFF0) return 0;
+  return (size_t)N * (size_t)K / 2;
+}
+
+static int pack_common(const void* src, int64_t N, int64_t K, void* dst, bool inverse, void* stream) {
+  if (qqq_packed_w4_bytes(N, K) == 0)
+    return set_error(QQQ_ERR_SHAPE, "pack: unsupported N=%lld K=%lld (need N%%16==0, K%%128==0)",
+                     (long long)N, (long long)K);
+  if (!src || !dst) return set_error(QQQ_ERR_NULL, "pack: null pointer argument");
+  if (src == dst) return set_error(QQQ_ERR_SHAPE, "pack: in-place repack is not supported");
+  return launch_pack((const uint32_t*)src, N, K, (uint32_t*)dst, inverse, (hipStream_t)stream);
+}
+
+int qqq_pack_w4(const uint32_t* w_nat, int64_t N, int64_t K, void* w_packed, void* stream) {
+  return pack_common(w_nat, N, K, w_packed, false, stream);
+}
+
+int qqq_unpack_w4(const void* w_packed, int64_t N, int64_t K, uint32_t* w_nat, void* stream) {
+  return pack_common(w_packed, N, K, w_nat, true, stream);
+}
+
+size_t qqq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
+  if (!gemm_shape_ok(M, N, K)) return 0;
+  const size_t cnt = ((size_t)(N / 16) * 4 + 255) & ~(size_t)255;
+  return cnt + ws_rows(M) * (size_t)N * 4;
+}
+
+int qqq_gemm_w4a8_perchannel(const int8_t* a_q, const float* s_a, const void* w_packed,
+                             const void* s_w_fp16, void* y_fp16, int32_t* acc_out, int64_t M,
+                             int64_t N, int64_t K, void* workspace, size_t workspace_bytes,
+                             void* stream) {
+  return gemm_common(a_q, s_a, w_packed, nullptr, s_w_fp16, y_fp16, acc_out, M, N, K, workspace,
+                     workspace_bytes, stream, kPerChannel);
+}
+
+int qqq_gemm_w4a8_pergroup(const int8_t* a_q, const float* s_a, const void* w_packed,
+                           const int8_t* s_g, const void* s_w_fp16, int group, int sg_max,
+                           void* y_fp16, int32_t* acc_out, int64_t M, int64_t N, int64_t K,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+  if (group != QQQ_GROUP) return set_error(QQQ_ERR_SHAPE, "pergroup: group must be 128, got %d", group);
+  if (sg_max < 0 || sg_max > 127)
+    return set_error(QQQ_ERR_SHAPE, "pergroup: sg_max must be in 0..127, got %d", sg_max);
+  int mode = kGroupClamp;
+  if (sg_max >= 1 && sg_max <= 16) mode = (M <= kSkinnyMaxM) ? kGroupLinear : kGroupFused;
+  if (g_group_mode != 0) mode = g_group_mode;
+  return gemm_common(a_q, s_a, w_packed, s_g, s_w_fp16, y_fp16, acc_out, M, N, K, workspace,
+                     workspace_bytes, stream, mode);
+}
+
+}  // extern "C"

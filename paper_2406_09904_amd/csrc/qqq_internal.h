@@ -1,0 +1,132 @@
+// Internal declarations shared by the translation units of libqqq (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "qqq.h"
+
+namespace qqq {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+
+// How the int4 codes become the int8 MFMA operand.
+enum Mode : int {
+  kPerChannel = 0,    // Sec. 3.3.1: code in the upper nibble (x16), undone before the scales
+  kGroupLinear = 1,   // Sec. 3.3.2 with s_g <= 16: clamp is dead, so the group scale is applied to
+                      // the group's partial int32 sum instead of to each weight (same integers)
+  kGroupClamp = 2,    // Sec. 3.3.2, general: code*s_g saturated to int8 per weight (fp16 route)
+  kGroupFused = 3,    // Sec. 3.3.2 with s_g <= 16: per-weight fp16 FMA + byte extract, no clamp
+};
+
+struct GemmParams {
+  const int8_t* a_q;    // [M,K]
+  const float* s_a;     // [M]
+  const uint4* w;       // packed int4, 1 KiB chunks [N/16][K/128][64 lanes]
+  const int8_t* s_g;    // [K/128,N] or nullptr
+  const _Float16* s_w;  // [N]
+  _Float16* y;          // [M,N]
+  int32_t* acc_out;     // [M,N] or nullptr
+  int32_t* ws_cnt;      // [N/16] arrival counters (zero between calls)
+  int32_t* ws_acc;      // [ws_rows,N] split-K partial sums (zero between calls)
+  int M, N, K, T;       // T = K/128
+};
+
+// host-side helpers (qqq_api.hip)
+int set_error(int code, const char* fmt, ...);
+int num_cus();
+
+// launchers; each returns QQQ_OK or QQQ_ERR_HIP/QQQ_ERR_SHAPE
+int launch_quant_act(const void* a, int64_t M, int64_t K, int64_t lda, int8_t* a_q, float* s_a,
+                     hipStream_t st);
+int launch_pack(const uint32_t* w_nat, int64_t N, int64_t K, uint32_t* w_packed, bool inverse,
+                hipStream_t st);
+int launch_gemm_skinny(const GemmParams& p, int mode, hipStream_t st);
+int launch_gemm_prefill(const GemmParams& p, int mode, hipStream_t st);
+
+constexpr int kSkinnyMaxM = 64;  // rows the split-K kernel handles (4 MFMA row tiles)
+
+// ---------------------------------------------------------------------------------------------
+// Packed layout.  Chunk (nt, t) = output channels [16nt,16nt+16) x k in [128t,128t+128), 1 KiB at
+// ((nt*T)+t)*1024.  Lane l = nl + 16*kc (nl = n%16, kc = 0..3) owns 16 bytes = dwords d0..d3.
+// Nibble q of dword i holds the code of k = 128t + 64*(i/2) + 16*kc + 8*(i%2) + 4*(q%2) + q/2,
+// i.e. each packed dword is natural word (k/8) with its nibbles reordered 0,4,1,5,2,6,3,7 so that
+// "even nibbles" and "odd nibbles" each come out as four k-consecutive bytes.
+// After conversion, dwords (lo(d0),hi(d0),lo(d1),hi(d1)) are the 16 k-consecutive int8 values
+// k = 128t + 16kc + 0..15 of MFMA step 0 and (lo(d2),hi(d2),lo(d3),hi(d3)) those of step 1 (+64).
+// ---------------------------------------------------------------------------------------------
+
+// Sec. 3.3.1 FastINT4toINT8: nibble into the upper half of its byte = 16*code as int8.
+__device__ __forceinline__ void unpack_x16(uint32_t x, int& lo, int& hi) {
+  lo = (int)((x << 4) & 0xF0F0F0F0u);
+  hi = (int)(x & 0xF0F0F0F0u);
+}
+
+__device__ __forceinline__ h2 as_h2(uint32_t u) { return __builtin_bit_cast(h2, u); }
+__device__ __forceinline__ uint32_t as_u32(h2 h) { return __builtin_bit_cast(uint32_t, h); }
+
+// Sec. 3.3.2, general route: int4 -> fp16 by mantissa placement (FastINT4toFP16: 0x6400|u is
+// 1024+u), FusedDequantQuant as one fp16 multiply by the integer group scale, saturation to
+// [-128,127], then FastFP16toINT8: adding 1536 puts code*s mod 256 into the low mantissa byte
+// (1536 = 1024 + 512 keeps the sum inside [1024,2048) and makes the byte two's complement
+// directly, so the XOR 0x80 of the unsigned variant is not needed).
+// `s` holds the scale in both halves.  All intermediate values are integers below 2048: exact.
+__device__ __forceinline__ void unpack_group_clamp(uint32_t x, h2 s, int& lo, int& hi) {
+  const uint32_t y = x ^ 0x88888888u;  // two's complement nibble -> offset binary u = code + 8
+  const h2 k1032 = {(_Float16)1032.0f, (_Float16)1032.0f};
+  const h2 k1536 = {(_Float16)1536.0f, (_Float16)1536.0f};
+  const h2 kmin = {(_Float16)-128.0f, (_Float16)-128.0f};
+  const h2 kmax = {(_Float16)127.0f, (_Float16)127.0f};
+  uint32_t f[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    h2 c = as_h2(((y >> (4 * j)) & 0x000F000Fu) | 0x64006400u) - k1032;  // nibbles j and j+4
+    h2 p = c * s;
+    p = __builtin_elementwise_min(__builtin_elementwise_max(p, kmin), kmax);
+    f[j] = as_u32(p + k1536);
+  }
+  // bytes: lo = nibbles (0,2,4,6) = (f0.b0, f2.b0, f0.b2, f2.b2); hi = nibbles (1,3,5,7)
+  lo = (int)((f[0] & 0xFFu) | ((f[2] & 0xFFu) << 8) | (f[0] & 0x00FF0000u) |
+             ((f[2] & 0x00FF0000u) << 8));
+  hi = (int)((f[1] & 0xFFu) | ((f[3] & 0xFFu) << 8) | (f[1] & 0x00FF0000u) |
+             ((f[3] & 0x00FF0000u) << 8));
+}
+
+// Sec. 3.3.2 with the clamp dead (s <= 16): one fp16 FMA per weight pair does the scale multiply
+// and the magic add together.  Even nibble pairs sit at mantissa bit 0 (value 1024+u, multiplier
+// s, addend 1536-1032s); odd nibble pairs are left at mantissa bit 4 (value 1024+16u, multiplier
+// s/16, addend 1536-72s) which saves their shift.  All four constants are exact in fp16 for s<=16.
+struct GroupFusedConsts {
+  h2 s, c0, s16, c1;
+};
+__device__ __forceinline__ GroupFusedConsts make_group_fused(int s) {
+  const float fs = (float)s;
+  GroupFusedConsts g;
+  g.s = {(_Float16)fs, (_Float16)fs};
+  g.c0 = {(_Float16)(1536.0f - 1032.0f * fs), (_Float16)(1536.0f - 1032.0f * fs)};
+  g.s16 = {(_Float16)(fs * 0.0625f), (_Float16)(fs * 0.0625f)};
+  g.c1 = {(_Float16)(1536.0f - 72.0f * fs), (_Float16)(1536.0f - 72.0f * fs)};
+  return g;
+}
+__device__ __forceinline__ void unpack_group_fused(uint32_t x, const GroupFusedConsts& g, int& lo,
+                                                   int& hi) {
+  const uint32_t y = x ^ 0x88888888u;
+  const uint32_t y8 = y >> 8;
+  const uint32_t magic = 0x64006400u;
+  const h2 f0 = __builtin_elementwise_fma(as_h2((y & 0x000F000Fu) | magic), g.s, g.c0);     // 0,4
+  const h2 f1 = __builtin_elementwise_fma(as_h2((y & 0x00F000F0u) | magic), g.s16, g.c1);   // 1,5
+  const h2 f2 = __builtin_elementwise_fma(as_h2((y8 & 0x000F000Fu) | magic), g.s, g.c0);    // 2,6
+  const h2 f3 = __builtin_elementwise_fma(as_h2((y8 & 0x00F000F0u) | magic), g.s16, g.c1);  // 3,7
+  // v_perm_b32: selector bytes 0-3 pick from the second source, 4-7 from the first
+  lo = (int)__builtin_amdgcn_perm(as_u32(f2), as_u32(f0), 0x06020400u);
+  hi = (int)__builtin_amdgcn_perm(as_u32(f3), as_u32(f1), 0x06020400u);
+}
+
+// Dequant (Sec. 3.3.1/3.3.2 last step): int32 -> fp32 -> two fp32 multiplies -> fp16 (RNE).
+__device__ __forceinline__ _Float16 dequant(int acc, float sa, float sw) {
+  return (_Float16)(((float)acc * sa) * sw);
+}
+
+}  // namespace qqq
