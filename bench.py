@@ -1,0 +1,277 @@
+#!/usr/bin/env python3
+"""Benchmark of the W4A8 hot path (quantise activations -> W4A8 GEMM) on one MI355X.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-sweep]
+                  [--no-cpu-baseline] [--eager]
+
+A step is one pass of the whole hot path over one batch of seeded synthetic input that is
+already resident in HBM: qqq_quant_act on the fp16 activations, then the W4A8 GEMM of the
+workload's variant (weights were repacked once, offline, outside the timed region).  Packed
+weights (and group scales) exist in R copies whose total exceeds four times the 256 MiB
+last-level cache and consecutive steps rotate through them, so every step streams its weights
+from HBM rather than from cache.  The K timed steps are captured once into a HIP graph and
+replayed, which removes Python's launch overhead from microsecond-scale kernels (--eager
+disables that).  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "W4A8 GEMM TOPS and % roofline (HBM at M<=16, int8 MFMA at M>=1024)"
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_I8_PEAK_TOPS = 5033.0     # dense int8 MFMA: 256 CU x 4 SIMD x 2048 op/clk x 2.4 GHz
+PRIMARY = "cfg2_pg_m1_k4096_n11008"
+SWEEP = ["cfg1_pc_m16_k4096_n4096", "cfg3_pc_m1_k5120_n13824", "cfg3_pc_m8_k5120_n13824",
+         "cfg3_pc_m2048_k5120_n13824", "cfg4_pg_m4096_k11008_n4096",
+         "cfg5_pc_m1_k8192_n28672", "cfg5_pg_m16_k8192_n28672", "cfg5_pc_m4096_k8192_n28672",
+         "cfg5_pg_m4096_k8192_n28672"]
+
+
+def algorithmic_bytes(M, N, K, pergroup):
+    """What the method itself must move once: packed int4 weights, group scales, fp16 channel
+    scales, int8 activations, fp32 token scales, fp16 output."""
+    return N * K // 2 + (K // 128 * N if pergroup else 0) + 2 * N + M * K + 4 * M + 2 * M * N
+
+
+def quant_bytes(M, K):
+    return 2 * M * K + M * K + 4 * M
+
+
+class Case:
+    """Device-resident inputs of one workload plus the launch closures."""
+
+    def __init__(self, wl, torch, qqq, rotate_bytes=1 << 30, max_copies=64):
+        import numpy as np
+        self.wl = wl
+        self.pg = wl.variant == "pergroup"
+        M, K, N = wl.M, wl.K, wl.N
+        self.a = torch.from_numpy(wl.activations()).cuda()
+        w_nat = torch.from_numpy(wl.w_nat().view(np.int32)).cuda()
+        packed = qqq.qqq_pack_w4(w_nat, K)
+        del w_nat
+        per_copy = packed.numel() + (K // 128 * N if self.pg else 0)
+        self.copies = int(max(1, min(max_copies, -(-rotate_bytes // per_copy))))
+        self.w = [packed] + [packed.clone() for _ in range(self.copies - 1)]
+        self.s_w = torch.from_numpy(wl.s_w()).cuda()
+        if self.pg:
+            sg = torch.from_numpy(wl.s_g()).cuda()
+            self.s_g = [sg] + [sg.clone() for _ in range(self.copies - 1)]
+        self.a_q = torch.empty((M, K), dtype=torch.int8, device="cuda")
+        self.s_a = torch.empty((M,), dtype=torch.float32, device="cuda")
+        self.y = torch.empty((M, N), dtype=torch.float16, device="cuda")
+        self.ws = qqq.new_workspace(M, N, K)
+        self.qqq = qqq
+        self.ops = 2 * M * N * K
+        self.bytes = algorithmic_bytes(M, N, K, self.pg)
+
+    def quant(self):
+        self.qqq.qqq_quant_act(self.a, self.a_q, self.s_a)
+
+    def gemm(self, i):
+        r = i % self.copies
+        if self.pg:
+            self.qqq.qqq_gemm_w4a8_pergroup(self.a_q, self.s_a, self.w[r], self.s_g[r], self.s_w,
+                                            self.ws, sg_max=self.wl.sg_hi, y=self.y)
+        else:
+            self.qqq.qqq_gemm_w4a8_perchannel(self.a_q, self.s_a, self.w[r], self.s_w, self.ws,
+                                              y=self.y)
+
+    def step(self, i):
+        self.quant()
+        self.gemm(i)
+
+
+def timed(torch, fn, steps, warmup, use_graph):
+    """fn(i) enqueues one unit of work on the current stream.  Returns average ms per unit over
+    exactly `steps` units, measured with events on that stream between two synchronisations."""
+    for i in range(warmup):
+        fn(i)
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    graph = None
+    if use_graph:
+        try:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                for i in range(steps):
+                    fn(warmup + i)
+            graph.replay()           # one untimed replay: graph upload
+            torch.cuda.synchronize()
+        except Exception as ex:      # capture unsupported: fall back to eager launches
+            print("bench: graph capture failed (%s); timing eager launches" % ex, file=sys.stderr)
+            graph = None
+            torch.cuda.synchronize()
+    torch.cuda.synchronize()
+    e0.record()
+    if graph is not None:
+        graph.replay()
+    else:
+        for i in range(steps):
+            fn(warmup + i)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps, graph is not None
+
+
+def roofline_for(case, gemm_ms):
+    wl = case.wl
+    t_mem = case.bytes / (HBM_PEAK_GBS * 1e9)
+    t_mfma = case.ops / (MFMA_I8_PEAK_TOPS * 1e12)
+    if t_mem >= t_mfma:
+        achieved = case.bytes / (gemm_ms * 1e-3) / 1e9
+        return {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4)}
+    achieved = case.ops / (gemm_ms * 1e-3) / 1e12
+    return {"bound": "mfma", "achieved": round(achieved, 1), "peak": MFMA_I8_PEAK_TOPS,
+            "unit": "TOP/s", "frac": round(achieved / MFMA_I8_PEAK_TOPS, 4)}
+
+
+def load_traffic(name):
+    """HBM bytes per GEMM launch from the rocprofv3 --pmc summaries under profiles/, if present."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(name)
+    except (OSError, ValueError):
+        return None
+
+
+def measure(case, torch, steps, warmup, use_graph):
+    step_ms, graphed = timed(torch, case.step, steps, warmup, use_graph)
+    gemm_ms, _ = timed(torch, case.gemm, steps, warmup, use_graph)
+    quant_ms, _ = timed(torch, lambda i: case.quant(), steps, warmup, use_graph)
+    return step_ms, gemm_ms, quant_ms, graphed
+
+
+def cpu_baseline(wl, budget_s=12.0):
+    """The oracle, as it stands, on this machine's host cores: whole path on the workload (repeated
+    until the time budget is used when one pass is short, on a row subset when one pass is long)."""
+    import numpy as np
+    from oracle import qqq_oracle as orc
+    cores = os.cpu_count() or 1
+    try:
+        cores = len(os.sched_getaffinity(0))
+    except AttributeError:
+        pass
+    env = os.environ.get("OMP_NUM_THREADS")
+    if env and env.isdigit():
+        cores = min(cores, int(env)) if int(env) > 0 else cores
+    a, w_nat, s_w = wl.activations(), wl.w_nat(), wl.s_w().view(np.uint16)
+    s_g = wl.s_g() if wl.variant == "pergroup" else None
+    rows = wl.M
+    macs_full = wl.M * wl.N * wl.K
+    if macs_full > 4e9:                       # keep one pass to roughly ten seconds
+        rows = max(1, int(wl.M * 4e9 / macs_full))
+    a = np.ascontiguousarray(a[:rows])
+
+    def one_pass():
+        a_q, s_a = orc.quant_act(a.view(np.uint16))
+        if s_g is None:
+            orc.gemm_perchannel(a_q, s_a, w_nat, s_w)
+        else:
+            orc.gemm_pergroup(a_q, s_a, w_nat, s_g, s_w)
+
+    one_pass()                                # builds/loads the library, warms the page cache
+    reps, t0 = 0, time.perf_counter()
+    while True:
+        one_pass()
+        reps += 1
+        el = time.perf_counter() - t0
+        if el >= budget_s or reps >= 200:
+            break
+    tops = 2.0 * rows * wl.N * wl.K * reps / el / 1e12
+    return {"value": round(tops, 6), "unit": "TOPS", "cores": cores, "kind": "oracle",
+            "sample": "%d pass(es) of quant_act + %s GEMM on rows 0..%d of %s (all N=%d columns, "
+                      "K=%d), %.1f s wall" % (reps, wl.variant, rows - 1, wl.name, wl.N, wl.K, el)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default=PRIMARY)
+    ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--eager", action="store_true", help="time eager launches, no HIP graph")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2406_09904_amd import binding as qqq
+    from paper_2406_09904_amd import synth
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    qqq.lib()                                  # fails loudly if the HIP library is not built
+    torch.cuda.set_device(0)
+    wls = synth.workloads()
+    if args.workload not in wls:
+        print("unknown workload %s; choose from: %s" % (args.workload, ", ".join(wls)),
+              file=sys.stderr)
+        return 2
+
+    use_graph = not args.eager
+    wl = wls[args.workload]
+    case = Case(wl, torch, qqq)
+    step_ms, gemm_ms, quant_ms, graphed = measure(case, torch, args.steps, args.warmup, use_graph)
+    roof = roofline_for(case, gemm_ms)
+    roof["traffic"] = load_traffic(wl.name)
+    roof["kernel"] = "gemm_w4a8_%s" % wl.variant
+    roof["kernel_us"] = round(gemm_ms * 1e3, 3)
+    roof["algorithmic_bytes"] = case.bytes
+    out = {
+        "metric": METRIC, "value": round(case.ops / (step_ms * 1e-3) / 1e12, 4), "unit": "TOPS",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(step_ms, 6), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": wl.name, "variant": wl.variant, "M": wl.M, "K": wl.K, "N": wl.N,
+                   "group": 128 if wl.variant == "pergroup" else None,
+                   "step": "qqq_quant_act + qqq_gemm_w4a8_%s" % wl.variant,
+                   "weight_copies_rotated": case.copies, "hip_graph": graphed,
+                   "quant_act_us": round(quant_ms * 1e3, 3), "gemm_us": round(gemm_ms * 1e3, 3)},
+        "roofline": roof,
+    }
+    del case
+    torch.cuda.empty_cache()
+
+    if not args.no_sweep:
+        sweep = []
+        for name in SWEEP:
+            if name == wl.name:
+                continue
+            w2 = wls[name]
+            big = w2.M >= 1024
+            c2 = Case(w2, torch, qqq, rotate_bytes=(1 << 28) if big else (1 << 30))
+            st = max(5, min(args.steps, 20 if big else 100))
+            s_ms, g_ms, q_ms, _ = measure(c2, torch, st, min(args.warmup, 5), use_graph)
+            r2 = roofline_for(c2, g_ms)
+            sweep.append({"workload": name, "steps": st, "ms_per_step": round(s_ms, 6),
+                          "gemm_us": round(g_ms * 1e3, 3), "quant_act_us": round(q_ms * 1e3, 3),
+                          "quant_act_gbs": round(quant_bytes(w2.M, w2.K) / (q_ms * 1e-3) / 1e9, 1),
+                          "tops": round(c2.ops / (s_ms * 1e-3) / 1e12, 3),
+                          "roofline": r2})
+            del c2
+            torch.cuda.empty_cache()
+        out["sweep"] = sweep
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

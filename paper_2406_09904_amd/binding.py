@@ -18,7 +18,7 @@ GROUP = 128
 SYMBOLS = [
     "qqq_version", "qqq_last_error", "qqq_quant_act", "qqq_packed_w4_bytes", "qqq_pack_w4",
     "qqq_unpack_w4", "qqq_gemm_workspace_bytes", "qqq_gemm_w4a8_perchannel",
-    "qqq_gemm_w4a8_pergroup", "qqq_set_kernel_override", "qqq_set_group_mode_override",
+    "qqq_gemm_w4a8_pergroup", "qqq_set_kernel_override", "qqq_set_group_mode_override", "qqq_set_skinny_tuning",
 ]
 
 _lib = None
@@ -54,6 +54,7 @@ def lib():
                                              vp, sz, vp]
         L.qqq_set_kernel_override.argtypes = [ci]
         L.qqq_set_group_mode_override.argtypes = [ci]
+        L.qqq_set_skinny_tuning.argtypes = [ci, ci, ci]
         _lib = L
     return _lib
 
@@ -159,3 +160,7 @@ def set_kernel_override(family: int) -> int:
 
 def set_group_mode_override(mode: int) -> int:
     return lib().qqq_set_group_mode_override(mode)
+
+
+def set_skinny_tuning(channel_tiles: int, k_slices: int, waves: int = 0) -> int:
+    return lib().qqq_set_skinny_tuning(channel_tiles, k_slices, waves)

@@ -61,7 +61,7 @@ __global__ __launch_bounds__(256) void gemm_prefill_kernel(const GemmParams p, c
       wreg[i] = make_uint4(0, 0, 0, 0);
       sgreg[i] = 0;
       if (nt0 + i < ntiles) {
-        wreg[i] = p.w[((int64_t)(nt0 + i) * T + t) * 64 + lane];
+        wreg[i] = p.w[((int64_t)t * ntiles + (nt0 + i)) * 64 + lane];
         if constexpr (MODE != kPerChannel)
           sgreg[i] = (int)p.s_g[(int64_t)t * N + (int64_t)(nt0 + i) * 16 + nl];
       }

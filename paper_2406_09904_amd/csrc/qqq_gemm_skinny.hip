@@ -1,13 +1,13 @@
 // Skinny (decode) W4A8 GEMM for M <= 64: HBM-bound streaming of the packed int4 weights.
 //
-// Work is the flat list of (channel group, k-step) units in the order the packed weights lie in
-// memory; every workgroup takes one contiguous range of it (so every CU streams the same number
-// of bytes whatever N and K are), its four waves interleave over the k-steps of the range, and
-// partial int32 tiles are summed across waves in LDS.  A range that covers a channel group's
-// whole K writes the result directly; otherwise partials meet in an int32 workspace through
-// device-scope atomics and the workgroup that completes a channel group runs the epilogue and
-// returns the workspace to zero.  Integer sums are exact in any order, so the result does not
-// depend on the split.
+// A workgroup of W waves owns one channel group (16*NT output channels) and one of S slices of
+// K; its waves interleave over the slice's k-steps and their partial int32 tiles are summed in
+// LDS.  With S == 1 the workgroup writes the result directly; otherwise partials meet in an int32
+// workspace through device-scope atomics and the workgroup that arrives last at a channel group
+// runs the epilogue and returns the workspace to zero.  Integer sums are exact in any order, so
+// the result does not depend on the split.  Each wave keeps two batches of U k-steps of 128-bit
+// loads in flight (the next batch is issued before the current one is consumed), which is what
+// keeps enough bytes in flight to stream HBM from short launches.
 //
 // Per k-step (128 k) a lane loads 16 B of packed codes per 16-channel tile, converts them in
 // registers to two int8 MFMA operands (Sec. 3.3.1 FastINT4toINT8, or Sec. 3.3.2's group-scale
@@ -17,182 +17,264 @@
 
 namespace qqq {
 
-template <int MODE, int NT, int MT>
-__global__ __launch_bounds__(256) void gemm_skinny_kernel(const GemmParams p, const int64_t units) {
+template <int NT, int MT, int U>
+struct Batch {
+  uint4 w[U][NT];
+  v4i a[U][MT][2];
+  int sg[U][NT];
+};
+
+template <int MODE, int NT, int MT, int U>
+__device__ __forceinline__ void load_batch(Batch<NT, MT, U>& b, const GemmParams& p,
+                                           const uint4* wbase, int tb, int tstride, int t1, int ng,
+                                           int nl, int kc) {
+  const int ntiles = p.N >> 4;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int t = tb + tstride * u;
+    const bool live = t < t1;
+#pragma unroll
+    for (int i = 0; i < NT; ++i) {
+      b.w[u][i] = make_uint4(0, 0, 0, 0);
+      b.sg[u][i] = 0;
+      if (live) {
+        b.w[u][i] = wbase[((int64_t)t * ntiles + i) * 64];
+        if constexpr (MODE != kPerChannel)
+          b.sg[u][i] = (int)p.s_g[(int64_t)t * p.N + (int64_t)(ng * NT + i) * 16 + nl];
+      }
+    }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int m = mt * 16 + nl;
+      b.a[u][mt][0] = (v4i){0, 0, 0, 0};
+      b.a[u][mt][1] = (v4i){0, 0, 0, 0};
+      if (live && m < p.M) {
+        const v4i* ap = (const v4i*)(p.a_q + (int64_t)m * p.K + (int64_t)t * 128 + kc * 16);
+        b.a[u][mt][0] = ap[0];
+        b.a[u][mt][1] = ap[4];  // +64 bytes: second MFMA step of this k-step
+      }
+    }
+  }
+}
+
+template <int MODE, int NT, int MT, int U>
+__device__ __forceinline__ void consume_batch(const Batch<NT, MT, U>& b, v4i (&acc)[MT][NT], int tb,
+                                              int tstride, int t1) {
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    if (tb + tstride * u >= t1) break;
+#pragma unroll
+    for (int i = 0; i < NT; ++i) {
+      const uint32_t d[4] = {b.w[u][i].x, b.w[u][i].y, b.w[u][i].z, b.w[u][i].w};
+      int o[8];
+      if constexpr (MODE == kPerChannel || MODE == kGroupLinear) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) unpack_x16(d[j], o[2 * j], o[2 * j + 1]);
+      } else if constexpr (MODE == kGroupClamp) {
+        const _Float16 hs = (_Float16)(float)b.sg[u][i];
+        const h2 s2 = {hs, hs};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) unpack_group_clamp(d[j], s2, o[2 * j], o[2 * j + 1]);
+      } else {
+        const GroupFusedConsts g = make_group_fused(b.sg[u][i]);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) unpack_group_fused(d[j], g, o[2 * j], o[2 * j + 1]);
+      }
+      const v4i b0 = {o[0], o[1], o[2], o[3]}, b1 = {o[4], o[5], o[6], o[7]};
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        if constexpr (MODE == kGroupLinear) {
+          // the group's partial sum of A*16*code, then (partial/16)*s_g: the same integer as
+          // summing A*(code*s_g) because no product saturates when s_g <= 16
+          v4i part =
+              __builtin_amdgcn_mfma_i32_16x16x64_i8(b.a[u][mt][0], b0, (v4i){0, 0, 0, 0}, 0, 0, 0);
+          part = __builtin_amdgcn_mfma_i32_16x16x64_i8(b.a[u][mt][1], b1, part, 0, 0, 0);
+#pragma unroll
+          for (int r = 0; r < 4; ++r) acc[mt][i][r] += (part[r] >> 4) * b.sg[u][i];
+        } else {
+          acc[mt][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(b.a[u][mt][0], b0, acc[mt][i], 0, 0, 0);
+          acc[mt][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(b.a[u][mt][1], b1, acc[mt][i], 0, 0, 0);
+        }
+      }
+    }
+  }
+}
+
+template <int MODE, int NT, int MT, int W, int U>
+__global__ __launch_bounds__(W * 64) void gemm_skinny_kernel(const GemmParams p, const int NG,
+                                                             const int S) {
   constexpr int kTiles = MT * NT;
-  __shared__ int red[4 * kTiles * 256];
+  constexpr int kElems = kTiles * 256;          // int32 outputs of the workgroup
+  constexpr int kThreads = W * 64;
+  constexpr int kPer = (kElems + kThreads - 1) / kThreads;  // outputs per thread after the reduction
+  __shared__ int red[W * kElems];
   __shared__ int s_last;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int nl = lane & 15, kc = lane >> 4;
   const int T = p.T, N = p.N, M = p.M;
-  const int64_t K = p.K;
 
-  const int64_t u0 = (int64_t)blockIdx.x * units / gridDim.x;
-  const int64_t u1 = (int64_t)(blockIdx.x + 1) * units / gridDim.x;
+  // consecutive workgroups take consecutive channel groups of the same K slice, so the
+  // workgroups that run together sweep one contiguous window of the packed weights
+  const int ng = blockIdx.x % NG, ks = blockIdx.x / NG;
+  const int t0 = ks * T / S, t1 = (ks + 1) * T / S;  // ks < S <= T <= 1024: no overflow
 
-  for (int64_t u = u0; u < u1;) {
-    const int ng = (int)(u / T);
-    const int tb = (int)(u - (int64_t)ng * T);
-    const int te = (int)((u1 - u < (int64_t)(T - tb)) ? (tb + (u1 - u)) : T);
-
-    v4i acc[MT][NT];
+  // this thread's output elements after the cross-wave sum: element e of [tile][r][lane]
+  int row[kPer], col[kPer];
+  float sa[kPer], sw[kPer];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-      for (int i = 0; i < NT; ++i) acc[mt][i] = (v4i){0, 0, 0, 0};
-
-    const uint4* wbase = p.w + ((int64_t)ng * NT * T) * 64 + lane;
-    for (int t = tb + wave; t < te; t += 4) {
-      uint4 wv[NT];
-#pragma unroll
-      for (int i = 0; i < NT; ++i) wv[i] = wbase[((int64_t)i * T + t) * 64];
-      v4i a[MT][2];
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        const int m = mt * 16 + nl;
-        a[mt][0] = (v4i){0, 0, 0, 0};
-        a[mt][1] = (v4i){0, 0, 0, 0};
-        if (m < M) {
-          const v4i* ap = (const v4i*)(p.a_q + (int64_t)m * K + (int64_t)t * 128 + kc * 16);
-          a[mt][0] = ap[0];
-          a[mt][1] = ap[4];  // +64 bytes: second MFMA step of this k-step
-        }
-      }
-      int sg[NT];
-      if constexpr (MODE != kPerChannel) {
-#pragma unroll
-        for (int i = 0; i < NT; ++i)
-          sg[i] = (int)p.s_g[(int64_t)t * N + (int64_t)(ng * NT + i) * 16 + nl];
-      }
-#pragma unroll
-      for (int i = 0; i < NT; ++i) {
-        v4i b0, b1;
-        const uint32_t d[4] = {wv[i].x, wv[i].y, wv[i].z, wv[i].w};
-        int o[8];
-        if constexpr (MODE == kPerChannel || MODE == kGroupLinear) {
-#pragma unroll
-          for (int j = 0; j < 4; ++j) unpack_x16(d[j], o[2 * j], o[2 * j + 1]);
-        } else if constexpr (MODE == kGroupClamp) {
-          const _Float16 hs = (_Float16)(float)sg[i];
-          const h2 s2 = {hs, hs};
-#pragma unroll
-          for (int j = 0; j < 4; ++j) unpack_group_clamp(d[j], s2, o[2 * j], o[2 * j + 1]);
-        } else {
-          const GroupFusedConsts g = make_group_fused(sg[i]);
-#pragma unroll
-          for (int j = 0; j < 4; ++j) unpack_group_fused(d[j], g, o[2 * j], o[2 * j + 1]);
-        }
-        b0 = (v4i){o[0], o[1], o[2], o[3]};
-        b1 = (v4i){o[4], o[5], o[6], o[7]};
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          if constexpr (MODE == kGroupLinear) {
-            // the group's partial sum of A*16*code, then (partial/16)*s_g: the same integer as
-            // summing A*(code*s_g) because no product saturates when s_g <= 16
-            v4i part = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[mt][0], b0, (v4i){0, 0, 0, 0}, 0, 0, 0);
-            part = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[mt][1], b1, part, 0, 0, 0);
-#pragma unroll
-            for (int r = 0; r < 4; ++r) acc[mt][i][r] += (part[r] >> 4) * sg[i];
-          } else {
-            acc[mt][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[mt][0], b0, acc[mt][i], 0, 0, 0);
-            acc[mt][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[mt][1], b1, acc[mt][i], 0, 0, 0);
-          }
-        }
-      }
+  for (int j = 0; j < kPer; ++j) {
+    const int e = tid + kThreads * j;
+    const int le = e & 63, r = (e >> 6) & 3, tile = e >> 8;
+    const int i = tile % NT, mt = tile / NT;
+    col[j] = (ng * NT + i) * 16 + (le & 15);
+    row[j] = (e < kElems) ? mt * 16 + 4 * (le >> 4) + r : M;  // M = "no output"
+    sa[j] = 0.0f;
+    sw[j] = 0.0f;
+    if (row[j] < M) {  // scales fetched now so the epilogue does not wait on memory
+      sa[j] = p.s_a[row[j]];
+      sw[j] = (float)p.s_w[col[j]];
     }
+  }
 
-    // ---- sum the four waves' tiles in LDS: red[wave][tile][r][lane]
+  v4i acc[MT][NT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+  for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-      for (int i = 0; i < NT; ++i)
+    for (int i = 0; i < NT; ++i) acc[mt][i] = (v4i){0, 0, 0, 0};
+
+  {
+    const uint4* wbase = p.w + (int64_t)ng * NT * 64 + lane;
+    constexpr int kStep = W * U;  // k-steps between consecutive batches of one wave
+    Batch<NT, MT, U> b0, b1;
+    int tb = t0 + wave;
+    load_batch<MODE>(b0, p, wbase, tb, W, t1, ng, nl, kc);
+    while (tb < t1) {
+      load_batch<MODE>(b1, p, wbase, tb + kStep, W, t1, ng, nl, kc);
+      consume_batch<MODE>(b0, acc, tb, W, t1);
+      tb += kStep;
+      if (tb >= t1) break;
+      load_batch<MODE>(b0, p, wbase, tb + kStep, W, t1, ng, nl, kc);
+      consume_batch<MODE>(b1, acc, tb, W, t1);
+      tb += kStep;
+    }
+  }
+
+  // ---- sum the waves' tiles in LDS: red[wave][tile][r][lane]
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-          red[((wave * kTiles + mt * NT + i) * 4 + r) * 64 + lane] = acc[mt][i][r];
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int i = 0; i < NT; ++i)
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        red[wave * kElems + ((mt * NT + i) * 4 + r) * 64 + lane] = acc[mt][i][r];
+  __syncthreads();
+  int val[kPer];
+#pragma unroll
+  for (int j = 0; j < kPer; ++j) {
+    const int e = tid + kThreads * j;
+    int v = 0;
+    if (e < kElems) {
+#pragma unroll
+      for (int w = 0; w < W; ++w) v += red[w * kElems + e];
+    }
+    val[j] = v;
+  }
+
+  if (S > 1) {
+#pragma unroll
+    for (int j = 0; j < kPer; ++j)
+      if (row[j] < M && val[j] != 0) atomicAdd(&p.ws_acc[(int64_t)row[j] * N + col[j]], val[j]);
+    // Partial sums travel only through device-scope atomics, so the arrival counter below needs
+    // just "my atomics have been performed" (vmcnt(0)), not a cache write-back/invalidate fence.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-
-    const bool full = (tb == 0 && te == T);
-    int val[kTiles], row[kTiles], col[kTiles];
+    if (tid == 0) s_last = (atomicAdd(&p.ws_cnt[ng], 1) == S - 1);
+    __syncthreads();
+    if (s_last == 0) return;
 #pragma unroll
-    for (int j = 0; j < kTiles; ++j) {
-      const int e = tid + 256 * j;  // element of [tile][r][lane]
-      val[j] = red[e] + red[e + kTiles * 256] + red[e + 2 * kTiles * 256] + red[e + 3 * kTiles * 256];
-      const int le = e & 63, r = (e >> 6) & 3, tile = e >> 8;
-      const int i = tile % NT, mt = tile / NT;
-      col[j] = (ng * NT + i) * 16 + (le & 15);
-      row[j] = mt * 16 + 4 * (le >> 4) + r;
+    for (int j = 0; j < kPer; ++j)
+      if (row[j] < M) val[j] = atomicExch(&p.ws_acc[(int64_t)row[j] * N + col[j]], 0);
+    if (tid == 0) atomicExch(&p.ws_cnt[ng], 0);
+  }
+#pragma unroll
+  for (int j = 0; j < kPer; ++j) {
+    if (row[j] < M) {
+      int v = val[j];
+      if constexpr (MODE == kPerChannel) v >>= 4;  // exact: the sum is a multiple of 16
+      const int64_t o = (int64_t)row[j] * N + col[j];
+      p.y[o] = dequant(v, sa[j], sw[j]);
+      if (p.acc_out) p.acc_out[o] = v;
     }
-
-    bool finish = full;
-    if (!full) {
-#pragma unroll
-      for (int j = 0; j < kTiles; ++j)
-        if (row[j] < M && val[j] != 0) atomicAdd(&p.ws_acc[(int64_t)row[j] * N + col[j]], val[j]);
-      __threadfence();
-      __syncthreads();
-      if (tid == 0) {
-        const int done = atomicAdd(&p.ws_cnt[ng], te - tb) + (te - tb);
-        s_last = (done == T);
-      }
-      __syncthreads();
-      finish = (s_last != 0);
-      if (finish) {
-        __threadfence();
-#pragma unroll
-        for (int j = 0; j < kTiles; ++j)
-          if (row[j] < M) val[j] = atomicExch(&p.ws_acc[(int64_t)row[j] * N + col[j]], 0);
-        if (tid == 0) atomicExch(&p.ws_cnt[ng], 0);
-      }
-    }
-    if (finish) {
-#pragma unroll
-      for (int j = 0; j < kTiles; ++j) {
-        if (row[j] < M) {
-          int v = val[j];
-          if constexpr (MODE == kPerChannel) v >>= 4;  // exact: the sum is a multiple of 16
-          const int64_t o = (int64_t)row[j] * N + col[j];
-          p.y[o] = dequant(v, p.s_a[row[j]], (float)p.s_w[col[j]]);
-          if (p.acc_out) p.acc_out[o] = v;
-        }
-      }
-    }
-    __syncthreads();  // red[] and s_last are reused by the next range
-    u += te - tb;
   }
 }
 
-template <int MODE, int NT, int MT>
-static int launch_one(const GemmParams& p, int blocks_per_cu, hipStream_t st) {
-  const int64_t units = (int64_t)(p.N / (16 * NT)) * p.T;
-  int64_t grid = (int64_t)num_cus() * blocks_per_cu;
-  if (grid > units) grid = units;
-  if (grid < 1) grid = 1;
-  hipLaunchKernelGGL((gemm_skinny_kernel<MODE, NT, MT>), dim3((unsigned)grid), dim3(256), 0, st, p,
-                     units);
+static int g_tune_nt = 0, g_tune_s = 0, g_tune_w = 0;
+void set_skinny_tuning(int nt, int s, int w) {
+  g_tune_nt = nt;
+  g_tune_s = s;
+  g_tune_w = w;
+}
+
+template <int MODE, int NT, int MT, int W, int U>
+static int launch_one(const GemmParams& p, int S, hipStream_t st) {
+  const int NG = p.N / (16 * NT);
+  const int64_t grid = (int64_t)NG * S;
+  hipLaunchKernelGGL((gemm_skinny_kernel<MODE, NT, MT, W, U>), dim3((unsigned)grid), dim3(W * 64), 0,
+                     st, p, NG, S);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return set_error(QQQ_ERR_HIP, "skinny gemm launch: %s", hipGetErrorString(e));
   return QQQ_OK;
 }
 
+template <int MODE, int NT, int MT, int U>
+static int launch_w(const GemmParams& p, int W, int S, hipStream_t st) {
+  if constexpr (NT * MT <= 2) {  // 16 waves x 4 tiles of partial sums would not fit in LDS
+    if (W >= 16) return launch_one<MODE, NT, MT, 16, U>(p, S, st);
+  }
+  if (W >= 8) return launch_one<MODE, NT, MT, 8, U>(p, S, st);
+  return launch_one<MODE, NT, MT, 4, U>(p, S, st);
+}
+
+// Shape of the launch: channel tiles per workgroup (nt), waves per workgroup (w), K slices (s).
+static void choose_split(const GemmParams& p, int mt, int& nt, int& w, int& s) {
+  nt = 1;
+  if (mt == 1) nt = (p.N % 64 == 0) ? 4 : (p.N % 32 == 0) ? 2 : 1;
+  if (mt == 2) nt = (p.N % 32 == 0) ? 2 : 1;
+  const int cus = num_cus();
+  // Measured on MI355X: the widest channel group that still leaves about two workgroups for
+  // every three CUs streams best, with 8 waves per workgroup and no K split (no atomics).
+  while (nt > 1 && (int64_t)(p.N / (16 * nt)) * 3 < 2 * cus) nt >>= 1;
+  w = (p.T >= 16) ? 8 : 4;
+  s = 1;
+  // Very narrow outputs: too few channel groups to occupy the chip, so slice K as well
+  const int ng = p.N / (16 * nt);
+  if (ng * 2 < cus) {
+    s = (cus + ng - 1) / ng;
+    const int max_s = p.T / (2 * w) > 0 ? p.T / (2 * w) : 1;
+    if (s > max_s) s = max_s;
+  }
+}
+
 template <int MODE>
 static int launch_mode(const GemmParams& p, hipStream_t st) {
   const int mt = (p.M + 15) / 16;
-  // channel tiles per unit: wider units reuse each activation fragment more, but need enough
-  // units to give every workgroup several k-steps per wave
-  const int64_t units1 = (int64_t)(p.N / 16) * p.T;
-  const int64_t want = (int64_t)num_cus() * 4 * 8;
+  int nt, w, S;
+  choose_split(p, mt, nt, w, S);
+  if (g_tune_nt > 0 && mt * g_tune_nt <= 4 && p.N % (16 * g_tune_nt) == 0) nt = g_tune_nt;
+  if (g_tune_s > 0 && g_tune_s <= p.T) S = g_tune_s;
+  if (g_tune_w > 0) w = g_tune_w;
   if (mt <= 1) {
-    if (p.N % 64 == 0 && units1 / 4 >= want) return launch_one<MODE, 4, 1>(p, 4, st);
-    if (p.N % 32 == 0 && units1 / 2 >= want) return launch_one<MODE, 2, 1>(p, 4, st);
-    return launch_one<MODE, 1, 1>(p, 4, st);
+    if (nt == 4) return launch_w<MODE, 4, 1, 1>(p, w, S, st);
+    if (nt == 2) return launch_w<MODE, 2, 1, 2>(p, w, S, st);
+    return launch_w<MODE, 1, 1, 4>(p, w, S, st);
   }
   if (mt == 2) {
-    if (p.N % 32 == 0 && units1 / 2 >= want) return launch_one<MODE, 2, 2>(p, 4, st);
-    return launch_one<MODE, 1, 2>(p, 4, st);
+    if (nt >= 2) return launch_w<MODE, 2, 2, 1>(p, w, S, st);
+    return launch_w<MODE, 1, 2, 2>(p, w, S, st);
   }
-  return launch_one<MODE, 1, 4>(p, 4, st);
+  return launch_w<MODE, 1, 4, 1>(p, w, S, st);
 }
 
 int launch_gemm_skinny(const GemmParams& p, int mode, hipStream_t st) {

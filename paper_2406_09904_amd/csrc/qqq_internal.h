@@ -24,7 +24,7 @@ enum Mode : int {
 struct GemmParams {
   const int8_t* a_q;    // [M,K]
   const float* s_a;     // [M]
-  const uint4* w;       // packed int4, 1 KiB chunks [N/16][K/128][64 lanes]
+  const uint4* w;       // packed int4, 1 KiB chunks [K/128][N/16][64 lanes]
   const int8_t* s_g;    // [K/128,N] or nullptr
   const _Float16* s_w;  // [N]
   _Float16* y;          // [M,N]
@@ -45,12 +45,14 @@ int launch_pack(const uint32_t* w_nat, int64_t N, int64_t K, uint32_t* w_packed,
                 hipStream_t st);
 int launch_gemm_skinny(const GemmParams& p, int mode, hipStream_t st);
 int launch_gemm_prefill(const GemmParams& p, int mode, hipStream_t st);
+void set_skinny_tuning(int nt, int s, int w);
 
 constexpr int kSkinnyMaxM = 64;  // rows the split-K kernel handles (4 MFMA row tiles)
 
 // ---------------------------------------------------------------------------------------------
 // Packed layout.  Chunk (nt, t) = output channels [16nt,16nt+16) x k in [128t,128t+128), 1 KiB at
-// ((nt*T)+t)*1024.  Lane l = nl + 16*kc (nl = n%16, kc = 0..3) owns 16 bytes = dwords d0..d3.
+// (t*(N/16)+nt)*1024 (k-step major: all channels of one k-step are contiguous).
+// Lane l = nl + 16*kc (nl = n%16, kc = 0..3) owns 16 bytes = dwords d0..d3.
 // Nibble q of dword i holds the code of k = 128t + 64*(i/2) + 16*kc + 8*(i%2) + 4*(q%2) + q/2,
 // i.e. each packed dword is natural word (k/8) with its nibbles reordered 0,4,1,5,2,6,3,7 so that
 // "even nibbles" and "odd nibbles" each come out as four k-consecutive bytes.

@@ -24,17 +24,17 @@ __device__ __forceinline__ uint32_t shuffle_nibbles_inv(uint32_t w) {
   return out;
 }
 
-// One thread per 32-bit word.  Packed word index = (((nt*T + t)*64 + lane)*4 + i).
+// One thread per 32-bit word.  Packed word index = (((t*(N/16) + nt)*64 + lane)*4 + i).
 __global__ __launch_bounds__(256) void pack_kernel(const uint32_t* __restrict__ src,
-                                                   uint32_t* __restrict__ dst, int64_t total, int T,
+                                                   uint32_t* __restrict__ dst, int64_t total, int ntiles,
                                                    int words_per_row, bool inverse) {
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= total) return;
   const int i = (int)(idx & 3);
   const int lane = (int)((idx >> 2) & 63);
-  const int64_t chunk = idx >> 8;
-  const int t = (int)(chunk % T);
-  const int64_t nt = chunk / T;
+  const int64_t chunk = idx >> 8;  // chunk = t * (N/16) + nt
+  const int64_t nt = chunk % ntiles;
+  const int t = (int)(chunk / ntiles);
   const int nl = lane & 15, kc = lane >> 4;
   const int64_t n = nt * 16 + nl;
   // k of nibble 0 of this word = 128t + 64*(i/2) + 16kc + 8*(i%2): always a multiple of 8
@@ -52,7 +52,7 @@ int launch_pack(const uint32_t* src, int64_t N, int64_t K, uint32_t* dst, bool i
   const int64_t blocks = (total + 255) / 256;
   if (blocks > 0x7FFFFFFF) return set_error(QQQ_ERR_SHAPE, "pack: too many words");
   hipLaunchKernelGGL(pack_kernel, dim3((unsigned)blocks), dim3(256), 0, st, src, dst, total,
-                     (int)(K / 128), (int)(K / 8), inverse);
+                     (int)(N / 16), (int)(K / 8), inverse);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return set_error(QQQ_ERR_HIP, "pack launch: %s", hipGetErrorString(e));
   return QQQ_OK;
