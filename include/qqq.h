@@ -122,6 +122,12 @@ int qqq_set_group_mode_override(int mode);
  */
 int qqq_set_skinny_tuning(int channel_tiles, int k_slices, int waves);
 
+/*
+ * Tuning/diagnostic knob (host state, not thread-safe) for the prefill kernel: waves per workgroup
+ * (4 or 8; the workgroup tile is 128 x 64*waves); 0 = automatic.  Returns 0.
+ */
+int qqq_set_prefill_tuning(int waves);
+
 #ifdef __cplusplus
 }
 #endif

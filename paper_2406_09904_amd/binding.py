@@ -18,7 +18,7 @@ GROUP = 128
 SYMBOLS = [
     "qqq_version", "qqq_last_error", "qqq_quant_act", "qqq_packed_w4_bytes", "qqq_pack_w4",
     "qqq_unpack_w4", "qqq_gemm_workspace_bytes", "qqq_gemm_w4a8_perchannel",
-    "qqq_gemm_w4a8_pergroup", "qqq_set_kernel_override", "qqq_set_group_mode_override", "qqq_set_skinny_tuning",
+    "qqq_gemm_w4a8_pergroup", "qqq_set_kernel_override", "qqq_set_group_mode_override", "qqq_set_skinny_tuning", "qqq_set_prefill_tuning",
 ]
 
 _lib = None
@@ -55,6 +55,7 @@ def lib():
         L.qqq_set_kernel_override.argtypes = [ci]
         L.qqq_set_group_mode_override.argtypes = [ci]
         L.qqq_set_skinny_tuning.argtypes = [ci, ci, ci]
+        L.qqq_set_prefill_tuning.argtypes = [ci]
         _lib = L
     return _lib
 
@@ -164,3 +165,7 @@ def set_group_mode_override(mode: int) -> int:
 
 def set_skinny_tuning(channel_tiles: int, k_slices: int, waves: int = 0) -> int:
     return lib().qqq_set_skinny_tuning(channel_tiles, k_slices, waves)
+
+
+def set_prefill_tuning(waves: int) -> int:
+    return lib().qqq_set_prefill_tuning(waves)

@@ -122,6 +122,11 @@ int qqq_set_skinny_tuning(int channel_tiles, int k_slices, int waves) {
   return 0;
 }
 
+int qqq_set_prefill_tuning(int waves) {
+  set_prefill_tuning(waves);
+  return 0;
+}
+
 size_t qqq_packed_w4_bytes(int64_t N, int64_t K) {
   if (N < 16 || N % 16 != 0 || K < 128 || K % 128 != 0 || K > 131072 || N > 0x7FFFFFF0) return 0;
   return (size_t)N * (size_t)K / 2;

@@ -46,6 +46,7 @@ int launch_pack(const uint32_t* w_nat, int64_t N, int64_t K, uint32_t* w_packed,
 int launch_gemm_skinny(const GemmParams& p, int mode, hipStream_t st);
 int launch_gemm_prefill(const GemmParams& p, int mode, hipStream_t st);
 void set_skinny_tuning(int nt, int s, int w);
+void set_prefill_tuning(int waves);
 
 constexpr int kSkinnyMaxM = 64;  // rows the split-K kernel handles (4 MFMA row tiles)
 
