@@ -123,8 +123,9 @@ int qqq_set_group_mode_override(int mode);
 int qqq_set_skinny_tuning(int channel_tiles, int k_slices, int waves);
 
 /*
- * Tuning/diagnostic knob (host state, not thread-safe) for the prefill kernel: waves per workgroup
- * (4 or 8; the workgroup tile is 128 x 64*waves); 0 = automatic.  Returns 0.
+ * Tuning/diagnostic knob (host state, not thread-safe) for the prefill path: 0 = the default kernel
+ * (128 x 512 tile, LDS ring fed by global->LDS DMA); 4 or 8 = the register-staged kernel with that
+ * many waves per workgroup (128 x 64*waves tile).  Returns 0.
  */
 int qqq_set_prefill_tuning(int waves);
 

@@ -1,0 +1,268 @@
+// Prefill W4A8 GEMM, main kernel: 128 x 512 workgroup tile, 8 waves, three-stage LDS ring fed by
+// global->LDS DMA loads (global_load_lds_dwordx4), v_mfma_i32_32x32x32_i8 main loop.
+//
+// Why this shape on gfx950.  The int8 MFMA pipe retires a 32x32x32 tile in 32 clocks, so one k-step
+// (128 k) of a wave's 128 x 64 tile is 1024 clocks of MFMA; a global load that misses L2 takes
+// several times that.  Registers cannot hold that much prefetch next to 128 accumulator registers,
+// but the 160 KiB LDS can: every wave issues the DMA loads for k-step t+2 before it computes k-step
+// t, the loads need no registers, and the only wait is "my DMA of k-step t+1 has landed"
+// (s_waitcnt vmcnt(6): six DMA loads per wave per k-step, seven with group scales) right before the workgroup barrier.
+//
+// LDS stage (50 KiB): activations 128 rows x 128 B with the 16-byte slots of row r XOR-swizzled by
+// r%8 (DMA writes lane-linear, so the swizzle is applied on the global side: lane l fetches slot
+// l%8 ^ row%8), then each wave's own 4 KiB of packed int4 codes exactly as they lie in memory,
+// then (per-group variant) each wave's 64 group scales of the k-step.
+// Weights never cross waves: the waves split N, each converts its codes to int8 once per k-step
+// (Sec. 3.3.1 / 3.3.2 of the QQQ paper) and feeds 4 MFMAs per converted fragment.
+#include "qqq_internal.h"
+
+namespace qqq {
+
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+constexpr int kDBM = 128, kDBK = 128, kDNW = 8, kDBN = kDNW * 64, kDStages = 3;
+constexpr int kDAStage = kDBM * kDBK;        // 16 KiB of activations
+constexpr int kDWStage = kDBN * kDBK / 2;    // 32 KiB of packed codes
+constexpr int kDSgStage = kDNW * 256;          // 256 B of group scales per wave (64 used)
+constexpr int kDStage = kDAStage + kDWStage + kDSgStage;
+
+template <int MODE>
+__device__ __forceinline__ v4i convert_b(uint32_t d0, uint32_t d1, int sg) {
+  int o[4];
+  if constexpr (MODE == kPerChannel) {
+    unpack_x16(d0, o[0], o[1]);
+    unpack_x16(d1, o[2], o[3]);
+  } else if constexpr (MODE == kGroupClamp) {
+    const _Float16 hs = (_Float16)(float)sg;
+    const h2 s2 = {hs, hs};
+    unpack_group_clamp(d0, s2, o[0], o[1]);
+    unpack_group_clamp(d1, s2, o[2], o[3]);
+  } else {
+    const GroupFusedConsts g = make_group_fused(sg);
+    unpack_group_fused(d0, g, o[0], o[1]);
+    unpack_group_fused(d1, g, o[2], o[3]);
+  }
+  return (v4i){o[0], o[1], o[2], o[3]};
+}
+
+template <int MODE>
+__global__ __launch_bounds__(kDNW * 64, 1) void gemm_prefill_dma_kernel(const GemmParams p,
+                                                                       const int tiles_m,
+                                                                       const int tiles_n) {
+  __shared__ __attribute__((aligned(1024))) int8_t lds[kDStages * kDStage];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int n32 = lane & 31, h = lane >> 5;
+  const int T = p.T, N = p.N, M = p.M;
+  const int64_t K = p.K;
+  const int ntiles = N >> 4;
+
+  // XCD-aware order: consecutive workgroup ids land on different XCDs (8 of them), so each XCD
+  // gets a contiguous run of tiles; within a run tiles are walked in groups of 8 row tiles, m
+  // fastest, so the workgroups resident on one XCD form a compact patch of Y and share their
+  // activation and weight tiles through that XCD's L2.
+  constexpr int kGroupM = 8;
+  const int nblk = tiles_m * tiles_n;
+  int pid = blockIdx.x;
+  {
+    const int per = nblk / 8;
+    if (per > 0 && pid < per * 8) pid = (pid % 8) * per + pid / 8;
+  }
+  const int width = kGroupM * tiles_n;
+  const int first_m = (pid / width) * kGroupM;
+  const int gsize = (tiles_m - first_m < kGroupM) ? tiles_m - first_m : kGroupM;
+  const int tm = first_m + (pid % width) % gsize, tn = (pid % width) / gsize;
+  const int m0 = tm * kDBM;
+
+  // ---- DMA sources.  Activations: this wave copies rows 16*wave .. +15 (two 1 KiB pieces of 8
+  // rows); lane l lands in slot l%8 of row l/8, so it fetches chunk (l%8) ^ (row%8).  Rows past M
+  // re-read row M-1 (never stored).  Weights: this wave's four 1 KiB chunks, copied verbatim;
+  // chunks past N/16 re-read the last valid chunk (never stored).
+  const int8_t* a_src[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int r = 16 * wave + 8 * i + (lane >> 3);
+    int m = m0 + r;
+    if (m > M - 1) m = M - 1;
+    a_src[i] = p.a_q + (int64_t)m * K + (((lane & 7) ^ (r & 7)) << 4);
+  }
+  const int8_t* w_src[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    int nt = tn * (kDBN / 16) + wave * 4 + j;
+    if (nt > ntiles - 1) nt = ntiles - 1;
+    w_src[j] = (const int8_t*)p.w + (int64_t)nt * 1024 + lane * 16;
+  }
+  const int64_t w_step = (int64_t)ntiles * 1024;  // bytes between k-steps of the packed weights
+  // group scales of the wave's 64 channels: lanes 0..15 fetch 4 bytes each, the other lanes (and
+  // channels past N) re-read the last valid dword; each lane writes its own LDS dword
+  const int8_t* sg_src = nullptr;
+  if constexpr (MODE != kPerChannel) {
+    int c0 = tn * kDBN + wave * 64 + 4 * (lane < 16 ? lane : 15);
+    if (c0 > N - 4) c0 = N - 4;
+    sg_src = p.s_g + c0;
+  }
+
+  // The DMA loads are issued through inline assembly so that the compiler's wait-count pass does
+  // not know they write LDS (it would otherwise drain every outstanding load before the first LDS
+  // read of each k-step); the waits are placed by hand below.  M0 carries the wave-uniform LDS
+  // destination; lane l writes its 16 (or 4) bytes at M0 + 16*l (4*l).
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_ptr_t)lds;
+  auto dma16 = [&](const int8_t* src, uint32_t dst) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src)
+                 : "memory");
+  };
+  auto dma4 = [&](const int8_t* src, uint32_t dst) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(dst), "v"(src)
+                 : "memory");
+  };
+  const uint32_t wave_u = (uint32_t)__builtin_amdgcn_readfirstlane(wave);
+  auto issue_dma = [&](int t, int stage) {
+    const uint32_t base = lds_base + (uint32_t)stage * kDStage;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) dma16(a_src[i] + (int64_t)t * kDBK, base + (2 * wave_u + i) * 1024);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      dma16(w_src[j] + (int64_t)t * w_step, base + kDAStage + wave_u * 4096 + j * 1024);
+    if constexpr (MODE != kPerChannel)
+      dma4(sg_src + (int64_t)t * N, base + kDAStage + kDWStage + wave_u * 256);
+  };
+
+  // ---- per-lane LDS read offsets.  A operand of MFMA step s: row 32*mt + n32, chunk 2s+h, stored
+  // in slot (2s+h) ^ (row%8).  W: tile c is chunks 2c and 2c+1; this lane's pieces are at
+  // (n32%16 + 16h)*16 and +512 of chunk 2c + n32/16.
+  int a_off[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) a_off[s] = n32 * 128 + (((2 * s + h) ^ (n32 & 7)) << 4);
+  const int w_off = kDAStage + wave * 4096 + (n32 >> 4) * 1024 + ((n32 & 15) + 16 * h) * 16;
+
+  // group scale of this lane's column in each of the wave's two 32-channel tiles
+  int col[2];
+  bool nvalid[2];
+#pragma unroll
+  for (int c = 0; c < 2; ++c) {
+    col[c] = tn * kDBN + wave * 64 + c * 32 + n32;
+    nvalid[c] = col[c] < N;
+  }
+  v16i acc[4][2];
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[mt][c][v] = 0;
+
+  // DMA loads per wave per k-step: 2 activation pieces + 4 weight chunks (+ 1 of group scales)
+  auto wait_all_but_newest_step = [&]() {
+    if constexpr (MODE == kPerChannel)
+      asm volatile("s_waitcnt vmcnt(6) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else
+      asm volatile("s_waitcnt vmcnt(7) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  };
+
+  // ---- prologue: k-steps 0 and 1 in flight, wait for step 0
+  issue_dma(0, 0);
+  if (T > 1) {
+    issue_dma(1, 1);
+    wait_all_but_newest_step();
+  } else {
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  }
+
+  int stage = 0;
+  for (int t = 0; t < T; ++t) {
+    // k-step t+2 goes into the stage that was read during k-step t-1 (everyone is past the
+    // barrier that ended it)
+    const bool more = t + 2 < T;
+    if (more) issue_dma(t + 2, stage == 0 ? 2 : stage - 1);
+
+    const int8_t* sbase = lds + stage * kDStage;
+    int sgcur[2] = {0, 0};
+    if constexpr (MODE != kPerChannel) {
+#pragma unroll
+      for (int c = 0; c < 2; ++c)
+        sgcur[c] = (int)sbase[kDAStage + kDWStage + wave * 256 + c * 32 + n32];
+    }
+    uint4 wcur[2][2];
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      wcur[c][0] = *(const uint4*)(sbase + w_off + c * 2048);
+      wcur[c][1] = *(const uint4*)(sbase + w_off + c * 2048 + 512);
+    }
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {  // MFMA k-steps of 32
+      v4i a[4];
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt) a[mt] = *(const v4i*)(sbase + a_off[s] + mt * 4096);
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        // MFMA step s uses piece s%2, dword pair s/2 of the lane's packed codes
+        const uint4 pc = wcur[c][s & 1];
+        const uint32_t d0 = (s >> 1) ? pc.z : pc.x, d1 = (s >> 1) ? pc.w : pc.y;
+        const v4i b = convert_b<MODE>(d0, d1, sgcur[c]);
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+          acc[mt][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[mt], b, acc[mt][c], 0, 0, 0);
+      }
+    }
+    // my DMA of k-step t+1 has landed (only the six loads of k-step t+2 may still be in flight),
+    // my LDS reads of this stage are done; then everyone's
+    if (more)
+      wait_all_but_newest_step();
+    else
+      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    stage = (stage == 2) ? 0 : stage + 1;
+  }
+
+  // ---- fused Dequant epilogue: lane holds column n32 of each tile; register v of a 32x32 tile is
+  // row 8*(v/4) + 4*h + v%4
+#pragma unroll
+  for (int c = 0; c < 2; ++c) {
+    if (!nvalid[c]) continue;
+    const int n = col[c];
+    const float sw = (float)p.s_w[n];
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int m = m0 + mt * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+        if (m < M) {
+          int x = acc[mt][c][v];
+          if constexpr (MODE == kPerChannel) x >>= 4;  // exact: the sum is a multiple of 16
+          const int64_t o = (int64_t)m * N + n;
+          p.y[o] = dequant(x, p.s_a[m], sw);
+          if (p.acc_out) p.acc_out[o] = x;
+        }
+      }
+    }
+  }
+}
+
+template <int MODE>
+static int launch_dma(const GemmParams& p, hipStream_t st) {
+  const int tiles_m = (p.M + kDBM - 1) / kDBM;
+  const int tiles_n = (p.N + kDBN - 1) / kDBN;
+  const int64_t grid = (int64_t)tiles_m * tiles_n;
+  if (grid > 0x7FFFFFFF) return set_error(QQQ_ERR_SHAPE, "prefill: grid too large");
+  hipLaunchKernelGGL((gemm_prefill_dma_kernel<MODE>), dim3((unsigned)grid), dim3(kDNW * 64), 0, st, p,
+                     tiles_m, tiles_n);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return set_error(QQQ_ERR_HIP, "prefill gemm launch: %s", hipGetErrorString(e));
+  return QQQ_OK;
+}
+
+int launch_gemm_prefill_dma(const GemmParams& p, int mode, hipStream_t st) {
+  switch (mode) {
+    case kPerChannel: return launch_dma<kPerChannel>(p, st);
+    case kGroupClamp: return launch_dma<kGroupClamp>(p, st);
+    // applying the group scale to partial sums costs more VALU work than the MFMAs hide once
+    // the tile has many rows, so both clamp-free requests use the per-weight fp16 FMA route here
+    case kGroupLinear:
+    case kGroupFused: return launch_dma<kGroupFused>(p, st);
+  }
+  return set_error(QQQ_ERR_SHAPE, "unknown mode %d", mode);
+}
+
+}  // namespace qqq
