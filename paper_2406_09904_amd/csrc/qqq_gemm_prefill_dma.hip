@@ -171,69 +171,135 @@ __global__ __launch_bounds__(kDNW * 64, 1) void gemm_prefill_dma_kernel(const Ge
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
   }
 
-  int stage = 0;
-  for (int t = 0; t < T; ++t) {
-    // k-step t+2 goes into the stage that was read during k-step t-1 (everyone is past the
-    // barrier that ended it)
-    const bool more = t + 2 < T;
-    if (more) issue_dma(t + 2, stage == 0 ? 2 : stage - 1);
-
-    const int8_t* sbase = lds + stage * kDStage;
-    int sgcur[2] = {0, 0};
-    if constexpr (MODE != kPerChannel) {
-#pragma unroll
-      for (int c = 0; c < 2; ++c)
-        sgcur[c] = (int)sbase[kDAStage + kDWStage + wave * 256 + c * 32 + n32];
-    }
-    uint4 wcur[2][2];
+  // ---- main loop, software-pipelined by hand.  The activation fragments of MFMA step s+1 are read
+  // from LDS while the MFMAs of step s run; the workgroup barrier sits before the LAST MFMA step of
+  // a k-step, so that the LDS reads of the next k-step (first activation fragments, the lane's
+  // packed codes, its group scales) are in flight behind 8 MFMAs instead of stalling the pipe.
+  struct WRegs {
+    uint4 w[2][2];  // [tile][piece]
+    int sg[2];
+  };
+  auto read_w = [&](WRegs& r, const int8_t* sb) {
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
-      wcur[c][0] = *(const uint4*)(sbase + w_off + c * 2048);
-      wcur[c][1] = *(const uint4*)(sbase + w_off + c * 2048 + 512);
+      r.w[c][0] = *(const uint4*)(sb + w_off + c * 2048);
+      r.w[c][1] = *(const uint4*)(sb + w_off + c * 2048 + 512);
+      r.sg[c] = 0;
+      if constexpr (MODE != kPerChannel)
+        r.sg[c] = (int)sb[kDAStage + kDWStage + wave * 256 + c * 32 + n32];
     }
+  };
+  auto read_a = [&](v4i (&a)[4], const int8_t* sb, int s) {
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {  // MFMA k-steps of 32
-      v4i a[4];
+    for (int mt = 0; mt < 4; ++mt) a[mt] = *(const v4i*)(sb + a_off[s] + mt * 4096);
+  };
+  auto mfma_step = [&](const v4i (&a)[4], const WRegs& r, int s) {
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt) a[mt] = *(const v4i*)(sbase + a_off[s] + mt * 4096);
+    for (int c = 0; c < 2; ++c) {
+      // MFMA step s uses piece s%2, dword pair s/2 of the lane's packed codes
+      const uint4 pc = r.w[c][s & 1];
+      const uint32_t d0 = (s >> 1) ? pc.z : pc.x, d1 = (s >> 1) ? pc.w : pc.y;
+      const v4i b = convert_b<MODE>(d0, d1, r.sg[c]);
 #pragma unroll
-      for (int c = 0; c < 2; ++c) {
-        // MFMA step s uses piece s%2, dword pair s/2 of the lane's packed codes
-        const uint4 pc = wcur[c][s & 1];
-        const uint32_t d0 = (s >> 1) ? pc.z : pc.x, d1 = (s >> 1) ? pc.w : pc.y;
-        const v4i b = convert_b<MODE>(d0, d1, sgcur[c]);
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
-          acc[mt][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[mt], b, acc[mt][c], 0, 0, 0);
-      }
+      for (int mt = 0; mt < 4; ++mt)
+        acc[mt][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[mt], b, acc[mt][c], 0, 0, 0);
     }
-    // my DMA of k-step t+1 has landed (only the six loads of k-step t+2 may still be in flight),
-    // my LDS reads of this stage are done; then everyone's
+  };
+
+  int stage = 0;
+  v4i a0[4], a1[4];
+  WRegs wr0, wr1;
+  read_w(wr0, lds);
+  read_a(a0, lds, 0);
+  auto kstep = [&](int t, const WRegs& wc, WRegs& wn) {
+    // k-step t+2 goes into the stage that was read during k-step t-1 (everyone is past the
+    // barrier inside it)
+    const bool more = t + 2 < T;
+    if (more) issue_dma(t + 2, stage == 0 ? 2 : stage - 1);
+    const int8_t* sb = lds + stage * kDStage;
+    read_a(a1, sb, 1);
+    mfma_step(a0, wc, 0);
+    read_a(a0, sb, 2);
+    mfma_step(a1, wc, 1);
+    read_a(a1, sb, 3);
+    mfma_step(a0, wc, 2);
+    // my DMA of k-step t+1 has landed (only the loads of k-step t+2 may still be in flight), my
+    // LDS reads of this stage are done; then everyone's
     if (more)
       wait_all_but_newest_step();
     else
       asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
     stage = (stage == 2) ? 0 : stage + 1;
+    if (t + 1 < T) {
+      const int8_t* nb = lds + stage * kDStage;
+      read_a(a0, nb, 0);
+      read_w(wn, nb);
+    }
+    mfma_step(a1, wc, 3);
+  };
+  for (int t = 0; t < T; t += 2) {
+    kstep(t, wr0, wr1);
+    if (t + 1 < T) kstep(t + 1, wr1, wr0);
   }
 
-  // ---- fused Dequant epilogue: lane holds column n32 of each tile; register v of a 32x32 tile is
-  // row 8*(v/4) + 4*h + v%4
+  // ---- fused Dequant epilogue.  Lane holds column n32 of each tile; register v of a 32x32 tile is
+  // row 8*(v/4) + 4*h + v%4.  The ring is free now (nothing reads it after the last barrier and
+  // every DMA has landed): each wave
+  // dequantises its 128 x 64 tile into its own fp16 LDS patch (row pitch 144 B so the two lane
+  // halves hit different banks) and streams it out as full 128-byte row segments.
+  constexpr int kEpRow = 144, kEpWave = kDBM * kEpRow;
+  static_assert(kDNW * kEpWave + kDBM * 4 <= kDStages * kDStage, "epilogue staging must fit the ring");
+  float* sa_lds = (float*)(lds + kDNW * kEpWave);
+  if (tid < kDBM) sa_lds[tid] = (m0 + tid < M) ? p.s_a[m0 + tid] : 0.0f;
+  float swv[2];
 #pragma unroll
-  for (int c = 0; c < 2; ++c) {
-    if (!nvalid[c]) continue;
-    const int n = col[c];
-    const float sw = (float)p.s_w[n];
+  for (int c = 0; c < 2; ++c) swv[c] = nvalid[c] ? (float)p.s_w[col[c]] : 0.0f;
+  __syncthreads();
+  int8_t* ep = lds + wave * kEpWave;
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt) {
+  for (int mt = 0; mt < 4; ++mt) {
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int m = m0 + mt * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
-        if (m < M) {
-          int x = acc[mt][c][v];
+    for (int q = 0; q < 4; ++q) {
+      const int r0 = mt * 32 + 8 * q + 4 * h;
+      const float4 sa4 = *(const float4*)(sa_lds + r0);
+      const float sav[4] = {sa4.x, sa4.y, sa4.z, sa4.w};
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          int x = acc[mt][c][4 * q + j];
           if constexpr (MODE == kPerChannel) x >>= 4;  // exact: the sum is a multiple of 16
-          const int64_t o = (int64_t)m * N + n;
-          p.y[o] = dequant(x, p.s_a[m], sw);
-          if (p.acc_out) p.acc_out[o] = x;
+          *(_Float16*)(ep + (r0 + j) * kEpRow + (c * 32 + n32) * 2) = dequant(x, sav[j], swv[c]);
+        }
+      }
+    }
+  }
+  // the patch is private to this wave and LDS serves one wave's accesses in order
+  {
+    const int cc = lane & 7;
+    const int ncol = tn * kDBN + wave * 64 + cc * 8;
+#pragma unroll
+    for (int it = 0; it < 16; ++it) {
+      const int row = it * 8 + (lane >> 3);
+      const v4i d = *(const v4i*)(ep + row * kEpRow + cc * 16);
+      const int m = m0 + row;
+      if (m < M && ncol < N) *(v4i*)(p.y + (int64_t)m * N + ncol) = d;
+    }
+  }
+  if (p.acc_out) {  // parity/debug output of the true accumulators: plain stores
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      if (!nvalid[c]) continue;
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int m = m0 + mt * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+          if (m < M) {
+            int x = acc[mt][c][v];
+            if constexpr (MODE == kPerChannel) x >>= 4;
+            p.acc_out[(int64_t)m * N + col[c]] = x;
+          }
         }
       }
     }
