@@ -162,85 +162,78 @@ __global__ __launch_bounds__(kDNW * 64, 1) void gemm_prefill_dma_kernel(const Ge
       asm volatile("s_waitcnt vmcnt(7) lgkmcnt(0)\n\ts_barrier" ::: "memory");
   };
 
-  // ---- prologue: k-steps 0 and 1 in flight, wait for step 0
+  // ---- prologue: k-steps 0 and 1 in flight, wait for step 0.  DMA requests past the last k-step
+  // re-fetch the last one (in bounds, never read), which keeps every k-step's wait count the same.
   issue_dma(0, 0);
-  if (T > 1) {
-    issue_dma(1, 1);
-    wait_all_but_newest_step();
-  } else {
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-  }
+  issue_dma(T > 1 ? 1 : 0, 1);
+  wait_all_but_newest_step();
 
-  // ---- main loop, software-pipelined by hand.  The activation fragments of MFMA step s+1 are read
-  // from LDS while the MFMAs of step s run; the workgroup barrier sits before the LAST MFMA step of
-  // a k-step, so that the LDS reads of the next k-step (first activation fragments, the lane's
-  // packed codes, its group scales) are in flight behind 8 MFMAs instead of stalling the pipe.
-  struct WRegs {
-    uint4 w[2][2];  // [tile][piece]
-    int sg[2];
-  };
-  auto read_w = [&](WRegs& r, const int8_t* sb) {
+  // ---- main loop, software-pipelined by hand and branch-free.  The activation fragments of MFMA
+  // step s+1 are read from LDS while the MFMAs of step s run; the workgroup barrier sits before
+  // the LAST MFMA step of a k-step (whose int8 operands are already converted), so that the LDS
+  // reads of the next k-step (first activation fragments, the lane's packed codes, its group
+  // scales) are in flight behind 8 MFMAs instead of stalling the pipe.
+  uint4 wq[2][2];  // this lane's packed codes of the current k-step: [tile][piece]
+  int sg[2];       // and its two group scales
+  auto read_w = [&](const int8_t* sb) {
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
-      r.w[c][0] = *(const uint4*)(sb + w_off + c * 2048);
-      r.w[c][1] = *(const uint4*)(sb + w_off + c * 2048 + 512);
-      r.sg[c] = 0;
+      wq[c][0] = *(const uint4*)(sb + w_off + c * 2048);
+      wq[c][1] = *(const uint4*)(sb + w_off + c * 2048 + 512);
+      sg[c] = 0;
       if constexpr (MODE != kPerChannel)
-        r.sg[c] = (int)sb[kDAStage + kDWStage + wave * 256 + c * 32 + n32];
+        sg[c] = (int)sb[kDAStage + kDWStage + wave * 256 + c * 32 + n32];
     }
   };
   auto read_a = [&](v4i (&a)[4], const int8_t* sb, int s) {
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) a[mt] = *(const v4i*)(sb + a_off[s] + mt * 4096);
   };
-  auto mfma_step = [&](const v4i (&a)[4], const WRegs& r, int s) {
+  // MFMA step s uses piece s%2, dword pair s/2 of the lane's packed codes
+  auto make_b = [&](int c, int s) {
+    const uint4 pc = wq[c][s & 1];
+    const uint32_t d0 = (s >> 1) ? pc.z : pc.x, d1 = (s >> 1) ? pc.w : pc.y;
+    return convert_b<MODE>(d0, d1, sg[c]);
+  };
+  auto mfma_row = [&](const v4i (&a)[4], const v4i b, int c) {
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
-      // MFMA step s uses piece s%2, dword pair s/2 of the lane's packed codes
-      const uint4 pc = r.w[c][s & 1];
-      const uint32_t d0 = (s >> 1) ? pc.z : pc.x, d1 = (s >> 1) ? pc.w : pc.y;
-      const v4i b = convert_b<MODE>(d0, d1, r.sg[c]);
-#pragma unroll
-      for (int mt = 0; mt < 4; ++mt)
-        acc[mt][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[mt], b, acc[mt][c], 0, 0, 0);
-    }
+    for (int mt = 0; mt < 4; ++mt)
+      acc[mt][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[mt], b, acc[mt][c], 0, 0, 0);
   };
 
   int stage = 0;
   v4i a0[4], a1[4];
-  WRegs wr0, wr1;
-  read_w(wr0, lds);
+  read_w(lds);
   read_a(a0, lds, 0);
-  auto kstep = [&](int t, const WRegs& wc, WRegs& wn) {
+  for (int t = 0; t < T; ++t) {
     // k-step t+2 goes into the stage that was read during k-step t-1 (everyone is past the
     // barrier inside it)
-    const bool more = t + 2 < T;
-    if (more) issue_dma(t + 2, stage == 0 ? 2 : stage - 1);
+    issue_dma(t + 2 < T ? t + 2 : T - 1, stage == 0 ? 2 : stage - 1);
     const int8_t* sb = lds + stage * kDStage;
     read_a(a1, sb, 1);
-    mfma_step(a0, wc, 0);
+    mfma_row(a0, make_b(0, 0), 0);
+    mfma_row(a0, make_b(1, 0), 1);
     read_a(a0, sb, 2);
-    mfma_step(a1, wc, 1);
+    mfma_row(a1, make_b(0, 1), 0);
+    mfma_row(a1, make_b(1, 1), 1);
     read_a(a1, sb, 3);
-    mfma_step(a0, wc, 2);
+    mfma_row(a0, make_b(0, 2), 0);
+    mfma_row(a0, make_b(1, 2), 1);
+    const v4i b30 = make_b(0, 3), b31 = make_b(1, 3);
     // my DMA of k-step t+1 has landed (only the loads of k-step t+2 may still be in flight), my
     // LDS reads of this stage are done; then everyone's
-    if (more)
-      wait_all_but_newest_step();
-    else
-      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    wait_all_but_newest_step();
     stage = (stage == 2) ? 0 : stage + 1;
-    if (t + 1 < T) {
-      const int8_t* nb = lds + stage * kDStage;
-      read_a(a0, nb, 0);
-      read_w(wn, nb);
-    }
-    mfma_step(a1, wc, 3);
-  };
-  for (int t = 0; t < T; t += 2) {
-    kstep(t, wr0, wr1);
-    if (t + 1 < T) kstep(t + 1, wr1, wr0);
+    // first LDS reads of k-step t+1 (stale data after the last k-step: read, never used) ...
+    const int8_t* nb = lds + stage * kDStage;
+    read_a(a0, nb, 0);
+    read_w(nb);
+    // ... in flight behind the last MFMA step of k-step t
+    mfma_row(a1, b30, 0);
+    mfma_row(a1, b31, 1);
   }
+  // the clamped DMA requests of the last two k-steps may still be landing in the ring
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
   // ---- fused Dequant epilogue.  Lane holds column n32 of each tile; register v of a 32x32 tile is
   // row 8*(v/4) + 4*h + v%4.  The ring is free now (nothing reads it after the last barrier and
