@@ -80,7 +80,9 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
     p.ws_acc = (int32_t*)((char*)workspace + (((size_t)(N / 16) * 4 + 255) & ~(size_t)255));
     return launch_gemm_skinny(p, mode, (hipStream_t)stream);
   }
-  if (get_prefill_tuning() == 0) return launch_gemm_prefill_dma(p, mode, (hipStream_t)stream);
+  const int tune = get_prefill_tuning();
+  if (tune >= 10 && tune <= 12) return launch_gemm_prefill_dma(p, mode, tune - 10, (hipStream_t)stream);
+  if (tune == 0) return launch_gemm_prefill_dma(p, mode, 0, (hipStream_t)stream);
   return launch_gemm_prefill(p, mode, (hipStream_t)stream);
 }
 

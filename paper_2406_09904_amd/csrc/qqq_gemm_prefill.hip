@@ -200,7 +200,7 @@ static int launch_one(const GemmParams& p, hipStream_t st) {
 template <int MODE>
 static int launch_mode(const GemmParams& p, hipStream_t st) {
   int nw = 8;
-  if (g_prefill_waves == 4 || g_prefill_waves == 8) nw = g_prefill_waves;
+  if (g_prefill_waves == 4) nw = 4;
   if (nw == 8) return launch_one<MODE, 8>(p, st);
   return launch_one<MODE, 4>(p, st);
 }

@@ -1,31 +1,33 @@
-// Prefill W4A8 GEMM, main kernel: 128 x 512 workgroup tile, 8 waves, three-stage LDS ring fed by
-// global->LDS DMA loads (global_load_lds_dwordx4), v_mfma_i32_32x32x32_i8 main loop.
+// Prefill W4A8 GEMM, main kernel family: three-stage LDS ring fed by global->LDS DMA loads
+// (global_load_lds_dwordx4), v_mfma_i32_32x32x32_i8 main loop, one workgroup per output tile.
 //
-// Why this shape on gfx950.  The int8 MFMA pipe retires a 32x32x32 tile in 32 clocks, so one k-step
-// (128 k) of a wave's 128 x 64 tile is 1024 clocks of MFMA; a global load that misses L2 takes
-// several times that.  Registers cannot hold that much prefetch next to 128 accumulator registers,
-// but the 160 KiB LDS can: every wave issues the DMA loads for k-step t+2 before it computes k-step
-// t, the loads need no registers, and the only wait is "my DMA of k-step t+1 has landed"
-// (s_waitcnt vmcnt(6): six DMA loads per wave per k-step, seven with group scales) right before the workgroup barrier.
+// Shape parameters: NW waves split N; each wave owns MT x CT MFMA tiles of 32 x 32, i.e. a
+// (32*MT) x (32*CT) patch of Y, so the workgroup tile is (32*MT) x (NW*32*CT).  Instances:
+//   <4,2,8>  128 x 512, 8 waves, 128 accumulator registers, two waves per SIMD
+//   <4,4,4>  128 x 512, 4 waves, 256 accumulator registers (AGPRs), one wave per SIMD: each
+//            activation fragment read from LDS feeds 4 MFMAs instead of 2
+//   <8,2,4>  256 x 256, 4 waves, 256 accumulator registers: each converted weight fragment feeds
+//            8 MFMAs instead of 4 (the per-group conversion is the VALU-heavy part)
 //
-// LDS stage (50 KiB): activations 128 rows x 128 B with the 16-byte slots of row r XOR-swizzled by
-// r%8 (DMA writes lane-linear, so the swizzle is applied on the global side: lane l fetches slot
-// l%8 ^ row%8), then each wave's own 4 KiB of packed int4 codes exactly as they lie in memory,
-// then (per-group variant) each wave's 64 group scales of the k-step.
-// Weights never cross waves: the waves split N, each converts its codes to int8 once per k-step
-// (Sec. 3.3.1 / 3.3.2 of the QQQ paper) and feeds 4 MFMAs per converted fragment.
+// Why a DMA ring on gfx950.  The int8 MFMA pipe retires a 32x32x32 tile in 32 clocks, so one
+// k-step (128 k) is 1-2 thousand clocks of MFMA per wave; a global load that misses L2 takes
+// several times that.  Registers cannot hold that much prefetch next to the accumulators, but the
+// 160 KiB LDS can: every wave issues the DMA loads for k-step t+2 before it computes k-step t, the
+// loads need no registers, and the only wait is "my DMA of k-step t+1 has landed" right before the
+// workgroup barrier (s_waitcnt vmcnt(number of DMA loads per wave per k-step)).
+//
+// LDS stage (<= 50 KiB): activations (32*MT) rows x 128 B with the 16-byte slots of row r
+// XOR-swizzled by r%8 (DMA writes lane-linear, so the swizzle is applied on the global side: lane
+// l fetches slot l%8 ^ row%8), then each wave's own 2*CT KiB of packed int4 codes exactly as they
+// lie in memory, then (per-group variant) each wave's 32*CT group scales of the k-step.
+// Weights never cross waves: each wave converts its codes to int8 once per k-step (Sec. 3.3.1 /
+// 3.3.2 of the QQQ paper) and feeds MT MFMAs per converted fragment.
 #include "qqq_internal.h"
 
 namespace qqq {
 
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
-
-constexpr int kDBM = 128, kDBK = 128, kDNW = 8, kDBN = kDNW * 64, kDStages = 3;
-constexpr int kDAStage = kDBM * kDBK;        // 16 KiB of activations
-constexpr int kDWStage = kDBN * kDBK / 2;    // 32 KiB of packed codes
-constexpr int kDSgStage = kDNW * 256;          // 256 B of group scales per wave (64 used)
-constexpr int kDStage = kDAStage + kDWStage + kDSgStage;
 
 template <int MODE>
 __device__ __forceinline__ v4i convert_b(uint32_t d0, uint32_t d1, int sg) {
@@ -46,11 +48,30 @@ __device__ __forceinline__ v4i convert_b(uint32_t d0, uint32_t d1, int sg) {
   return (v4i){o[0], o[1], o[2], o[3]};
 }
 
-template <int MODE>
-__global__ __launch_bounds__(kDNW * 64, 1) void gemm_prefill_dma_kernel(const GemmParams p,
-                                                                       const int tiles_m,
-                                                                       const int tiles_n) {
-  __shared__ __attribute__((aligned(1024))) int8_t lds[kDStages * kDStage];
+template <int MT, int CT, int NW>
+struct DmaShape {
+  static constexpr int kBM = 32 * MT, kBN = NW * 32 * CT, kBK = 128, kStages = 3;
+  static constexpr int kAStage = kBM * kBK;           // activations of one k-step
+  static constexpr int kWWave = CT * 2048;            // packed codes of one wave and k-step
+  static constexpr int kWStage = NW * kWWave;
+  static constexpr int kSgStage = NW * 256;           // 256 B of group scales per wave (32*CT used)
+  static constexpr int kStage = kAStage + kWStage + kSgStage;
+  static constexpr int kAPieces = kBM / (8 * NW);     // 1 KiB DMA pieces (8 rows) per wave
+  static constexpr int kWChunks = 2 * CT;             // 1 KiB DMA chunks (16 channels) per wave
+  static constexpr int kEpRow = 64 * CT + 16;         // fp16 row of the epilogue patch + bank pad
+  static constexpr int kEpWave = kBM * kEpRow;
+  static constexpr int kLds = kStages * kStage;
+  static_assert(kBM % (8 * NW) == 0, "activation rows must split evenly over the waves");
+  static_assert(NW * kEpWave + kBM * 4 <= kLds, "epilogue staging must fit the ring");
+  static_assert(kLds <= 160 * 1024, "ring must fit the 160 KiB LDS");
+};
+
+template <int MODE, int MT, int CT, int NW>
+__global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const GemmParams p,
+                                                                     const int tiles_m,
+                                                                     const int tiles_n) {
+  using S = DmaShape<MT, CT, NW>;
+  __shared__ __attribute__((aligned(1024))) int8_t lds[S::kLds];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -74,33 +95,34 @@ __global__ __launch_bounds__(kDNW * 64, 1) void gemm_prefill_dma_kernel(const Ge
   const int first_m = (pid / width) * kGroupM;
   const int gsize = (tiles_m - first_m < kGroupM) ? tiles_m - first_m : kGroupM;
   const int tm = first_m + (pid % width) % gsize, tn = (pid % width) / gsize;
-  const int m0 = tm * kDBM;
+  const int m0 = tm * S::kBM;
+  const int n_wave = tn * S::kBN + wave * 32 * CT;  // first channel of this wave
 
-  // ---- DMA sources.  Activations: this wave copies rows 16*wave .. +15 (two 1 KiB pieces of 8
+  // ---- DMA sources.  Activations: this wave copies rows 8*kAPieces*wave .. (1 KiB pieces of 8
   // rows); lane l lands in slot l%8 of row l/8, so it fetches chunk (l%8) ^ (row%8).  Rows past M
-  // re-read row M-1 (never stored).  Weights: this wave's four 1 KiB chunks, copied verbatim;
-  // chunks past N/16 re-read the last valid chunk (never stored).
-  const int8_t* a_src[2];
+  // re-read row M-1 (never stored).  Weights: this wave's 1 KiB chunks, copied verbatim; chunks
+  // past N/16 re-read the last valid chunk (never stored).
+  const int8_t* a_src[S::kAPieces];
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int r = 16 * wave + 8 * i + (lane >> 3);
+  for (int i = 0; i < S::kAPieces; ++i) {
+    const int r = 8 * (S::kAPieces * wave + i) + (lane >> 3);
     int m = m0 + r;
     if (m > M - 1) m = M - 1;
     a_src[i] = p.a_q + (int64_t)m * K + (((lane & 7) ^ (r & 7)) << 4);
   }
-  const int8_t* w_src[4];
+  const int8_t* w_src[S::kWChunks];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    int nt = tn * (kDBN / 16) + wave * 4 + j;
+  for (int j = 0; j < S::kWChunks; ++j) {
+    int nt = (n_wave >> 4) + j;
     if (nt > ntiles - 1) nt = ntiles - 1;
     w_src[j] = (const int8_t*)p.w + (int64_t)nt * 1024 + lane * 16;
   }
   const int64_t w_step = (int64_t)ntiles * 1024;  // bytes between k-steps of the packed weights
-  // group scales of the wave's 64 channels: lanes 0..15 fetch 4 bytes each, the other lanes (and
-  // channels past N) re-read the last valid dword; each lane writes its own LDS dword
+  // group scales of the wave's 32*CT channels: the first 8*CT lanes fetch 4 bytes each, the other
+  // lanes (and channels past N) re-read a valid dword; each lane writes its own LDS dword
   const int8_t* sg_src = nullptr;
   if constexpr (MODE != kPerChannel) {
-    int c0 = tn * kDBN + wave * 64 + 4 * (lane < 16 ? lane : 15);
+    int c0 = n_wave + 4 * (lane < 8 * CT ? lane : 8 * CT - 1);
     if (c0 > N - 4) c0 = N - 4;
     sg_src = p.s_g + c0;
   }
@@ -120,14 +142,22 @@ __global__ __launch_bounds__(kDNW * 64, 1) void gemm_prefill_dma_kernel(const Ge
   };
   const uint32_t wave_u = (uint32_t)__builtin_amdgcn_readfirstlane(wave);
   auto issue_dma = [&](int t, int stage) {
-    const uint32_t base = lds_base + (uint32_t)stage * kDStage;
+    const uint32_t base = lds_base + (uint32_t)stage * S::kStage;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) dma16(a_src[i] + (int64_t)t * kDBK, base + (2 * wave_u + i) * 1024);
+    for (int i = 0; i < S::kAPieces; ++i)
+      dma16(a_src[i] + (int64_t)t * S::kBK, base + (S::kAPieces * wave_u + i) * 1024);
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-      dma16(w_src[j] + (int64_t)t * w_step, base + kDAStage + wave_u * 4096 + j * 1024);
+    for (int j = 0; j < S::kWChunks; ++j)
+      dma16(w_src[j] + (int64_t)t * w_step, base + S::kAStage + wave_u * S::kWWave + j * 1024);
     if constexpr (MODE != kPerChannel)
-      dma4(sg_src + (int64_t)t * N, base + kDAStage + kDWStage + wave_u * 256);
+      dma4(sg_src + (int64_t)t * N, base + S::kAStage + S::kWStage + wave_u * 256);
+  };
+  // DMA loads per wave per k-step
+  constexpr int kDmaPerStep = S::kAPieces + S::kWChunks + (MODE != kPerChannel ? 1 : 0);
+  static_assert(kDmaPerStep <= 32, "wait count must fit the vmcnt field with room to spare");
+  // "everything but my newest k-step of DMA has landed, my LDS reads are done", then the barrier
+  auto wait_all_but_newest_step = [&]() {
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(kDmaPerStep) : "memory");
   };
 
   // ---- per-lane LDS read offsets.  A operand of MFMA step s: row 32*mt + n32, chunk 2s+h, stored
@@ -136,31 +166,23 @@ __global__ __launch_bounds__(kDNW * 64, 1) void gemm_prefill_dma_kernel(const Ge
   int a_off[4];
 #pragma unroll
   for (int s = 0; s < 4; ++s) a_off[s] = n32 * 128 + (((2 * s + h) ^ (n32 & 7)) << 4);
-  const int w_off = kDAStage + wave * 4096 + (n32 >> 4) * 1024 + ((n32 & 15) + 16 * h) * 16;
+  const int w_off = S::kAStage + wave * S::kWWave + (n32 >> 4) * 1024 + ((n32 & 15) + 16 * h) * 16;
+  const int sg_off = S::kAStage + S::kWStage + wave * 256 + n32;
 
-  // group scale of this lane's column in each of the wave's two 32-channel tiles
-  int col[2];
-  bool nvalid[2];
+  int col[CT];
+  bool nvalid[CT];
 #pragma unroll
-  for (int c = 0; c < 2; ++c) {
-    col[c] = tn * kDBN + wave * 64 + c * 32 + n32;
+  for (int c = 0; c < CT; ++c) {
+    col[c] = n_wave + c * 32 + n32;
     nvalid[c] = col[c] < N;
   }
-  v16i acc[4][2];
+  v16i acc[MT][CT];
 #pragma unroll
-  for (int mt = 0; mt < 4; ++mt)
+  for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-    for (int c = 0; c < 2; ++c)
+    for (int c = 0; c < CT; ++c)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[mt][c][v] = 0;
-
-  // DMA loads per wave per k-step: 2 activation pieces + 4 weight chunks (+ 1 of group scales)
-  auto wait_all_but_newest_step = [&]() {
-    if constexpr (MODE == kPerChannel)
-      asm volatile("s_waitcnt vmcnt(6) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    else
-      asm volatile("s_waitcnt vmcnt(7) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-  };
 
   // ---- prologue: k-steps 0 and 1 in flight, wait for step 0.  DMA requests past the last k-step
   // re-fetch the last one (in bounds, never read), which keeps every k-step's wait count the same.
@@ -172,22 +194,21 @@ __global__ __launch_bounds__(kDNW * 64, 1) void gemm_prefill_dma_kernel(const Ge
   // step s+1 are read from LDS while the MFMAs of step s run; the workgroup barrier sits before
   // the LAST MFMA step of a k-step (whose int8 operands are already converted), so that the LDS
   // reads of the next k-step (first activation fragments, the lane's packed codes, its group
-  // scales) are in flight behind 8 MFMAs instead of stalling the pipe.
-  uint4 wq[2][2];  // this lane's packed codes of the current k-step: [tile][piece]
-  int sg[2];       // and its two group scales
+  // scales) are in flight behind MT*CT MFMAs instead of stalling the pipe.
+  uint4 wq[CT][2];  // this lane's packed codes of the current k-step: [tile][piece]
+  int sg[CT];       // and its group scales
   auto read_w = [&](const int8_t* sb) {
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
+    for (int c = 0; c < CT; ++c) {
       wq[c][0] = *(const uint4*)(sb + w_off + c * 2048);
       wq[c][1] = *(const uint4*)(sb + w_off + c * 2048 + 512);
       sg[c] = 0;
-      if constexpr (MODE != kPerChannel)
-        sg[c] = (int)sb[kDAStage + kDWStage + wave * 256 + c * 32 + n32];
+      if constexpr (MODE != kPerChannel) sg[c] = (int)sb[sg_off + c * 32];
     }
   };
-  auto read_a = [&](v4i (&a)[4], const int8_t* sb, int s) {
+  auto read_a = [&](v4i (&a)[MT], const int8_t* sb, int s) {
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt) a[mt] = *(const v4i*)(sb + a_off[s] + mt * 4096);
+    for (int mt = 0; mt < MT; ++mt) a[mt] = *(const v4i*)(sb + a_off[s] + mt * 4096);
   };
   // MFMA step s uses piece s%2, dword pair s/2 of the lane's packed codes
   auto make_b = [&](int c, int s) {
@@ -195,96 +216,98 @@ __global__ __launch_bounds__(kDNW * 64, 1) void gemm_prefill_dma_kernel(const Ge
     const uint32_t d0 = (s >> 1) ? pc.z : pc.x, d1 = (s >> 1) ? pc.w : pc.y;
     return convert_b<MODE>(d0, d1, sg[c]);
   };
-  auto mfma_row = [&](const v4i (&a)[4], const v4i b, int c) {
+  auto mfma_col = [&](const v4i (&a)[MT], const v4i b, int c) {
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
+    for (int mt = 0; mt < MT; ++mt)
       acc[mt][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[mt], b, acc[mt][c], 0, 0, 0);
+  };
+  auto mfma_step = [&](const v4i (&a)[MT], int s) {
+#pragma unroll
+    for (int c = 0; c < CT; ++c) mfma_col(a, make_b(c, s), c);
   };
 
   int stage = 0;
-  v4i a0[4], a1[4];
+  v4i a0[MT], a1[MT];
   read_w(lds);
   read_a(a0, lds, 0);
   for (int t = 0; t < T; ++t) {
     // k-step t+2 goes into the stage that was read during k-step t-1 (everyone is past the
     // barrier inside it)
     issue_dma(t + 2 < T ? t + 2 : T - 1, stage == 0 ? 2 : stage - 1);
-    const int8_t* sb = lds + stage * kDStage;
+    const int8_t* sb = lds + stage * S::kStage;
     read_a(a1, sb, 1);
-    mfma_row(a0, make_b(0, 0), 0);
-    mfma_row(a0, make_b(1, 0), 1);
+    mfma_step(a0, 0);
     read_a(a0, sb, 2);
-    mfma_row(a1, make_b(0, 1), 0);
-    mfma_row(a1, make_b(1, 1), 1);
+    mfma_step(a1, 1);
     read_a(a1, sb, 3);
-    mfma_row(a0, make_b(0, 2), 0);
-    mfma_row(a0, make_b(1, 2), 1);
-    const v4i b30 = make_b(0, 3), b31 = make_b(1, 3);
+    mfma_step(a0, 2);
+    v4i b3[CT];
+#pragma unroll
+    for (int c = 0; c < CT; ++c) b3[c] = make_b(c, 3);
     // my DMA of k-step t+1 has landed (only the loads of k-step t+2 may still be in flight), my
     // LDS reads of this stage are done; then everyone's
     wait_all_but_newest_step();
     stage = (stage == 2) ? 0 : stage + 1;
     // first LDS reads of k-step t+1 (stale data after the last k-step: read, never used) ...
-    const int8_t* nb = lds + stage * kDStage;
+    const int8_t* nb = lds + stage * S::kStage;
     read_a(a0, nb, 0);
     read_w(nb);
     // ... in flight behind the last MFMA step of k-step t
-    mfma_row(a1, b30, 0);
-    mfma_row(a1, b31, 1);
+#pragma unroll
+    for (int c = 0; c < CT; ++c) mfma_col(a1, b3[c], c);
   }
   // the clamped DMA requests of the last two k-steps may still be landing in the ring
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
   // ---- fused Dequant epilogue.  Lane holds column n32 of each tile; register v of a 32x32 tile is
   // row 8*(v/4) + 4*h + v%4.  The ring is free now (nothing reads it after the last barrier and
-  // every DMA has landed): each wave
-  // dequantises its 128 x 64 tile into its own fp16 LDS patch (row pitch 144 B so the two lane
-  // halves hit different banks) and streams it out as full 128-byte row segments.
-  constexpr int kEpRow = 144, kEpWave = kDBM * kEpRow;
-  static_assert(kDNW * kEpWave + kDBM * 4 <= kDStages * kDStage, "epilogue staging must fit the ring");
-  float* sa_lds = (float*)(lds + kDNW * kEpWave);
-  if (tid < kDBM) sa_lds[tid] = (m0 + tid < M) ? p.s_a[m0 + tid] : 0.0f;
-  float swv[2];
+  // every DMA has landed): each wave dequantises its patch into its own fp16 LDS region (row pitch
+  // padded by 16 B so the two lane halves hit different banks) and streams it out as full rows.
+  float* sa_lds = (float*)(lds + NW * S::kEpWave);
+  for (int r = tid; r < S::kBM; r += NW * 64) sa_lds[r] = (m0 + r < M) ? p.s_a[m0 + r] : 0.0f;
+  float swv[CT];
 #pragma unroll
-  for (int c = 0; c < 2; ++c) swv[c] = nvalid[c] ? (float)p.s_w[col[c]] : 0.0f;
+  for (int c = 0; c < CT; ++c) swv[c] = nvalid[c] ? (float)p.s_w[col[c]] : 0.0f;
   __syncthreads();
-  int8_t* ep = lds + wave * kEpWave;
+  int8_t* ep = lds + wave * S::kEpWave;
 #pragma unroll
-  for (int mt = 0; mt < 4; ++mt) {
+  for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const int r0 = mt * 32 + 8 * q + 4 * h;
       const float4 sa4 = *(const float4*)(sa_lds + r0);
       const float sav[4] = {sa4.x, sa4.y, sa4.z, sa4.w};
 #pragma unroll
-      for (int c = 0; c < 2; ++c) {
+      for (int c = 0; c < CT; ++c) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           int x = acc[mt][c][4 * q + j];
           if constexpr (MODE == kPerChannel) x >>= 4;  // exact: the sum is a multiple of 16
-          *(_Float16*)(ep + (r0 + j) * kEpRow + (c * 32 + n32) * 2) = dequant(x, sav[j], swv[c]);
+          *(_Float16*)(ep + (r0 + j) * S::kEpRow + (c * 32 + n32) * 2) = dequant(x, sav[j], swv[c]);
         }
       }
     }
   }
   // the patch is private to this wave and LDS serves one wave's accesses in order
   {
-    const int cc = lane & 7;
-    const int ncol = tn * kDBN + wave * 64 + cc * 8;
+    constexpr int kLanesPerRow = 4 * CT;            // 16-byte pieces per patch row
+    constexpr int kRowsPerIt = 64 / kLanesPerRow;
+    const int cc = lane % kLanesPerRow;
+    const int ncol = n_wave + cc * 8;
 #pragma unroll
-    for (int it = 0; it < 16; ++it) {
-      const int row = it * 8 + (lane >> 3);
-      const v4i d = *(const v4i*)(ep + row * kEpRow + cc * 16);
+    for (int it = 0; it < S::kBM / kRowsPerIt; ++it) {
+      const int row = it * kRowsPerIt + lane / kLanesPerRow;
+      const v4i d = *(const v4i*)(ep + row * S::kEpRow + cc * 16);
       const int m = m0 + row;
       if (m < M && ncol < N) *(v4i*)(p.y + (int64_t)m * N + ncol) = d;
     }
   }
   if (p.acc_out) {  // parity/debug output of the true accumulators: plain stores
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
+    for (int c = 0; c < CT; ++c) {
       if (!nvalid[c]) continue;
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt) {
+      for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int m = m0 + mt * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
@@ -299,27 +322,38 @@ __global__ __launch_bounds__(kDNW * 64, 1) void gemm_prefill_dma_kernel(const Ge
   }
 }
 
-template <int MODE>
+template <int MODE, int MT, int CT, int NW>
 static int launch_dma(const GemmParams& p, hipStream_t st) {
-  const int tiles_m = (p.M + kDBM - 1) / kDBM;
-  const int tiles_n = (p.N + kDBN - 1) / kDBN;
+  using S = DmaShape<MT, CT, NW>;
+  const int tiles_m = (p.M + S::kBM - 1) / S::kBM;
+  const int tiles_n = (p.N + S::kBN - 1) / S::kBN;
   const int64_t grid = (int64_t)tiles_m * tiles_n;
   if (grid > 0x7FFFFFFF) return set_error(QQQ_ERR_SHAPE, "prefill: grid too large");
-  hipLaunchKernelGGL((gemm_prefill_dma_kernel<MODE>), dim3((unsigned)grid), dim3(kDNW * 64), 0, st, p,
-                     tiles_m, tiles_n);
+  hipLaunchKernelGGL((gemm_prefill_dma_kernel<MODE, MT, CT, NW>), dim3((unsigned)grid), dim3(NW * 64),
+                     0, st, p, tiles_m, tiles_n);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return set_error(QQQ_ERR_HIP, "prefill gemm launch: %s", hipGetErrorString(e));
   return QQQ_OK;
 }
 
-int launch_gemm_prefill_dma(const GemmParams& p, int mode, hipStream_t st) {
+template <int MODE>
+static int launch_shape(const GemmParams& p, int shape, hipStream_t st) {
+  switch (shape) {
+    case 1: return launch_dma<MODE, 4, 4, 4>(p, st);
+    case 2: return launch_dma<MODE, 8, 2, 4>(p, st);
+    default: return launch_dma<MODE, 4, 2, 8>(p, st);
+  }
+}
+
+// shape: 0 = 128x512 tile with 8 waves, 1 = 128x512 with 4 waves, 2 = 256x256 with 4 waves
+int launch_gemm_prefill_dma(const GemmParams& p, int mode, int shape, hipStream_t st) {
   switch (mode) {
-    case kPerChannel: return launch_dma<kPerChannel>(p, st);
-    case kGroupClamp: return launch_dma<kGroupClamp>(p, st);
+    case kPerChannel: return launch_shape<kPerChannel>(p, shape, st);
+    case kGroupClamp: return launch_shape<kGroupClamp>(p, shape, st);
     // applying the group scale to partial sums costs more VALU work than the MFMAs hide once
     // the tile has many rows, so both clamp-free requests use the per-weight fp16 FMA route here
     case kGroupLinear:
-    case kGroupFused: return launch_dma<kGroupFused>(p, st);
+    case kGroupFused: return launch_shape<kGroupFused>(p, shape, st);
   }
   return set_error(QQQ_ERR_SHAPE, "unknown mode %d", mode);
 }

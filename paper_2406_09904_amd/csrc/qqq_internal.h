@@ -48,7 +48,7 @@ int launch_gemm_prefill(const GemmParams& p, int mode, hipStream_t st);
 void set_skinny_tuning(int nt, int s, int w);
 void set_prefill_tuning(int waves);
 int get_prefill_tuning();
-int launch_gemm_prefill_dma(const GemmParams& p, int mode, hipStream_t st);
+int launch_gemm_prefill_dma(const GemmParams& p, int mode, int shape, hipStream_t st);
 
 constexpr int kSkinnyMaxM = 64;  // rows the split-K kernel handles (4 MFMA row tiles)
 
