@@ -140,8 +140,9 @@ def load_traffic(name):
     path = os.path.join(ROOT, "profiles", "traffic.json")
     try:
         with open(path) as f:
-            return json.load(f).get(name)
-    except (OSError, ValueError):
+            rec = json.load(f).get(name)
+        return int(rec["fetch_bytes"]) + int(rec["write_bytes"]) if rec else None
+    except (OSError, ValueError, KeyError, TypeError):
         return None
 
 

@@ -1,0 +1,93 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+Every workload of ``synth.workloads()`` runs the whole hot path on the GPU (qqq_quant_act, then the
+GEMM of its variant with automatic kernel selection).  The activation codes and token scales are
+compared in full (bit-exact).  The int32 accumulators and fp16 outputs are compared on sampled
+entries that the oracle computes one by one (all four corners, the last row/column, tile borders
+and seeded random positions); shapes whose full product the oracle finishes in seconds are also
+compared in full.
+"""
+import functools
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import qqq_oracle as orc
+from paper_2406_09904_amd import binding as qqq
+from paper_2406_09904_amd import synth
+from tests.util import f16_bits, ulp_distance
+
+pytestmark = pytest.mark.gpu
+
+WORKLOADS = synth.workloads()
+FULL_COMPARE_MACS = 3e9
+
+
+@functools.lru_cache(maxsize=2)
+def _weights(seed, N, K):
+    """Natural words of the workload's weights (same seeded recipe as Workload.w_nat) and their
+    packed device copy; cached because the config-5 workloads share one weight matrix."""
+    w_nat = synth.random_w_nat(N, K, seed + 2)
+    d_w = qqq.qqq_pack_w4(torch.from_numpy(w_nat.view(np.int32)).cuda(), K)
+    return w_nat, d_w
+
+
+def sample_positions(M, N, count, seed):
+    g = synth.rng(seed)
+    ms = [0, 0, M - 1, M - 1]
+    ns = [0, N - 1, 0, N - 1]
+    for b in (15, 16, 31, 32, 63, 64, 127, 128, 255, 256, 511, 512):      # tile borders
+        if b < M:
+            ms += [b, b]
+            ns += [int(g.integers(0, N)), N - 1]
+        if b < N:
+            ms += [int(g.integers(0, M)), M - 1]
+            ns += [b, b]
+    ms += g.integers(0, M, count).tolist()
+    ns += g.integers(0, N, count).tolist()
+    return np.array(ms, np.int64), np.array(ns, np.int64)
+
+
+@pytest.mark.parametrize("name", sorted(WORKLOADS))
+def test_full_size_workload(name):
+    wl = WORKLOADS[name]
+    M, K, N = wl.M, wl.K, wl.N
+    pg = wl.variant == "pergroup"
+    a = wl.activations()
+    w_nat, d_w = _weights(wl.seed, N, K)
+    s_w = wl.s_w()
+    s_g = wl.s_g() if pg else None
+
+    d_q, d_sa = qqq.qqq_quant_act(torch.from_numpy(a).cuda())
+    ws = qqq.new_workspace(M, N, K)
+    acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
+    d_sw = torch.from_numpy(s_w).cuda()
+    if pg:
+        y = qqq.qqq_gemm_w4a8_pergroup(d_q, d_sa, d_w, torch.from_numpy(s_g).cuda(), d_sw, ws,
+                                       sg_max=wl.sg_hi, acc_out=acc)
+    else:
+        y = qqq.qqq_gemm_w4a8_perchannel(d_q, d_sa, d_w, d_sw, ws, acc_out=acc)
+    torch.cuda.synchronize()
+
+    o_q, o_sa = orc.quant_act(a.view(np.uint16))
+    assert np.array_equal(d_q.cpu().numpy(), o_q), "activation codes differ"
+    assert np.array_equal(d_sa.cpu().numpy().view(np.uint32), o_sa.view(np.uint32)), "token scales differ"
+    assert not ws.any().item(), "workspace not returned to zero"
+
+    im, jn = sample_positions(M, N, 3000, wl.seed + 7)
+    o_acc, o_y = orc.gemm_samples(o_q, o_sa, w_nat, s_g, s_w.view(np.uint16), im, jn)
+    t_im, t_jn = torch.from_numpy(im).cuda(), torch.from_numpy(jn).cuda()
+    g_acc = acc[t_im, t_jn].cpu().numpy().astype(np.int64)
+    g_y = f16_bits(y[t_im, t_jn])
+    assert np.array_equal(g_acc, o_acc), "sampled int32 accumulators differ"
+    assert ulp_distance(g_y, o_y).max() <= 1, "sampled fp16 outputs differ by more than 1 ulp"
+    assert np.abs(o_acc).max() > 0 and np.isfinite(o_y.view(np.float16).astype(np.float32)).all()
+
+    if float(M) * N * K <= FULL_COMPARE_MACS:
+        if pg:
+            f_acc, _, f_y = orc.gemm_pergroup(o_q, o_sa, w_nat, s_g, s_w.view(np.uint16))
+        else:
+            f_acc, _, f_y = orc.gemm_perchannel(o_q, o_sa, w_nat, s_w.view(np.uint16))
+        assert np.array_equal(acc.cpu().numpy(), f_acc), "int32 accumulators differ"
+        assert ulp_distance(f16_bits(y), f_y).max() <= 1, "fp16 outputs differ by more than 1 ulp"
