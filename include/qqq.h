@@ -117,10 +117,11 @@ int qqq_set_group_mode_override(int mode);
 
 /*
  * Tuning/diagnostic knob (host state, not thread-safe) for the skinny kernel: channel tiles per
- * workgroup (1, 2 or 4), number of K slices, waves per workgroup (4, 8 or 16); 0 = automatic for
- * each.  Values that do not fit the shape are ignored.  Returns 0.
+ * workgroup (1, 2 or 4), number of K slices, waves per workgroup (4, 8 or 16), load depth (1 =
+ * shallow, 2 = deep batches of in-flight loads); 0 = automatic for each.  Values that do not fit
+ * the shape are ignored.  Returns 0.
  */
-int qqq_set_skinny_tuning(int channel_tiles, int k_slices, int waves);
+int qqq_set_skinny_tuning(int channel_tiles, int k_slices, int waves, int depth);
 
 /*
  * Tuning/diagnostic knob (host state, not thread-safe) for the prefill path: 0 = automatic;

@@ -54,7 +54,7 @@ def lib():
                                              vp, sz, vp]
         L.qqq_set_kernel_override.argtypes = [ci]
         L.qqq_set_group_mode_override.argtypes = [ci]
-        L.qqq_set_skinny_tuning.argtypes = [ci, ci, ci]
+        L.qqq_set_skinny_tuning.argtypes = [ci, ci, ci, ci]
         L.qqq_set_prefill_tuning.argtypes = [ci]
         _lib = L
     return _lib
@@ -163,8 +163,8 @@ def set_group_mode_override(mode: int) -> int:
     return lib().qqq_set_group_mode_override(mode)
 
 
-def set_skinny_tuning(channel_tiles: int, k_slices: int, waves: int = 0) -> int:
-    return lib().qqq_set_skinny_tuning(channel_tiles, k_slices, waves)
+def set_skinny_tuning(channel_tiles: int, k_slices: int, waves: int = 0, depth: int = 0) -> int:
+    return lib().qqq_set_skinny_tuning(channel_tiles, k_slices, waves, depth)
 
 
 def set_prefill_tuning(waves: int) -> int:

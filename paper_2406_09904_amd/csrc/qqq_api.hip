@@ -120,8 +120,8 @@ int qqq_set_group_mode_override(int mode) {
   return old;
 }
 
-int qqq_set_skinny_tuning(int channel_tiles, int k_slices, int waves) {
-  set_skinny_tuning(channel_tiles, k_slices, waves);
+int qqq_set_skinny_tuning(int channel_tiles, int k_slices, int waves, int depth) {
+  set_skinny_tuning(channel_tiles, k_slices, waves, depth);
   return 0;
 }
 

@@ -38,7 +38,10 @@ __device__ __forceinline__ void load_batch(Batch<NT, MT, U>& b, const GemmParams
       b.w[u][i] = make_uint4(0, 0, 0, 0);
       b.sg[u][i] = 0;
       if (live) {
-        b.w[u][i] = wbase[((int64_t)t * ntiles + i) * 64];
+        // streamed once: non-temporal, so the weights do not evict the activations from L2
+        const v4i raw = __builtin_nontemporal_load(
+            reinterpret_cast<const v4i*>(&wbase[((int64_t)t * ntiles + i) * 64]));
+        b.w[u][i] = make_uint4((uint32_t)raw[0], (uint32_t)raw[1], (uint32_t)raw[2], (uint32_t)raw[3]);
         if constexpr (MODE != kPerChannel)
           b.sg[u][i] = (int)p.s_g[(int64_t)t * p.N + (int64_t)(ng * NT + i) * 16 + nl];
       }
@@ -210,11 +213,12 @@ __global__ __launch_bounds__(W * 64) void gemm_skinny_kernel(const GemmParams p,
   }
 }
 
-static int g_tune_nt = 0, g_tune_s = 0, g_tune_w = 0;
-void set_skinny_tuning(int nt, int s, int w) {
+static int g_tune_nt = 0, g_tune_s = 0, g_tune_w = 0, g_tune_u = 0;
+void set_skinny_tuning(int nt, int s, int w, int u) {
   g_tune_nt = nt;
   g_tune_s = s;
   g_tune_w = w;
+  g_tune_u = u;
 }
 
 template <int MODE, int NT, int MT, int W, int U>
@@ -266,9 +270,13 @@ static int launch_mode(const GemmParams& p, hipStream_t st) {
   if (g_tune_s > 0 && g_tune_s <= p.T) S = g_tune_s;
   if (g_tune_w > 0) w = g_tune_w;
   if (mt <= 1) {
-    if (nt == 4) return launch_w<MODE, 4, 1, 1>(p, w, S, st);
-    if (nt == 2) return launch_w<MODE, 2, 1, 2>(p, w, S, st);
-    return launch_w<MODE, 1, 1, 4>(p, w, S, st);
+    // k-steps per batch of loads: two batches are in flight, so "deep" keeps 4 (NT=4), 8 (NT=2)
+    // or 16 (NT=1) KiB per wave outstanding
+    // (measured: the shallow setting streams better on every benchmark shape, so it is the default)
+    const bool deep = g_tune_u > 1;
+    if (nt == 4) return deep ? launch_w<MODE, 4, 1, 2>(p, w, S, st) : launch_w<MODE, 4, 1, 1>(p, w, S, st);
+    if (nt == 2) return deep ? launch_w<MODE, 2, 1, 4>(p, w, S, st) : launch_w<MODE, 2, 1, 2>(p, w, S, st);
+    return deep ? launch_w<MODE, 1, 1, 8>(p, w, S, st) : launch_w<MODE, 1, 1, 4>(p, w, S, st);
   }
   if (mt == 2) {
     if (nt >= 2) return launch_w<MODE, 2, 2, 1>(p, w, S, st);

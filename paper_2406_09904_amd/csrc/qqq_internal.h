@@ -45,7 +45,7 @@ int launch_pack(const uint32_t* w_nat, int64_t N, int64_t K, uint32_t* w_packed,
                 hipStream_t st);
 int launch_gemm_skinny(const GemmParams& p, int mode, hipStream_t st);
 int launch_gemm_prefill(const GemmParams& p, int mode, hipStream_t st);
-void set_skinny_tuning(int nt, int s, int w);
+void set_skinny_tuning(int nt, int s, int w, int u);
 void set_prefill_tuning(int waves);
 int get_prefill_tuning();
 int launch_gemm_prefill_dma(const GemmParams& p, int mode, int shape, hipStream_t st);
