@@ -125,9 +125,10 @@ int qqq_set_skinny_tuning(int channel_tiles, int k_slices, int waves, int depth)
 
 /*
  * Tuning/diagnostic knob (host state, not thread-safe) for the prefill path: 0 = automatic;
- * 10, 11, 12 = the DMA-ring kernel with a 128x512 tile on 8 waves, a 128x512 tile on 4 waves, a
- * 256x256 tile on 4 waves; 4 or 8 = the register-staged kernel with that many waves per workgroup
- * (128 x 64*waves tile).  Returns 0.
+ * 10, 11, 12 = the DMA-ring kernel, one workgroup per tile, with a 128x512 tile on 8 waves, a
+ * 128x512 tile on 4 waves, a 256x256 tile on 4 waves; 13 = the persistent DMA-ring kernel (128x512
+ * tiles, one workgroup per CU); 4 or 8 = the register-staged kernel with that many waves per
+ * workgroup (128 x 64*waves tile).  Returns 0.
  */
 int qqq_set_prefill_tuning(int waves);
 

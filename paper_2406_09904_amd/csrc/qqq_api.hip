@@ -49,8 +49,11 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
   if (M == 0) return QQQ_OK;
   if (!a_q || !s_a || !w_packed || !s_w || !y || (mode != kPerChannel && !s_g))
     return set_error(QQQ_ERR_NULL, "gemm: null pointer argument");
-  if (!aligned16(a_q) || !aligned16(w_packed) || !aligned16(y) || !aligned16(workspace))
-    return set_error(QQQ_ERR_SHAPE, "gemm: a_q, w_packed, y and workspace must be 16-byte aligned");
+  if (!aligned16(a_q) || !aligned16(w_packed) || !aligned16(y) || !aligned16(workspace) ||
+      (reinterpret_cast<uintptr_t>(s_a) & 3u) || (reinterpret_cast<uintptr_t>(s_w) & 3u) ||
+      (reinterpret_cast<uintptr_t>(s_g) & 3u))
+    return set_error(QQQ_ERR_SHAPE, "gemm: a_q, w_packed, y and workspace must be 16-byte aligned, "
+                     "s_a, s_w and s_g 4-byte aligned");
   int family = g_override;
   if (family == 0) family = (M <= kSkinnyMaxM) ? 1 : 2;
   if (family == 1 && M > kSkinnyMaxM)
@@ -82,7 +85,16 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
   }
   const int tune = get_prefill_tuning();
   if (tune >= 10 && tune <= 12) return launch_gemm_prefill_dma(p, mode, tune - 10, (hipStream_t)stream);
-  if (tune == 0) return launch_gemm_prefill_dma(p, mode, 0, (hipStream_t)stream);
+  if (tune == 13) return launch_gemm_prefill_ring(p, mode, (hipStream_t)stream);
+  if (tune == 0) {
+    // Measured on MI355X: the persistent kernel wins for the per-channel variant at every K and
+    // for the per-group variant when tiles are short (its per-k-step cost is a little higher
+    // there, its per-tile cost much lower).
+    const bool tiles_repeat = ((M + 127) / 128) * ((N + 511) / 512) > num_cus();
+    if (mode == kPerChannel || (tiles_repeat && K <= 3072))
+      return launch_gemm_prefill_ring(p, mode, (hipStream_t)stream);
+    return launch_gemm_prefill_dma(p, mode, 0, (hipStream_t)stream);
+  }
   return launch_gemm_prefill(p, mode, (hipStream_t)stream);
 }
 

@@ -1,0 +1,343 @@
+// Prefill W4A8 GEMM, persistent variant of the DMA-ring kernel: one workgroup per CU walks a
+// list of 128 x 512 output tiles and the LDS ring keeps rotating across tile borders.
+//
+// Same k-step body as gemm_prefill_dma_kernel<.,4,2,8> (8 waves splitting N, 128 accumulator
+// registers per lane, v_mfma_i32_32x32x32_i8, three 50 KiB LDS stages fed by global->LDS DMA two
+// k-steps ahead).  What persistence buys: the DMA stream is a cursor over (tile, k-step) that runs
+// two steps ahead of the MFMAs, so the first two k-steps of the NEXT tile are already in flight
+// while the current tile finishes and is written out — the per-tile pipeline fill (an HBM
+// round trip with one workgroup per CU) disappears, and the output stores of tile i drain under
+// the MFMAs of tile i+1.
+//
+// Everything the k-loop and the epilogue need from global memory arrives by DMA (activations,
+// packed codes, group scales per k-step; token scales and channel scales once per tile),
+// so the loop contains no compiler-visible global load and the hand-placed s_waitcnt vmcnt(N)
+// counts are exact: N = DMA loads per wave per k-step (+2 right after a tile's scale loads).
+//
+// Epilogue: the stage of the tile's last k-step is free until someone issues the DMA of the next
+// tile's third k-step, which the closing barrier of the epilogue prevents; each wave dequantises
+// 32 rows at a time into its own fp16 patch there and streams them out as 128-byte row segments.
+#include "qqq_prefill_common.h"
+
+namespace qqq {
+
+template <int MODE>
+__global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmParams p,
+                                                                  const int tiles_m,
+                                                                  const int tiles_n) {
+  constexpr int kBM = 128, kBN = 512, kBK = 128;
+  constexpr int kAStage = kBM * kBK;              // 16 KiB activations
+  constexpr int kWWave = 4096, kWStage = 8 * kWWave;  // 4 KiB packed codes per wave
+  constexpr int kSmall = kAStage + kWStage;       // per-wave 256 B of group scales (64 used)
+  constexpr int kStage = kSmall + 8 * 256;        // 50 KiB
+  constexpr int kSide = 8 * 512;                  // per tile parity, per wave: 256 B s_a, 256 B s_w
+  constexpr int kEpRow = 144, kEpWave = 32 * kEpRow;  // epilogue patch: 32 rows per pass
+  static_assert(8 * kEpWave <= kSmall, "epilogue patches must not reach the scale slots");
+  __shared__ __attribute__((aligned(1024))) int8_t lds[3 * kStage];
+  __shared__ __attribute__((aligned(256))) int8_t side[2 * kSide];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int n32 = lane & 31, h = lane >> 5;
+  const int T = p.T, N = p.N, M = p.M;
+  const int64_t K = p.K;
+  const int ntiles = N >> 4;
+  const int nblk = tiles_m * tiles_n;
+  const int my_tiles = (nblk - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
+
+  // XCD-aware tile order: consecutive workgroup ids sit on different XCDs (8 of them); the i-th
+  // tile of workgroup b is virtual id b + i*grid, remapped so that each XCD owns one contiguous run
+  // of tiles, walked in groups of 8 row tiles with m fastest: the tiles resident on one XCD at any
+  // time form a compact patch of Y and share activation and weight tiles through that XCD's L2.
+  auto tile_coords = [&](int iter, int& tm, int& tn) {
+    int pid = (int)blockIdx.x + iter * (int)gridDim.x;
+    const int per = nblk / 8;
+    if (per > 0 && pid < per * 8) pid = (pid % 8) * per + pid / 8;
+    constexpr int kGroupM = 8;
+    const int width = kGroupM * tiles_n;
+    const int first_m = (pid / width) * kGroupM;
+    const int gsize = (tiles_m - first_m < kGroupM) ? tiles_m - first_m : kGroupM;
+    tm = first_m + (pid % width) % gsize;
+    tn = (pid % width) / gsize;
+  };
+
+  // ---- DMA side: a cursor (tile iteration d_iter, k-step d_t) that runs two k-steps ahead.
+  // Per-lane source pointers of the cursor's position: two activation rows (1 KiB pieces of 8
+  // rows; lane l lands in slot l%8 of row l/8 and fetches chunk (l%8)^(row%8); rows past M re-read
+  // row M-1), four 1 KiB weight chunks (chunks past N/16 re-read the last one) and a group-scale
+  // dword (lanes past the wave's 64 channels, and channels past N, re-read a valid dword).  They
+  // advance by constant strides per k-step and are rebuilt when the cursor enters a new tile,
+  // which is also when the tile's token scales and channel scales are fetched, once, into a small
+  // side buffer indexed by the tile's parity.
+  int d_iter = 0, d_t = 0;
+  const int8_t* pa[2];
+  const int8_t* pw[4];
+  const int8_t* psg = nullptr;
+  const int swz = ((lane & 7) ^ ((lane >> 3) & 7)) << 4;
+  const int64_t w_step = (int64_t)ntiles * 1024;  // bytes between k-steps of the packed weights
+
+  // DMA loads are issued through inline assembly so that the compiler's wait-count pass does not
+  // know they write LDS (it would drain every outstanding load before the first LDS read of each
+  // k-step); the waits are placed by hand.  M0 carries the wave-uniform LDS destination; lane l
+  // writes its 16 (or 4) bytes at M0 + 16*l (4*l).
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_ptr_t)lds;
+  const uint32_t side_base = (uint32_t)(uintptr_t)(lds_ptr_t)side;
+  const uint32_t wave_u = (uint32_t)__builtin_amdgcn_readfirstlane(wave);
+  auto dma16 = [&](const int8_t* src, uint32_t dst) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src)
+                 : "memory");
+  };
+  auto dma4 = [&](const int8_t* src, uint32_t dst) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(dst), "v"(src)
+                 : "memory");
+  };
+  // enters tile `iter`: rebuilds the pointers and fetches the tile's scales (two more DMA loads)
+  auto enter_dma_tile = [&](int iter) {
+    int tm, tn;
+    tile_coords(iter, tm, tn);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      int m = tm * kBM + 16 * wave + 8 * i + (lane >> 3);
+      if (m > M - 1) m = M - 1;
+      pa[i] = p.a_q + (int64_t)m * K + swz;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int nt = tn * (kBN / 16) + wave * 4 + j;
+      if (nt > ntiles - 1) nt = ntiles - 1;
+      pw[j] = (const int8_t*)p.w + (int64_t)nt * 1024 + lane * 16;
+    }
+    const int c0 = tn * kBN + wave * 64;
+    if constexpr (MODE != kPerChannel) {
+      int c = c0 + 4 * (lane & 15);
+      if (c > N - 4) c = N - 4;
+      psg = p.s_g + c;
+    }
+    int row = tm * kBM + 16 * wave + (lane & 15);  // 16 token scales per wave (lanes repeat)
+    if (row > M - 1) row = M - 1;
+    int col = c0 + 2 * (lane & 31);                // 64 channel scales per wave, 2 per lane
+    if (col > N - 2) col = N - 2;
+    const uint32_t dst = side_base + (uint32_t)(iter & 1) * kSide + wave_u * 512;
+    dma4((const int8_t*)(p.s_a + row), dst);
+    dma4((const int8_t*)(p.s_w + col), dst + 256);
+  };
+  // issues the cursor's k-step into `stage` and advances the cursor; returns true when the step
+  // was the first of a tile (two more loads are then in flight).  Past the last tile the cursor
+  // keeps re-fetching the last k-step (in bounds, never read), so wait counts never change.
+  auto issue_next_dma = [&](int stage) {
+    const uint32_t base = lds_base + (uint32_t)stage * kStage;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) dma16(pa[i], base + (2 * wave_u + i) * 1024);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) dma16(pw[j], base + kAStage + wave_u * kWWave + j * 1024);
+    if constexpr (MODE != kPerChannel) dma4(psg, base + kSmall + wave_u * 256);
+    ++d_t;
+    if (d_t < T) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) pa[i] += kBK;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) pw[j] += w_step;
+      if constexpr (MODE != kPerChannel) psg += N;
+      return false;
+    }
+    if (d_iter + 1 < my_tiles) {
+      d_t = 0;
+      ++d_iter;
+      enter_dma_tile(d_iter);
+      return true;
+    }
+    d_t = T - 1;  // stay on the last k-step
+    return false;
+  };
+  constexpr int kDmaPerStep = 6 + (MODE != kPerChannel ? 1 : 0);
+  // "everything but my newest k-step of DMA has landed, my LDS reads are done", then the barrier;
+  // `extra` = the newest k-step was followed by a tile's two scale loads
+  auto wait_all_but_newest_step = [&](bool extra) {
+    if (extra)
+      asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(kDmaPerStep + 2) : "memory");
+    else
+      asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(kDmaPerStep) : "memory");
+  };
+
+  // ---- per-lane LDS read offsets (see gemm_prefill_dma_kernel)
+  int a_off[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) a_off[s] = n32 * 128 + (((2 * s + h) ^ (n32 & 7)) << 4);
+  const int w_off = kAStage + wave * kWWave + (n32 >> 4) * 1024 + ((n32 & 15) + 16 * h) * 16;
+  const int small_off = kSmall + wave * 256;
+
+  v16i acc[4][2];
+  uint4 wq[2][2];  // this lane's packed codes of the current k-step: [tile][piece]
+  int sg[2];       // and its group scales
+  auto read_w = [&](const int8_t* sb) {
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      wq[c][0] = *(const uint4*)(sb + w_off + c * 2048);
+      wq[c][1] = *(const uint4*)(sb + w_off + c * 2048 + 512);
+      sg[c] = 0;
+      if constexpr (MODE != kPerChannel) sg[c] = (int)sb[small_off + c * 32 + n32];
+    }
+  };
+  auto read_a = [&](v4i (&a)[4], const int8_t* sb, int s) {
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) a[mt] = *(const v4i*)(sb + a_off[s] + mt * 4096);
+  };
+  // MFMA step s uses piece s%2, dword pair s/2 of the lane's packed codes
+  auto make_b = [&](int c, int s) {
+    const uint4 pc = wq[c][s & 1];
+    const uint32_t d0 = (s >> 1) ? pc.z : pc.x, d1 = (s >> 1) ? pc.w : pc.y;
+    return convert_b<MODE>(d0, d1, sg[c]);
+  };
+  auto mfma_col = [&](const v4i (&a)[4], const v4i b, int c) {
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+      acc[mt][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[mt], b, acc[mt][c], 0, 0, 0);
+  };
+
+  // ---- prologue: k-steps 0 and 1 of the first tile in flight, wait for step 0
+  enter_dma_tile(0);  // its two scale loads are older than everything below: always landed
+  issue_next_dma(0);
+  wait_all_but_newest_step(issue_next_dma(1));
+
+  int stage = 0;
+  v4i a0[4], a1[4];
+  read_w(lds);
+  read_a(a0, lds, 0);
+  for (int it = 0; it < my_tiles; ++it) {
+    int tm, tn;
+    tile_coords(it, tm, tn);
+    const int m0 = tm * kBM;
+    const int n_wave = tn * kBN + wave * 64;
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+      for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[mt][c][v] = 0;
+
+    for (int t = 0; t < T; ++t) {
+      // the cursor's k-step (two ahead, possibly already in the next tile) goes into the stage
+      // that was read during the previous k-step (everyone is past the barrier inside it)
+      const bool extra = issue_next_dma(stage == 0 ? 2 : stage - 1);
+      const int8_t* sb = lds + stage * kStage;
+      read_a(a1, sb, 1);
+      mfma_col(a0, make_b(0, 0), 0);
+      mfma_col(a0, make_b(1, 0), 1);
+      read_a(a0, sb, 2);
+      mfma_col(a1, make_b(0, 1), 0);
+      mfma_col(a1, make_b(1, 1), 1);
+      read_a(a1, sb, 3);
+      mfma_col(a0, make_b(0, 2), 0);
+      mfma_col(a0, make_b(1, 2), 1);
+      const v4i b30 = make_b(0, 3), b31 = make_b(1, 3);
+      // my DMA of the next k-step has landed (only the loads of the one after may still be in
+      // flight), my LDS reads of this stage are done; then everyone's
+      wait_all_but_newest_step(extra);
+      stage = (stage == 2) ? 0 : stage + 1;
+      // first LDS reads of the next k-step (after a tile's last k-step: the next tile's first;
+      // after the very last: stale data, read but never used) ...
+      const int8_t* nb = lds + stage * kStage;
+      read_a(a0, nb, 0);
+      read_w(nb);
+      // ... in flight behind the last MFMA step of this k-step
+      mfma_col(a1, b30, 0);
+      mfma_col(a1, b31, 1);
+    }
+
+    // ---- fused Dequant epilogue in the stage of the tile's last k-step.  Lane holds column n32
+    // of each 32-wide tile; register v of a 32x32 tile is row 8*(v/4) + 4*h + v%4.
+    {
+      const int8_t* fsb = lds + (stage == 0 ? 2 : stage - 1) * kStage;
+      int8_t* patch = const_cast<int8_t*>(fsb) + wave * kEpWave;
+      const int8_t* sd = side + (it & 1) * kSide;  // this tile's scales: [wave][256 B s_a, 256 B s_w]
+      float swv[2];
+#pragma unroll
+      for (int c = 0; c < 2; ++c)
+        swv[c] = (float)*(const _Float16*)(sd + wave * 512 + 256 + (c * 32 + n32) * 2);
+      const int cc = lane & 7;
+      const int ncol = n_wave + cc * 8;
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int r0 = mt * 32 + 8 * q + 4 * h;  // token scales of rows r0..r0+3: wave r0/16's slot
+          const float4 sa4 = *(const float4*)(sd + (r0 >> 4) * 512 + (r0 & 15) * 4);
+          const float sav[4] = {sa4.x, sa4.y, sa4.z, sa4.w};
+#pragma unroll
+          for (int c = 0; c < 2; ++c) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              int x = acc[mt][c][4 * q + j];
+              if constexpr (MODE == kPerChannel) x >>= 4;  // exact: the sum is a multiple of 16
+              *(_Float16*)(patch + (8 * q + 4 * h + j) * kEpRow + (c * 32 + n32) * 2) =
+                  dequant(x, sav[j], swv[c]);
+            }
+          }
+        }
+        // the patch is private to this wave and LDS serves one wave's accesses in order
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const int row = i4 * 8 + (lane >> 3);
+          const v4i d = *(const v4i*)(patch + row * kEpRow + cc * 16);
+          const int m = m0 + mt * 32 + row;
+          if (m < M && ncol < N) *(v4i*)(p.y + (int64_t)m * N + ncol) = d;
+        }
+      }
+      if (p.acc_out) {  // parity/debug output of the true accumulators: plain stores
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+          const int col = n_wave + c * 32 + n32;
+          if (col >= N) continue;
+#pragma unroll
+          for (int mt = 0; mt < 4; ++mt) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const int m = m0 + mt * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+              if (m < M) {
+                int x = acc[mt][c][v];
+                if constexpr (MODE == kPerChannel) x >>= 4;
+                p.acc_out[(int64_t)m * N + col] = x;
+              }
+            }
+          }
+        }
+      }
+      // nobody may start the next tile (whose first DMA reuses this stage) before all are done
+      asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    }
+  }
+  // the cursor's last requests may still be landing in the ring
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
+template <int MODE>
+static int launch_ring(const GemmParams& p, hipStream_t st) {
+  const int tiles_m = (p.M + 127) / 128;
+  const int tiles_n = (p.N + 511) / 512;
+  const int64_t tiles = (int64_t)tiles_m * tiles_n;
+  if (tiles > 0x7FFFFFFF) return set_error(QQQ_ERR_SHAPE, "prefill: too many tiles");
+  int64_t grid = num_cus();
+  if (grid > tiles) grid = tiles;
+  hipLaunchKernelGGL((gemm_prefill_ring_kernel<MODE>), dim3((unsigned)grid), dim3(512), 0, st, p,
+                     tiles_m, tiles_n);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return set_error(QQQ_ERR_HIP, "prefill gemm launch: %s", hipGetErrorString(e));
+  return QQQ_OK;
+}
+
+int launch_gemm_prefill_ring(const GemmParams& p, int mode, hipStream_t st) {
+  // With fewer than three k-steps per tile the DMA cursor would run more than one tile ahead and
+  // overwrite the two-deep scale buffer before its tile is written out: use the per-tile kernel.
+  if (p.T < 3) return launch_gemm_prefill_dma(p, mode, 0, st);
+  switch (mode) {
+    case kPerChannel: return launch_ring<kPerChannel>(p, st);
+    case kGroupClamp: return launch_ring<kGroupClamp>(p, st);
+    // applying the group scale to partial sums costs more VALU work than the MFMAs hide once
+    // the tile has many rows, so both clamp-free requests use the per-weight fp16 FMA route here
+    case kGroupLinear:
+    case kGroupFused: return launch_ring<kGroupFused>(p, st);
+  }
+  return set_error(QQQ_ERR_SHAPE, "unknown mode %d", mode);
+}
+
+}  // namespace qqq

@@ -49,6 +49,7 @@ void set_skinny_tuning(int nt, int s, int w, int u);
 void set_prefill_tuning(int waves);
 int get_prefill_tuning();
 int launch_gemm_prefill_dma(const GemmParams& p, int mode, int shape, hipStream_t st);
+int launch_gemm_prefill_ring(const GemmParams& p, int mode, hipStream_t st);
 
 constexpr int kSkinnyMaxM = 64;  // rows the split-K kernel handles (4 MFMA row tiles)
 
