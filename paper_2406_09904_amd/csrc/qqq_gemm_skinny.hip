@@ -12,7 +12,7 @@
 // Per k-step (128 k) a lane loads 16 B of packed codes per 16-channel tile, converts them in
 // registers to two int8 MFMA operands (Sec. 3.3.1 FastINT4toINT8, or Sec. 3.3.2's group-scale
 // route) and issues two v_mfma_i32_16x16x64_i8 per row tile.  Activations are the other operand
-// (rows >= M are zero registers, never loaded).  Dequant (Sec. 3.3) is fused at the end.
+// (rows >= M repeat row M-1; their outputs are never stored).  Dequant (Sec. 3.3) is fused at the end.
 #include "qqq_internal.h"
 
 namespace qqq {
@@ -21,48 +21,70 @@ template <int NT, int MT, int U>
 struct Batch {
   uint4 w[U][NT];
   v4i a[U][MT][2];
-  int sg[U][NT];
+  int sgs[U][4 * NT];  // wave-uniform: the k-step's 16*NT group-scale bytes
 };
 
+// The 16*NT group scales of one k-step of a wave's channel group are contiguous and the same for
+// the whole wave, so they travel through the scalar (constant) path: no vector-memory
+// instruction, which is the scarce issue slot of this kernel.  The compiler tracks the scalar
+// loads' completion itself, so they stay in flight across the batch like the vector loads.
+typedef const __attribute__((address_space(4))) int* const_int_ptr;
+
+template <int NT>
+__device__ __forceinline__ void load_group_scales(const int8_t* gp, int (&sgs)[4 * NT]) {
+  const const_int_ptr sp = (const_int_ptr)(uintptr_t)gp;  // gp is wave-uniform
+#pragma unroll
+  for (int j = 0; j < 4 * NT; ++j) sgs[j] = sp[j];
+}
+
+// lane's scale for tile i: byte 16*i + n%16 of the wave's scale words
+template <int NT>
+__device__ __forceinline__ int pick_group_scale(const int (&sgs)[4 * NT], int i, int nl) {
+  // word nl/4 through lane masks (and/or on scalar operands), then byte nl%4
+  const int q = nl >> 2;
+  const int m0 = -(int)(q == 0), m1 = -(int)(q == 1), m2 = -(int)(q == 2), m3 = -(int)(q == 3);
+  const int d = (sgs[4 * i] & m0) | (sgs[4 * i + 1] & m1) | (sgs[4 * i + 2] & m2) | (sgs[4 * i + 3] & m3);
+  return (d >> ((nl & 3) * 8)) & 0xFF;
+}
+
+// Issues the loads of one batch.  Every call issues the same instructions whatever the position:
+// k-steps past the end of the slice are clamped to its last k-step and rows past M to row M-1
+// (their products land in k-steps that consume_batch skips and in output rows that are never
+// stored).  With no branch around a load the compiler can count the loads issued after a batch
+// and waits only for that batch when it is consumed, leaving the next one in flight.
 template <int MODE, int NT, int MT, int U>
-__device__ __forceinline__ void load_batch(Batch<NT, MT, U>& b, const GemmParams& p,
-                                           const uint4* wbase, int tb, int tstride, int t1, int ng,
-                                           int nl, int kc) {
+__device__ __forceinline__ void load_batch(Batch<NT, MT, U>& b, const GemmParams& p, int tb,
+                                           int tstride, int t1, int ng, uint32_t lane,
+                                           const uint32_t (&aoff)[MT]) {
   const int ntiles = p.N >> 4;
 #pragma unroll
   for (int u = 0; u < U; ++u) {
-    const int t = tb + tstride * u;
-    const bool live = t < t1;
+    // wave-uniform bases (scalar registers) plus 32-bit lane offsets
+    const int t = min(tb + tstride * u, t1 - 1);
+    const uint4* wt = p.w + ((int64_t)t * ntiles + (int64_t)ng * NT) * 64;
+    const int8_t* at = p.a_q + (int64_t)t * 128;
 #pragma unroll
     for (int i = 0; i < NT; ++i) {
-      b.w[u][i] = make_uint4(0, 0, 0, 0);
-      b.sg[u][i] = 0;
-      if (live) {
-        // streamed once: non-temporal, so the weights do not evict the activations from L2
-        const v4i raw = __builtin_nontemporal_load(
-            reinterpret_cast<const v4i*>(&wbase[((int64_t)t * ntiles + i) * 64]));
-        b.w[u][i] = make_uint4((uint32_t)raw[0], (uint32_t)raw[1], (uint32_t)raw[2], (uint32_t)raw[3]);
-        if constexpr (MODE != kPerChannel)
-          b.sg[u][i] = (int)p.s_g[(int64_t)t * p.N + (int64_t)(ng * NT + i) * 16 + nl];
-      }
+      // streamed once: non-temporal, so the weights do not evict the activations from L2
+      const v4i raw = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(&wt[lane + 64u * i]));
+      b.w[u][i] = make_uint4((uint32_t)raw[0], (uint32_t)raw[1], (uint32_t)raw[2], (uint32_t)raw[3]);
     }
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-      const int m = mt * 16 + nl;
-      b.a[u][mt][0] = (v4i){0, 0, 0, 0};
-      b.a[u][mt][1] = (v4i){0, 0, 0, 0};
-      if (live && m < p.M) {
-        const v4i* ap = (const v4i*)(p.a_q + (int64_t)m * p.K + (int64_t)t * 128 + kc * 16);
-        b.a[u][mt][0] = ap[0];
-        b.a[u][mt][1] = ap[4];  // +64 bytes: second MFMA step of this k-step
-      }
+      b.a[u][mt][0] = *(const v4i*)(at + aoff[mt]);
+      b.a[u][mt][1] = *(const v4i*)(at + aoff[mt] + 64u);  // second MFMA step of this k-step
     }
+    if constexpr (MODE != kPerChannel)
+      load_group_scales<NT>(p.s_g + (int64_t)t * p.N + (int64_t)ng * NT * 16, b.sgs[u]);
   }
+  // keep every load of the batch ahead of the arithmetic that follows (the scheduler would
+  // otherwise sink the scalar loads next to their first use and expose their latency)
+  __builtin_amdgcn_sched_barrier(0);
 }
 
 template <int MODE, int NT, int MT, int U>
 __device__ __forceinline__ void consume_batch(const Batch<NT, MT, U>& b, v4i (&acc)[MT][NT], int tb,
-                                              int tstride, int t1) {
+                                              int tstride, int t1, int nl) {
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     if (tb + tstride * u >= t1) break;
@@ -70,16 +92,18 @@ __device__ __forceinline__ void consume_batch(const Batch<NT, MT, U>& b, v4i (&a
     for (int i = 0; i < NT; ++i) {
       const uint32_t d[4] = {b.w[u][i].x, b.w[u][i].y, b.w[u][i].z, b.w[u][i].w};
       int o[8];
+      int sg = 0;
+      if constexpr (MODE != kPerChannel) sg = pick_group_scale<NT>(b.sgs[u], i, nl);
       if constexpr (MODE == kPerChannel || MODE == kGroupLinear) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) unpack_x16(d[j], o[2 * j], o[2 * j + 1]);
       } else if constexpr (MODE == kGroupClamp) {
-        const _Float16 hs = (_Float16)(float)b.sg[u][i];
+        const _Float16 hs = (_Float16)(float)sg;
         const h2 s2 = {hs, hs};
 #pragma unroll
         for (int j = 0; j < 4; ++j) unpack_group_clamp(d[j], s2, o[2 * j], o[2 * j + 1]);
       } else {
-        const GroupFusedConsts g = make_group_fused(b.sg[u][i]);
+        const GroupFusedConsts g = make_group_fused(sg);
 #pragma unroll
         for (int j = 0; j < 4; ++j) unpack_group_fused(d[j], g, o[2 * j], o[2 * j + 1]);
       }
@@ -93,7 +117,7 @@ __device__ __forceinline__ void consume_batch(const Batch<NT, MT, U>& b, v4i (&a
               __builtin_amdgcn_mfma_i32_16x16x64_i8(b.a[u][mt][0], b0, (v4i){0, 0, 0, 0}, 0, 0, 0);
           part = __builtin_amdgcn_mfma_i32_16x16x64_i8(b.a[u][mt][1], b1, part, 0, 0, 0);
 #pragma unroll
-          for (int r = 0; r < 4; ++r) acc[mt][i][r] += (part[r] >> 4) * b.sg[u][i];
+          for (int r = 0; r < 4; ++r) acc[mt][i][r] += (part[r] >> 4) * sg;
         } else {
           acc[mt][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(b.a[u][mt][0], b0, acc[mt][i], 0, 0, 0);
           acc[mt][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(b.a[u][mt][1], b1, acc[mt][i], 0, 0, 0);
@@ -114,7 +138,10 @@ __global__ __launch_bounds__(W * 64) void gemm_skinny_kernel(const GemmParams p,
   __shared__ int s_last;
 
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63;
+  // the wave index through a scalar register: the k-loop's control flow and the group-scale
+  // addresses are then wave-uniform for the compiler too
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nl = lane & 15, kc = lane >> 4;
   const int T = p.T, N = p.N, M = p.M;
 
@@ -147,20 +174,29 @@ __global__ __launch_bounds__(W * 64) void gemm_skinny_kernel(const GemmParams p,
 #pragma unroll
     for (int i = 0; i < NT; ++i) acc[mt][i] = (v4i){0, 0, 0, 0};
 
-  {
-    const uint4* wbase = p.w + (int64_t)ng * NT * 64 + lane;
+  if (t0 + wave < t1) {  // wave-uniform
     constexpr int kStep = W * U;  // k-steps between consecutive batches of one wave
+    uint32_t aoff[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+      aoff[mt] = (uint32_t)min(mt * 16 + nl, M - 1) * (uint32_t)p.K + (uint32_t)kc * 16u;
     Batch<NT, MT, U> b0, b1;
     int tb = t0 + wave;
-    load_batch<MODE>(b0, p, wbase, tb, W, t1, ng, nl, kc);
-    while (tb < t1) {
-      load_batch<MODE>(b1, p, wbase, tb + kStep, W, t1, ng, nl, kc);
-      consume_batch<MODE>(b0, acc, tb, W, t1);
-      tb += kStep;
-      if (tb >= t1) break;
-      load_batch<MODE>(b0, p, wbase, tb + kStep, W, t1, ng, nl, kc);
-      consume_batch<MODE>(b1, acc, tb, W, t1);
-      tb += kStep;
+    int more = (t1 - tb - 1) / kStep;  // batches after the first
+    load_batch<MODE>(b0, p, tb, W, t1, ng, (uint32_t)lane, aoff);
+    for (; more >= 2; more -= 2) {  // one basic block: load the next batch, consume the current
+      load_batch<MODE>(b1, p, tb + kStep, W, t1, ng, (uint32_t)lane, aoff);
+      consume_batch<MODE>(b0, acc, tb, W, t1, nl);
+      load_batch<MODE>(b0, p, tb + 2 * kStep, W, t1, ng, (uint32_t)lane, aoff);
+      consume_batch<MODE>(b1, acc, tb + kStep, W, t1, nl);
+      tb += 2 * kStep;
+    }
+    if (more == 1) {
+      load_batch<MODE>(b1, p, tb + kStep, W, t1, ng, (uint32_t)lane, aoff);
+      consume_batch<MODE>(b0, acc, tb, W, t1, nl);
+      consume_batch<MODE>(b1, acc, tb + kStep, W, t1, nl);
+    } else {
+      consume_batch<MODE>(b0, acc, tb, W, t1, nl);
     }
   }
 
