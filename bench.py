@@ -5,8 +5,10 @@
                   [--no-cpu-baseline] [--eager]
 
 A step is one pass of the whole hot path over one batch of seeded synthetic input that is
-already resident in HBM: qqq_quant_act on the fp16 activations, then the W4A8 GEMM of the
-workload's variant (weights were repacked once, offline, outside the timed region).  Packed
+already resident in HBM: per-token int8 quantisation of the fp16 activations, then the W4A8 GEMM
+of the workload's variant, through the library's one-call entry point qqq_linear_w4a8_* (for a
+few decode rows that is one fused kernel, otherwise qqq_quant_act's kernel followed by the GEMM
+kernel; weights were repacked once, offline, outside the timed region).  Packed
 weights (and group scales) exist in R copies whose total exceeds four times the 256 MiB
 last-level cache and consecutive steps rotate through them, so every step streams its weights
 from HBM rather than from cache.  The K timed steps are captured once into a HIP graph and
@@ -45,6 +47,16 @@ def quant_bytes(M, K):
     return 2 * M * K + M * K + 4 * M
 
 
+def fused_bytes(M, N, K, pergroup):
+    """Algorithmic bytes of the fused decode kernel: fp16 activations in, no int8 round trip."""
+    return N * K // 2 + (K // 128 * N if pergroup else 0) + 2 * N + 2 * M * K + 2 * M * N
+
+
+def is_fused(M, K):
+    """Shapes for which qqq_linear_* runs the single fused kernel (see include/qqq.h)."""
+    return M <= 4 and M * K <= 8192
+
+
 class Case:
     """Device-resident inputs of one workload plus the launch closures."""
 
@@ -68,9 +80,11 @@ class Case:
         self.s_a = torch.empty((M,), dtype=torch.float32, device="cuda")
         self.y = torch.empty((M, N), dtype=torch.float16, device="cuda")
         self.ws = qqq.new_workspace(M, N, K)
+        self.lws = qqq.new_linear_workspace(M, N, K)
         self.qqq = qqq
         self.ops = 2 * M * N * K
         self.bytes = algorithmic_bytes(M, N, K, self.pg)
+        self.fused = is_fused(M, K)
 
     def quant(self):
         self.qqq.qqq_quant_act(self.a, self.a_q, self.s_a)
@@ -85,8 +99,12 @@ class Case:
                                               y=self.y)
 
     def step(self, i):
-        self.quant()
-        self.gemm(i)
+        r = i % self.copies
+        if self.pg:
+            self.qqq.qqq_linear_w4a8_pergroup(self.a, self.w[r], self.s_g[r], self.s_w, self.lws,
+                                              sg_max=self.wl.sg_hi, y=self.y)
+        else:
+            self.qqq.qqq_linear_w4a8_perchannel(self.a, self.w[r], self.s_w, self.lws, y=self.y)
 
 
 def timed(torch, fn, steps, warmup, use_graph):
@@ -122,17 +140,29 @@ def timed(torch, fn, steps, warmup, use_graph):
     return e0.elapsed_time(e1) / steps, graph is not None
 
 
-def roofline_for(case, gemm_ms):
+def roofline_for(case, step_ms, gemm_ms):
+    """Roofline of the step's dominant kernel: the fused kernel (= the whole step) where
+    qqq_linear_* fuses, the GEMM kernel otherwise."""
     wl = case.wl
-    t_mem = case.bytes / (HBM_PEAK_GBS * 1e9)
+    if case.fused:
+        kernel, kernel_ms = "linear_w4a8_%s (fused quant_act + gemm)" % wl.variant, step_ms
+        nbytes = fused_bytes(wl.M, wl.N, wl.K, case.pg)
+    else:
+        kernel, kernel_ms, nbytes = "gemm_w4a8_%s" % wl.variant, gemm_ms, case.bytes
+    t_mem = nbytes / (HBM_PEAK_GBS * 1e9)
     t_mfma = case.ops / (MFMA_I8_PEAK_TOPS * 1e12)
     if t_mem >= t_mfma:
-        achieved = case.bytes / (gemm_ms * 1e-3) / 1e9
-        return {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+        achieved = nbytes / (kernel_ms * 1e-3) / 1e9
+        roof = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4)}
-    achieved = case.ops / (gemm_ms * 1e-3) / 1e12
-    return {"bound": "mfma", "achieved": round(achieved, 1), "peak": MFMA_I8_PEAK_TOPS,
-            "unit": "TOP/s", "frac": round(achieved / MFMA_I8_PEAK_TOPS, 4)}
+    else:
+        achieved = case.ops / (kernel_ms * 1e-3) / 1e12
+        roof = {"bound": "mfma", "achieved": round(achieved, 1), "peak": MFMA_I8_PEAK_TOPS,
+                "unit": "TOP/s", "frac": round(achieved / MFMA_I8_PEAK_TOPS, 4)}
+    roof["kernel"] = kernel
+    roof["kernel_us"] = round(kernel_ms * 1e3, 3)
+    roof["algorithmic_bytes"] = nbytes
+    return roof
 
 
 def load_traffic(name):
@@ -228,11 +258,8 @@ def main():
     wl = wls[args.workload]
     case = Case(wl, torch, qqq)
     step_ms, gemm_ms, quant_ms, graphed = measure(case, torch, args.steps, args.warmup, use_graph)
-    roof = roofline_for(case, gemm_ms)
+    roof = roofline_for(case, step_ms, gemm_ms)
     roof["traffic"] = load_traffic(wl.name)
-    roof["kernel"] = "gemm_w4a8_%s" % wl.variant
-    roof["kernel_us"] = round(gemm_ms * 1e3, 3)
-    roof["algorithmic_bytes"] = case.bytes
     out = {
         "metric": METRIC, "value": round(case.ops / (step_ms * 1e-3) / 1e12, 4), "unit": "TOPS",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -240,9 +267,12 @@ def main():
         "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": wl.name, "variant": wl.variant, "M": wl.M, "K": wl.K, "N": wl.N,
                    "group": 128 if wl.variant == "pergroup" else None,
-                   "step": "qqq_quant_act + qqq_gemm_w4a8_%s" % wl.variant,
+                   "step": "qqq_linear_w4a8_%s (%s)" % (
+                       wl.variant, "one fused kernel" if case.fused else
+                       "quant_act kernel + gemm kernel"),
                    "weight_copies_rotated": case.copies, "hip_graph": graphed,
-                   "quant_act_us": round(quant_ms * 1e3, 3), "gemm_us": round(gemm_ms * 1e3, 3)},
+                   "separate_quant_act_us": round(quant_ms * 1e3, 3),
+                   "separate_gemm_us": round(gemm_ms * 1e3, 3)},
         "roofline": roof,
     }
     del case
@@ -258,7 +288,7 @@ def main():
             c2 = Case(w2, torch, qqq, rotate_bytes=(1 << 28) if big else (1 << 30))
             st = max(5, min(args.steps, 20 if big else 100))
             s_ms, g_ms, q_ms, _ = measure(c2, torch, st, min(args.warmup, 5), use_graph)
-            r2 = roofline_for(c2, g_ms)
+            r2 = roofline_for(c2, s_ms, g_ms)
             sweep.append({"workload": name, "steps": st, "ms_per_step": round(s_ms, 6),
                           "gemm_us": round(g_ms * 1e3, 3), "quant_act_us": round(q_ms * 1e3, 3),
                           "quant_act_gbs": round(quant_bytes(w2.M, w2.K) / (q_ms * 1e-3) / 1e9, 1),

@@ -100,6 +100,35 @@ int qqq_gemm_w4a8_pergroup(const int8_t* a_q, const float* s_a, const void* w_pa
                            void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Linear layer in one call (Sec. 4.1 per-token activation quantisation feeding Sec. 3.3's W4A8
+ * GEMM): the result is exactly that of qqq_quant_act followed by qqq_gemm_w4a8_perchannel /
+ * qqq_gemm_w4a8_pergroup on the same inputs (acc_out bit-identical, y_fp16 bit-identical).
+ * For a few decode rows (M <= 4 and M*K <= 8192) a single kernel does both: every workgroup
+ * quantises the rows into LDS before streaming its weights, which removes one launch from a
+ * microsecond-scale step.  Otherwise the two kernels run back to back on `stream`, with the
+ * int8 activations and their scales in the workspace.
+ *   a_fp16 [M,lda] fp16, lda >= K, lda % 8 == 0, 16-byte aligned; the other arguments as in the
+ *   GEMM calls.  workspace: qqq_linear_workspace_bytes(M,N,K) bytes, zero-filled once after
+ *   allocation (its split-K part is left zero by every call), never shared by concurrent calls.
+ */
+size_t qqq_linear_workspace_bytes(int64_t M, int64_t N, int64_t K);
+int qqq_linear_w4a8_perchannel(const void* a_fp16, int64_t lda, const void* w_packed,
+                               const void* s_w_fp16, void* y_fp16, int32_t* acc_out, int64_t M,
+                               int64_t N, int64_t K, void* workspace, size_t workspace_bytes,
+                               void* stream);
+int qqq_linear_w4a8_pergroup(const void* a_fp16, int64_t lda, const void* w_packed, const int8_t* s_g,
+                             const void* s_w_fp16, int group, int sg_max, void* y_fp16,
+                             int32_t* acc_out, int64_t M, int64_t N, int64_t K, void* workspace,
+                             size_t workspace_bytes, void* stream);
+
+/*
+ * Tuning/diagnostic knob (host state, not thread-safe): 0 makes the qqq_linear_* calls always
+ * run the two kernels, 1 (default) lets them use the fused decode kernel.  Returns the previous
+ * value.
+ */
+int qqq_set_fused_quant(int enable);
+
+/*
  * Tuning/diagnostic knob (host state, not thread-safe): force a kernel family.
  *   0 = automatic, 1 = skinny split-K kernel, 2 = LDS-tiled prefill kernel.
  * Returns the previous value.  Forcing a family outside its M range gives QQQ_ERR_SHAPE.

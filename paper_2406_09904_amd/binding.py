@@ -18,7 +18,9 @@ GROUP = 128
 SYMBOLS = [
     "qqq_version", "qqq_last_error", "qqq_quant_act", "qqq_packed_w4_bytes", "qqq_pack_w4",
     "qqq_unpack_w4", "qqq_gemm_workspace_bytes", "qqq_gemm_w4a8_perchannel",
-    "qqq_gemm_w4a8_pergroup", "qqq_set_kernel_override", "qqq_set_group_mode_override", "qqq_set_skinny_tuning", "qqq_set_prefill_tuning",
+    "qqq_gemm_w4a8_pergroup", "qqq_linear_workspace_bytes", "qqq_linear_w4a8_perchannel",
+    "qqq_linear_w4a8_pergroup", "qqq_set_fused_quant", "qqq_set_kernel_override",
+    "qqq_set_group_mode_override", "qqq_set_skinny_tuning", "qqq_set_prefill_tuning",
 ]
 
 _lib = None
@@ -52,6 +54,12 @@ def lib():
         L.qqq_gemm_w4a8_perchannel.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, sz, vp]
         L.qqq_gemm_w4a8_pergroup.argtypes = [vp, vp, vp, vp, vp, ci, ci, vp, vp, i64, i64, i64,
                                              vp, sz, vp]
+        L.qqq_linear_workspace_bytes.argtypes = [i64, i64, i64]
+        L.qqq_linear_workspace_bytes.restype = sz
+        L.qqq_linear_w4a8_perchannel.argtypes = [vp, i64, vp, vp, vp, vp, i64, i64, i64, vp, sz, vp]
+        L.qqq_linear_w4a8_pergroup.argtypes = [vp, i64, vp, vp, vp, ci, ci, vp, vp, i64, i64, i64,
+                                               vp, sz, vp]
+        L.qqq_set_fused_quant.argtypes = [ci]
         L.qqq_set_kernel_override.argtypes = [ci]
         L.qqq_set_group_mode_override.argtypes = [ci]
         L.qqq_set_skinny_tuning.argtypes = [ci, ci, ci, ci]
@@ -153,6 +161,54 @@ def qqq_gemm_w4a8_pergroup(a_q, s_a, w_packed, s_g, s_w, workspace, sg_max=0, y=
         _ptr(acc_out, torch.int32), M, N, K, _ptr(workspace, torch.uint8), workspace.numel(),
         _stream()))
     return y
+
+
+def qqq_linear_workspace_bytes(M: int, N: int, K: int) -> int:
+    return int(lib().qqq_linear_workspace_bytes(M, N, K))
+
+
+def new_linear_workspace(M: int, N: int, K: int, device="cuda") -> torch.Tensor:
+    """Zero-filled workspace for the qqq_linear_* calls (zeroed once here)."""
+    return torch.zeros((max(qqq_linear_workspace_bytes(M, N, K), 16),), dtype=torch.uint8, device=device)
+
+
+def _fp16_rows(a_fp16):
+    if a_fp16.dtype != torch.float16 or a_fp16.dim() != 2 or a_fp16.stride(1) != 1:
+        raise ValueError("a_fp16 must be a 2-D fp16 tensor with unit inner stride")
+    if not a_fp16.is_cuda:
+        raise ValueError("libqqq takes device tensors only")
+    M, K = a_fp16.shape
+    lda = a_fp16.stride(0) if M > 1 else max(K, a_fp16.stride(0))
+    return M, K, lda
+
+
+def qqq_linear_w4a8_perchannel(a_fp16, w_packed, s_w, workspace, y=None, acc_out=None):
+    M, K, lda = _fp16_rows(a_fp16)
+    N = s_w.shape[0]
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=a_fp16.device)
+    _check(lib().qqq_linear_w4a8_perchannel(
+        ctypes.c_void_p(a_fp16.data_ptr()), lda, _ptr(w_packed, torch.uint8), _ptr(s_w, torch.float16),
+        _ptr(y, torch.float16), _ptr(acc_out, torch.int32), M, N, K, _ptr(workspace, torch.uint8),
+        workspace.numel(), _stream()))
+    return y
+
+
+def qqq_linear_w4a8_pergroup(a_fp16, w_packed, s_g, s_w, workspace, sg_max=0, y=None, acc_out=None,
+                             group=GROUP):
+    M, K, lda = _fp16_rows(a_fp16)
+    N = s_w.shape[0]
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=a_fp16.device)
+    _check(lib().qqq_linear_w4a8_pergroup(
+        ctypes.c_void_p(a_fp16.data_ptr()), lda, _ptr(w_packed, torch.uint8), _ptr(s_g, torch.int8),
+        _ptr(s_w, torch.float16), group, sg_max, _ptr(y, torch.float16), _ptr(acc_out, torch.int32),
+        M, N, K, _ptr(workspace, torch.uint8), workspace.numel(), _stream()))
+    return y
+
+
+def set_fused_quant(enable: int) -> int:
+    return lib().qqq_set_fused_quant(enable)
 
 
 def set_kernel_override(family: int) -> int:

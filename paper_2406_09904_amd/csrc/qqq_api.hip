@@ -9,6 +9,7 @@ namespace qqq {
 static thread_local char g_err[256] = "no error";
 static int g_override = 0;
 static int g_group_mode = 0;
+static int g_fuse_quant = 1;
 
 int set_error(int code, const char* fmt, ...) {
   va_list ap;
@@ -38,16 +39,26 @@ static bool gemm_shape_ok(int64_t M, int64_t N, int64_t K) {
          K % 128 == 0 && K <= 131072;
 }
 
+// per-group conversion route from the caller's bound on the group scales
+static int group_mode(int sg_max, int64_t M) {
+  int mode = kGroupClamp;
+  if (sg_max >= 1 && sg_max <= 16) mode = (M <= kSkinnyMaxM) ? kGroupLinear : kGroupFused;
+  if (g_group_mode != 0) mode = g_group_mode;
+  return mode;
+}
+
 static size_t ws_rows(int64_t M) { return (size_t)(M < kSkinnyMaxM ? M : kSkinnyMaxM); }
 
 static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed, const int8_t* s_g,
                        const void* s_w, void* y, int32_t* acc_out, int64_t M, int64_t N, int64_t K,
-                       void* workspace, size_t workspace_bytes, void* stream, int mode) {
+                       void* workspace, size_t workspace_bytes, void* stream, int mode,
+                       const void* a_fp16 = nullptr, int64_t lda = 0) {
   if (!gemm_shape_ok(M, N, K))
     return set_error(QQQ_ERR_SHAPE, "gemm: unsupported shape M=%lld N=%lld K=%lld (need N%%16==0, "
                      "K%%128==0, 128<=K<=131072)", (long long)M, (long long)N, (long long)K);
   if (M == 0) return QQQ_OK;
-  if (!a_q || !s_a || !w_packed || !s_w || !y || (mode != kPerChannel && !s_g))
+  const bool fused = a_fp16 != nullptr;  // the decode kernel quantises the rows itself
+  if ((!fused && (!a_q || !s_a)) || !w_packed || !s_w || !y || (mode != kPerChannel && !s_g))
     return set_error(QQQ_ERR_NULL, "gemm: null pointer argument");
   if (!aligned16(a_q) || !aligned16(w_packed) || !aligned16(y) || !aligned16(workspace) ||
       (reinterpret_cast<uintptr_t>(s_a) & 3u) || (reinterpret_cast<uintptr_t>(s_w) & 3u) ||
@@ -73,6 +84,9 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
   p.T = (int)(K / 128);
   p.ws_cnt = nullptr;
   p.ws_acc = nullptr;
+  p.a_fp16 = (const uint4*)a_fp16;
+  p.lda_vec = lda / 8;
+  if (fused && family != 1) return set_error(QQQ_ERR_SHAPE, "gemm: fused quantisation needs the decode kernel");
   if (family == 1) {
     const size_t need = qqq_gemm_workspace_bytes(M, N, K);
     if (!workspace) return set_error(QQQ_ERR_NULL, "gemm: workspace is NULL");
@@ -96,6 +110,39 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
     return launch_gemm_prefill_dma(p, mode, 0, (hipStream_t)stream);
   }
   return launch_gemm_prefill(p, mode, (hipStream_t)stream);
+}
+
+static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+static bool fused_ok(int64_t M, int64_t K) {
+  return g_override == 0 && g_fuse_quant && M >= 1 && M <= kFusedMaxM && M * K <= kFusedLdsBytes;
+}
+
+// quant_act followed by the GEMM; for a few decode rows a single launch that does both
+static int linear_common(const void* a_fp16, int64_t lda, const void* w_packed, const int8_t* s_g,
+                         const void* s_w, void* y, int32_t* acc_out, int64_t M, int64_t N, int64_t K,
+                         void* workspace, size_t workspace_bytes, void* stream, int mode) {
+  if (!gemm_shape_ok(M, N, K))
+    return set_error(QQQ_ERR_SHAPE, "linear: unsupported shape M=%lld N=%lld K=%lld (need N%%16==0, "
+                     "K%%128==0, 128<=K<=131072)", (long long)M, (long long)N, (long long)K);
+  if (lda < K || lda % 8 != 0)
+    return set_error(QQQ_ERR_SHAPE, "linear: lda=%lld must be >= K and a multiple of 8", (long long)lda);
+  if (M == 0) return QQQ_OK;
+  if (!a_fp16 || !workspace) return set_error(QQQ_ERR_NULL, "linear: null pointer argument");
+  if (!aligned16(a_fp16) || !aligned16(workspace))
+    return set_error(QQQ_ERR_SHAPE, "linear: a_fp16 and workspace must be 16-byte aligned");
+  const size_t need = qqq_linear_workspace_bytes(M, N, K);
+  if (workspace_bytes < need)
+    return set_error(QQQ_ERR_WORKSPACE, "linear: workspace %zu bytes < %zu needed", workspace_bytes, need);
+  const size_t gemm_ws = align256(qqq_gemm_workspace_bytes(M, N, K));
+  if (fused_ok(M, K))
+    return gemm_common(nullptr, nullptr, w_packed, s_g, s_w, y, acc_out, M, N, K, workspace, gemm_ws,
+                       stream, mode, a_fp16, lda);
+  float* s_a = (float*)((char*)workspace + gemm_ws);
+  int8_t* a_q = (int8_t*)((char*)workspace + gemm_ws + align256((size_t)M * 4));
+  const int rc = launch_quant_act(a_fp16, M, K, lda, a_q, s_a, (hipStream_t)stream);
+  if (rc != QQQ_OK) return rc;
+  return gemm_common(a_q, s_a, w_packed, s_g, s_w, y, acc_out, M, N, K, workspace, gemm_ws, stream, mode);
 }
 
 }  // namespace qqq
@@ -185,11 +232,38 @@ int qqq_gemm_w4a8_pergroup(const int8_t* a_q, const float* s_a, const void* w_pa
   if (group != QQQ_GROUP) return set_error(QQQ_ERR_SHAPE, "pergroup: group must be 128, got %d", group);
   if (sg_max < 0 || sg_max > 127)
     return set_error(QQQ_ERR_SHAPE, "pergroup: sg_max must be in 0..127, got %d", sg_max);
-  int mode = kGroupClamp;
-  if (sg_max >= 1 && sg_max <= 16) mode = (M <= kSkinnyMaxM) ? kGroupLinear : kGroupFused;
-  if (g_group_mode != 0) mode = g_group_mode;
   return gemm_common(a_q, s_a, w_packed, s_g, s_w_fp16, y_fp16, acc_out, M, N, K, workspace,
-                     workspace_bytes, stream, mode);
+                     workspace_bytes, stream, group_mode(sg_max, M));
+}
+
+size_t qqq_linear_workspace_bytes(int64_t M, int64_t N, int64_t K) {
+  if (!gemm_shape_ok(M, N, K)) return 0;
+  return align256(qqq_gemm_workspace_bytes(M, N, K)) + align256((size_t)M * 4) + (size_t)M * (size_t)K;
+}
+
+int qqq_set_fused_quant(int enable) {
+  const int old = g_fuse_quant;
+  g_fuse_quant = enable ? 1 : 0;
+  return old;
+}
+
+int qqq_linear_w4a8_perchannel(const void* a_fp16, int64_t lda, const void* w_packed,
+                               const void* s_w_fp16, void* y_fp16, int32_t* acc_out, int64_t M,
+                               int64_t N, int64_t K, void* workspace, size_t workspace_bytes,
+                               void* stream) {
+  return linear_common(a_fp16, lda, w_packed, nullptr, s_w_fp16, y_fp16, acc_out, M, N, K, workspace,
+                       workspace_bytes, stream, kPerChannel);
+}
+
+int qqq_linear_w4a8_pergroup(const void* a_fp16, int64_t lda, const void* w_packed, const int8_t* s_g,
+                             const void* s_w_fp16, int group, int sg_max, void* y_fp16,
+                             int32_t* acc_out, int64_t M, int64_t N, int64_t K, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+  if (group != QQQ_GROUP) return set_error(QQQ_ERR_SHAPE, "pergroup: group must be 128, got %d", group);
+  if (sg_max < 0 || sg_max > 127)
+    return set_error(QQQ_ERR_SHAPE, "pergroup: sg_max must be in 0..127, got %d", sg_max);
+  return linear_common(a_fp16, lda, w_packed, s_g, s_w_fp16, y_fp16, acc_out, M, N, K, workspace,
+                       workspace_bytes, stream, group_mode(sg_max, M));
 }
 
 }  // extern "C"

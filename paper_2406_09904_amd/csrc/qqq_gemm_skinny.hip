@@ -21,29 +21,27 @@ template <int NT, int MT, int U>
 struct Batch {
   uint4 w[U][NT];
   v4i a[U][MT][2];
-  int sgs[U][4 * NT];  // wave-uniform: the k-step's 16*NT group-scale bytes
+  int sgv[U];  // word (lane mod 4*NT) of the k-step's 16*NT group-scale bytes
 };
 
-// The 16*NT group scales of one k-step of a wave's channel group are contiguous and the same for
-// the whole wave, so they travel through the scalar (constant) path: no vector-memory
-// instruction, which is the scarce issue slot of this kernel.  The compiler tracks the scalar
-// loads' completion itself, so they stay in flight across the batch like the vector loads.
-typedef const __attribute__((address_space(4))) int* const_int_ptr;
-
+// The 16*NT group scales of one k-step of a wave's channel group are 4*NT contiguous words: lane
+// l requests word l mod 4*NT (one vector-memory instruction for the wave instead of one per
+// tile); when the batch is consumed the words are broadcast from lanes 0..4*NT-1 through scalar
+// registers and each lane picks its byte.
 template <int NT>
-__device__ __forceinline__ void load_group_scales(const int8_t* gp, int (&sgs)[4 * NT]) {
-  const const_int_ptr sp = (const_int_ptr)(uintptr_t)gp;  // gp is wave-uniform
-#pragma unroll
-  for (int j = 0; j < 4 * NT; ++j) sgs[j] = sp[j];
+__device__ __forceinline__ int load_group_scales(const int8_t* gp, uint32_t lane) {
+  return reinterpret_cast<const int*>(gp)[lane & (4u * NT - 1u)];
 }
 
 // lane's scale for tile i: byte 16*i + n%16 of the wave's scale words
 template <int NT>
-__device__ __forceinline__ int pick_group_scale(const int (&sgs)[4 * NT], int i, int nl) {
+__device__ __forceinline__ int pick_group_scale(int sgv, int i, int nl) {
+  const int sgs[4] = {__builtin_amdgcn_readlane(sgv, 4 * i), __builtin_amdgcn_readlane(sgv, 4 * i + 1),
+                      __builtin_amdgcn_readlane(sgv, 4 * i + 2), __builtin_amdgcn_readlane(sgv, 4 * i + 3)};
   // word nl/4 through lane masks (and/or on scalar operands), then byte nl%4
   const int q = nl >> 2;
   const int m0 = -(int)(q == 0), m1 = -(int)(q == 1), m2 = -(int)(q == 2), m3 = -(int)(q == 3);
-  const int d = (sgs[4 * i] & m0) | (sgs[4 * i + 1] & m1) | (sgs[4 * i + 2] & m2) | (sgs[4 * i + 3] & m3);
+  const int d = (sgs[0] & m0) | (sgs[1] & m1) | (sgs[2] & m2) | (sgs[3] & m3);
   return (d >> ((nl & 3) * 8)) & 0xFF;
 }
 
@@ -52,33 +50,56 @@ __device__ __forceinline__ int pick_group_scale(const int (&sgs)[4 * NT], int i,
 // (their products land in k-steps that consume_batch skips and in output rows that are never
 // stored).  With no branch around a load the compiler can count the loads issued after a batch
 // and waits only for that batch when it is consumed, leaving the next one in flight.
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() would also wait for every
+// global load in flight, and here the first weight batches are deliberately still on their way.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 template <int MODE, int NT, int MT, int U>
-__device__ __forceinline__ void load_batch(Batch<NT, MT, U>& b, const GemmParams& p, int tb,
-                                           int tstride, int t1, int ng, uint32_t lane,
-                                           const uint32_t (&aoff)[MT]) {
+__device__ __forceinline__ void load_batch_w(Batch<NT, MT, U>& b, const GemmParams& p, int tb,
+                                             int tstride, int t1, int ng, uint32_t lane) {
   const int ntiles = p.N >> 4;
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     // wave-uniform bases (scalar registers) plus 32-bit lane offsets
     const int t = min(tb + tstride * u, t1 - 1);
     const uint4* wt = p.w + ((int64_t)t * ntiles + (int64_t)ng * NT) * 64;
-    const int8_t* at = p.a_q + (int64_t)t * 128;
 #pragma unroll
     for (int i = 0; i < NT; ++i) {
       // streamed once: non-temporal, so the weights do not evict the activations from L2
       const v4i raw = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(&wt[lane + 64u * i]));
       b.w[u][i] = make_uint4((uint32_t)raw[0], (uint32_t)raw[1], (uint32_t)raw[2], (uint32_t)raw[3]);
     }
+    if constexpr (MODE != kPerChannel)
+      b.sgv[u] = load_group_scales<NT>(p.s_g + (int64_t)t * p.N + (int64_t)ng * NT * 16, lane);
+  }
+}
+
+// abase: the global a_q, or the workgroup's LDS copy in the fused kernel
+template <int NT, int MT, int U>
+__device__ __forceinline__ void load_batch_a(Batch<NT, MT, U>& b, const int8_t* abase, int tb,
+                                             int tstride, int t1, const uint32_t (&aoff)[MT]) {
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int t = min(tb + tstride * u, t1 - 1);
+    const int8_t* at = abase + (int64_t)t * 128;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       b.a[u][mt][0] = *(const v4i*)(at + aoff[mt]);
       b.a[u][mt][1] = *(const v4i*)(at + aoff[mt] + 64u);  // second MFMA step of this k-step
     }
-    if constexpr (MODE != kPerChannel)
-      load_group_scales<NT>(p.s_g + (int64_t)t * p.N + (int64_t)ng * NT * 16, b.sgs[u]);
   }
+}
+
+template <int MODE, int NT, int MT, int U>
+__device__ __forceinline__ void load_batch(Batch<NT, MT, U>& b, const GemmParams& p,
+                                           const int8_t* abase, int tb, int tstride, int t1, int ng,
+                                           uint32_t lane, const uint32_t (&aoff)[MT]) {
+  load_batch_w<MODE>(b, p, tb, tstride, t1, ng, lane);
+  load_batch_a(b, abase, tb, tstride, t1, aoff);
   // keep every load of the batch ahead of the arithmetic that follows (the scheduler would
-  // otherwise sink the scalar loads next to their first use and expose their latency)
+  // otherwise interleave them with the conversion and shorten the time they are in flight)
   __builtin_amdgcn_sched_barrier(0);
 }
 
@@ -93,7 +114,7 @@ __device__ __forceinline__ void consume_batch(const Batch<NT, MT, U>& b, v4i (&a
       const uint32_t d[4] = {b.w[u][i].x, b.w[u][i].y, b.w[u][i].z, b.w[u][i].w};
       int o[8];
       int sg = 0;
-      if constexpr (MODE != kPerChannel) sg = pick_group_scale<NT>(b.sgs[u], i, nl);
+      if constexpr (MODE != kPerChannel) sg = pick_group_scale<NT>(b.sgv[u], i, nl);
       if constexpr (MODE == kPerChannel || MODE == kGroupLinear) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) unpack_x16(d[j], o[2 * j], o[2 * j + 1]);
@@ -127,15 +148,26 @@ __device__ __forceinline__ void consume_batch(const Batch<NT, MT, U>& b, v4i (&a
   }
 }
 
-template <int MODE, int NT, int MT, int W, int U>
+// FUSED: the workgroup quantises the fp16 activation rows itself (Sec. 4.1: per-token absmax
+// scale, division, round half to even) into LDS before the k-loop, with the arithmetic of the
+// stand-alone pass, so a decode step is a single launch.  Every workgroup repeats the M*K
+// conversions, which is only worth it for a few rows; the A operands then come from LDS.
+template <int MODE, int NT, int MT, int W, int U, bool FUSED>
 __global__ __launch_bounds__(W * 64) void gemm_skinny_kernel(const GemmParams p, const int NG,
                                                              const int S) {
   constexpr int kTiles = MT * NT;
   constexpr int kElems = kTiles * 256;          // int32 outputs of the workgroup
   constexpr int kThreads = W * 64;
   constexpr int kPer = (kElems + kThreads - 1) / kThreads;  // outputs per thread after the reduction
-  __shared__ int red[W * kElems];
+  // one LDS buffer: the quantised activations during the k-loop (FUSED), the waves' partial
+  // tiles after it
+  constexpr int kRedInts = W * kElems;
+  constexpr int kSmemInts = (FUSED && kFusedLdsBytes / 4 > kRedInts) ? kFusedLdsBytes / 4 : kRedInts;
+  __shared__ __attribute__((aligned(16))) int smem[kSmemInts];
+  int* const red = smem;
   __shared__ int s_last;
+  __shared__ uint32_t s_amax[kFusedMaxM][W];
+  __shared__ float s_sa[kFusedMaxM];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -152,7 +184,10 @@ __global__ __launch_bounds__(W * 64) void gemm_skinny_kernel(const GemmParams p,
 
   // this thread's output elements after the cross-wave sum: element e of [tile][r][lane]
   int row[kPer], col[kPer];
-  float sa[kPer], sw[kPer];
+  // The epilogue's scales are requested now, with clamped indices and no arithmetic on them (the
+  // fp16 stays raw bits), so nothing here waits for memory and the epilogue does not either.
+  float sa[kPer];
+  uint32_t sw_bits[kPer];
 #pragma unroll
   for (int j = 0; j < kPer; ++j) {
     const int e = tid + kThreads * j;
@@ -161,11 +196,88 @@ __global__ __launch_bounds__(W * 64) void gemm_skinny_kernel(const GemmParams p,
     col[j] = (ng * NT + i) * 16 + (le & 15);
     row[j] = (e < kElems) ? mt * 16 + 4 * (le >> 4) + r : M;  // M = "no output"
     sa[j] = 0.0f;
-    sw[j] = 0.0f;
-    if (row[j] < M) {  // scales fetched now so the epilogue does not wait on memory
-      sa[j] = p.s_a[row[j]];
-      sw[j] = (float)p.s_w[col[j]];
+    if constexpr (!FUSED) sa[j] = p.s_a[min(row[j], M - 1)];
+    sw_bits[j] = reinterpret_cast<const uint16_t*>(p.s_w)[min(col[j], N - 1)];
+  }
+
+  constexpr int kStep = W * U;  // k-steps between consecutive batches of one wave
+  Batch<NT, MT, U> b0, b1;
+  const int8_t* abase = p.a_q;
+  if constexpr (FUSED) {
+    // host guarantees M <= kFusedMaxM and M*K <= kFusedLdsBytes
+    constexpr int kVPT = kFusedLdsBytes / 8 / kThreads;  // 128-bit fp16 vectors per thread
+    static_assert(kVPT >= 1 && kVPT * kThreads * 8 == kFusedLdsBytes, "fused path sized for 8 waves");
+    const int nvec = p.K >> 3;  // 128-bit vectors of 8 fp16 per row
+    const int total = M * nvec;
+    uint2* const aq_lds = reinterpret_cast<uint2*>(smem);
+    {
+      // The rows stay in registers between the |max| pass and the division.  Every thread issues
+      // all kVPT loads (positions past the end re-read some earlier vector, spread over many
+      // addresses) and then the first two batches of weights, with no branch in between: the
+      // rows return first and are quantised while the weights are still on their way.
+      uint4 v[kVPT];
+      int vm[kVPT];
+      const int wrap = (1 << (31 - __builtin_clz(total))) - 1;  // largest 2^k <= total, minus 1
+#pragma unroll
+      for (int j = 0; j < kVPT; ++j) {
+        const int raw = tid + kThreads * j;
+        const int idx = raw < total ? raw : (raw & wrap);
+        vm[j] = idx / nvec;
+        v[j] = p.a_fp16[(int64_t)vm[j] * p.lda_vec + (idx - vm[j] * nvec)];
+      }
+      load_batch_w<MODE>(b0, p, t0 + wave, W, t1, ng, (uint32_t)lane);
+      __builtin_amdgcn_sched_barrier(0);  // request order = consumption order, as in the k-loop
+      load_batch_w<MODE>(b1, p, t0 + wave + kStep, W, t1, ng, (uint32_t)lane);
+      __builtin_amdgcn_sched_barrier(0);  // all requests are out before any arithmetic on the rows
+      uint32_t am[kFusedMaxM];
+#pragma unroll
+      for (int m = 0; m < kFusedMaxM; ++m) am[m] = 0;
+#pragma unroll
+      for (int j = 0; j < kVPT; ++j) {
+        const uint32_t bits = absmax_bits(v[j], 0);
+#pragma unroll
+        for (int m = 0; m < kFusedMaxM; ++m) am[m] = max(am[m], vm[j] == m ? bits : 0u);
+      }
+#pragma unroll
+      for (int m = 0; m < kFusedMaxM; ++m) {
+        am[m] = wave_max_u32(am[m]);
+        if (lane == 0) s_amax[m][wave] = am[m];
+      }
+      lds_barrier();
+      float amax[kFusedMaxM], sc[kFusedMaxM];
+#pragma unroll
+      for (int m = 0; m < kFusedMaxM; ++m) {
+        uint32_t bits = 0;
+#pragma unroll
+        for (int w = 0; w < W; ++w) bits = max(bits, s_amax[m][w]);
+        amax[m] = half_bits_to_float(bits);
+        sc[m] = amax[m] / 127.0f;
+        if (tid == 0 && m < M) s_sa[m] = (amax[m] == 0.0f) ? 0.0f : sc[m];
+      }
+#pragma unroll
+      for (int j = 0; j < kVPT; ++j) {
+        const int idx = tid + kThreads * j;
+        float a_m = amax[0], s_m = sc[0];
+#pragma unroll
+        for (int m = 1; m < kFusedMaxM; ++m) {
+          a_m = (vm[j] == m) ? amax[m] : a_m;
+          s_m = (vm[j] == m) ? sc[m] : s_m;
+        }
+        if (idx < total) {
+          uint2 o = make_uint2(0, 0);
+          if (a_m != 0.0f) {
+            o.x = quant4(v[j].x, v[j].y, s_m);
+            o.y = quant4(v[j].z, v[j].w, s_m);
+          }
+          aq_lds[idx] = o;  // rows are contiguous in LDS: row m starts at byte m*K
+        }
+      }
     }
+    lds_barrier();
+#pragma unroll
+    for (int j = 0; j < kPer; ++j)
+      if (row[j] < M) sa[j] = s_sa[row[j]];
+    abase = reinterpret_cast<const int8_t*>(smem);
   }
 
   v4i acc[MT][NT];
@@ -175,32 +287,54 @@ __global__ __launch_bounds__(W * 64) void gemm_skinny_kernel(const GemmParams p,
     for (int i = 0; i < NT; ++i) acc[mt][i] = (v4i){0, 0, 0, 0};
 
   if (t0 + wave < t1) {  // wave-uniform
-    constexpr int kStep = W * U;  // k-steps between consecutive batches of one wave
     uint32_t aoff[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
       aoff[mt] = (uint32_t)min(mt * 16 + nl, M - 1) * (uint32_t)p.K + (uint32_t)kc * 16u;
-    Batch<NT, MT, U> b0, b1;
     int tb = t0 + wave;
     int more = (t1 - tb - 1) / kStep;  // batches after the first
-    load_batch<MODE>(b0, p, tb, W, t1, ng, (uint32_t)lane, aoff);
-    for (; more >= 2; more -= 2) {  // one basic block: load the next batch, consume the current
-      load_batch<MODE>(b1, p, tb + kStep, W, t1, ng, (uint32_t)lane, aoff);
+    if constexpr (FUSED) {
+      // the weights of the first two batches were requested before the prologue (the second is a
+      // clamped repeat when the wave has a single batch and is then never consumed)
+      load_batch_a(b0, abase, tb, W, t1, aoff);
+      load_batch_a(b1, abase, tb + kStep, W, t1, aoff);
+      __builtin_amdgcn_sched_barrier(0);
+      for (; more >= 3; more -= 2) {  // one basic block: consume a batch, request the one after next
+        consume_batch<MODE>(b0, acc, tb, W, t1, nl);
+        load_batch<MODE>(b0, p, abase, tb + 2 * kStep, W, t1, ng, (uint32_t)lane, aoff);
+        consume_batch<MODE>(b1, acc, tb + kStep, W, t1, nl);
+        load_batch<MODE>(b1, p, abase, tb + 3 * kStep, W, t1, ng, (uint32_t)lane, aoff);
+        tb += 2 * kStep;
+      }
       consume_batch<MODE>(b0, acc, tb, W, t1, nl);
-      load_batch<MODE>(b0, p, tb + 2 * kStep, W, t1, ng, (uint32_t)lane, aoff);
-      consume_batch<MODE>(b1, acc, tb + kStep, W, t1, nl);
-      tb += 2 * kStep;
-    }
-    if (more == 1) {
-      load_batch<MODE>(b1, p, tb + kStep, W, t1, ng, (uint32_t)lane, aoff);
-      consume_batch<MODE>(b0, acc, tb, W, t1, nl);
-      consume_batch<MODE>(b1, acc, tb + kStep, W, t1, nl);
+      if (more == 2) {
+        load_batch<MODE>(b0, p, abase, tb + 2 * kStep, W, t1, ng, (uint32_t)lane, aoff);
+        consume_batch<MODE>(b1, acc, tb + kStep, W, t1, nl);
+        consume_batch<MODE>(b0, acc, tb + 2 * kStep, W, t1, nl);
+      } else if (more == 1) {
+        consume_batch<MODE>(b1, acc, tb + kStep, W, t1, nl);
+      }
     } else {
-      consume_batch<MODE>(b0, acc, tb, W, t1, nl);
+      load_batch<MODE>(b0, p, abase, tb, W, t1, ng, (uint32_t)lane, aoff);
+      for (; more >= 2; more -= 2) {  // one basic block: load the next batch, consume the current
+        load_batch<MODE>(b1, p, abase, tb + kStep, W, t1, ng, (uint32_t)lane, aoff);
+        consume_batch<MODE>(b0, acc, tb, W, t1, nl);
+        load_batch<MODE>(b0, p, abase, tb + 2 * kStep, W, t1, ng, (uint32_t)lane, aoff);
+        consume_batch<MODE>(b1, acc, tb + kStep, W, t1, nl);
+        tb += 2 * kStep;
+      }
+      if (more == 1) {
+        load_batch<MODE>(b1, p, abase, tb + kStep, W, t1, ng, (uint32_t)lane, aoff);
+        consume_batch<MODE>(b0, acc, tb, W, t1, nl);
+        consume_batch<MODE>(b1, acc, tb + kStep, W, t1, nl);
+      } else {
+        consume_batch<MODE>(b0, acc, tb, W, t1, nl);
+      }
     }
   }
 
   // ---- sum the waves' tiles in LDS: red[wave][tile][r][lane]
+  if constexpr (FUSED) __syncthreads();  // every wave is done reading the activations in smem
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -243,7 +377,7 @@ __global__ __launch_bounds__(W * 64) void gemm_skinny_kernel(const GemmParams p,
       int v = val[j];
       if constexpr (MODE == kPerChannel) v >>= 4;  // exact: the sum is a multiple of 16
       const int64_t o = (int64_t)row[j] * N + col[j];
-      p.y[o] = dequant(v, sa[j], sw[j]);
+      p.y[o] = dequant(v, sa[j], half_bits_to_float(sw_bits[j]));
       if (p.acc_out) p.acc_out[o] = v;
     }
   }
@@ -257,12 +391,12 @@ void set_skinny_tuning(int nt, int s, int w, int u) {
   g_tune_u = u;
 }
 
-template <int MODE, int NT, int MT, int W, int U>
+template <int MODE, int NT, int MT, int W, int U, bool FUSED = false>
 static int launch_one(const GemmParams& p, int S, hipStream_t st) {
   const int NG = p.N / (16 * NT);
   const int64_t grid = (int64_t)NG * S;
-  hipLaunchKernelGGL((gemm_skinny_kernel<MODE, NT, MT, W, U>), dim3((unsigned)grid), dim3(W * 64), 0,
-                     st, p, NG, S);
+  hipLaunchKernelGGL((gemm_skinny_kernel<MODE, NT, MT, W, U, FUSED>), dim3((unsigned)grid),
+                     dim3(W * 64), 0, st, p, NG, S);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return set_error(QQQ_ERR_HIP, "skinny gemm launch: %s", hipGetErrorString(e));
   return QQQ_OK;
@@ -305,6 +439,14 @@ static int launch_mode(const GemmParams& p, hipStream_t st) {
   if (g_tune_nt > 0 && mt * g_tune_nt <= 4 && p.N % (16 * g_tune_nt) == 0) nt = g_tune_nt;
   if (g_tune_s > 0 && g_tune_s <= p.T) S = g_tune_s;
   if (g_tune_w > 0) w = g_tune_w;
+  if (p.a_fp16 != nullptr) {
+    // fused activation quantisation: one row tile, 8 waves, default batch depth
+    if (mt != 1 || p.M > kFusedMaxM || (int64_t)p.M * p.K > kFusedLdsBytes)
+      return set_error(QQQ_ERR_SHAPE, "fused decode kernel: M=%d K=%d out of range", p.M, p.K);
+    if (nt == 4) return launch_one<MODE, 4, 1, 8, 1, true>(p, S, st);
+    if (nt == 2) return launch_one<MODE, 2, 1, 8, 2, true>(p, S, st);
+    return launch_one<MODE, 1, 1, 8, 4, true>(p, S, st);
+  }
   if (mt <= 1) {
     // k-steps per batch of loads: two batches are in flight, so "deep" keeps 4 (NT=4), 8 (NT=2)
     // or 16 (NT=1) KiB per wave outstanding

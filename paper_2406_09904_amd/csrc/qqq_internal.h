@@ -32,6 +32,9 @@ struct GemmParams {
   int32_t* ws_cnt;      // [N/16] arrival counters (zero between calls)
   int32_t* ws_acc;      // [ws_rows,N] split-K partial sums (zero between calls)
   int M, N, K, T;       // T = K/128
+  // fused activation quantisation (decode kernel only): fp16 rows instead of a_q/s_a
+  const uint4* a_fp16;  // [M, lda] fp16 as 128-bit vectors, or nullptr
+  int64_t lda_vec;      // row stride of a_fp16 in 128-bit vectors
 };
 
 // host-side helpers (qqq_api.hip)
@@ -51,6 +54,8 @@ int get_prefill_tuning();
 int launch_gemm_prefill_dma(const GemmParams& p, int mode, int shape, hipStream_t st);
 int launch_gemm_prefill_ring(const GemmParams& p, int mode, hipStream_t st);
 
+constexpr int kFusedMaxM = 4;          // rows the decode kernel quantises itself (fused path)
+constexpr int kFusedLdsBytes = 8192;   // most activations the fused path quantises: M*K int8 in LDS
 constexpr int kSkinnyMaxM = 64;  // rows the split-K kernel handles (4 MFMA row tiles)
 
 // ---------------------------------------------------------------------------------------------
@@ -128,6 +133,52 @@ __device__ __forceinline__ void unpack_group_fused(uint32_t x, const GroupFusedC
   // v_perm_b32: selector bytes 0-3 pick from the second source, 4-7 from the first
   lo = (int)__builtin_amdgcn_perm(as_u32(f2), as_u32(f0), 0x06020400u);
   hi = (int)__builtin_amdgcn_perm(as_u32(f3), as_u32(f1), 0x06020400u);
+}
+
+// ---- per-token activation quantisation arithmetic (Sec. 4.1), shared by the stand-alone pass
+// ---- and the decode kernel's fused prologue so both produce the same bits
+__device__ __forceinline__ float half_bits_to_float(uint32_t h16) {
+  return (float)__builtin_bit_cast(_Float16, (uint16_t)h16);
+}
+
+// |max| over the 8 fp16 values of a 128-bit vector, on the bit patterns (for finite values the
+// magnitude order of fp16 equals the integer order of the bits with the sign cleared)
+__device__ __forceinline__ uint32_t absmax_bits(uint4 v, uint32_t cur) {
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t lo = w[i] & 0x7FFFu, hi = (w[i] >> 16) & 0x7FFFu;
+    cur = max(cur, max(lo, hi));
+  }
+  return cur;
+}
+
+// Maximum over the 64 lanes of a wave, in every lane (wave-uniform result).  Data-parallel
+// primitives inside the 16-lane rows, then the four row results through scalar registers: no
+// LDS-crossbar shuffles, whose latency would dominate a microsecond-scale prologue.
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, false));  // row_half_mirror
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xF, 0xF, false));  // row_mirror
+  const uint32_t r0 = (uint32_t)__builtin_amdgcn_readlane((int)v, 0);
+  const uint32_t r1 = (uint32_t)__builtin_amdgcn_readlane((int)v, 16);
+  const uint32_t r2 = (uint32_t)__builtin_amdgcn_readlane((int)v, 32);
+  const uint32_t r3 = (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
+  return max(max(r0, r1), max(r2, r3));
+}
+
+__device__ __forceinline__ uint32_t quant4(uint32_t w0, uint32_t w1, float s) {
+  // four fp16 values (two dwords) -> four int8 codes packed in one dword
+  const float x0 = half_bits_to_float(w0 & 0xFFFFu), x1 = half_bits_to_float(w0 >> 16);
+  const float x2 = half_bits_to_float(w1 & 0xFFFFu), x3 = half_bits_to_float(w1 >> 16);
+  // IEEE fp32 division (never a reciprocal multiply), then round half to even, then the guard clamp
+  const int q0 = (int)fminf(fmaxf(__builtin_rintf(x0 / s), -127.0f), 127.0f);
+  const int q1 = (int)fminf(fmaxf(__builtin_rintf(x1 / s), -127.0f), 127.0f);
+  const int q2 = (int)fminf(fmaxf(__builtin_rintf(x2 / s), -127.0f), 127.0f);
+  const int q3 = (int)fminf(fmaxf(__builtin_rintf(x3 / s), -127.0f), 127.0f);
+  return (uint32_t)(q0 & 0xFF) | ((uint32_t)(q1 & 0xFF) << 8) | ((uint32_t)(q2 & 0xFF) << 16) |
+         ((uint32_t)(q3 & 0xFF) << 24);
 }
 
 // Dequant (Sec. 3.3.1/3.3.2 last step): int32 -> fp32 -> two fp32 multiplies -> fp16 (RNE).

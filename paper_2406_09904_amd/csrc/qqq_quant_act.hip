@@ -6,38 +6,8 @@
 
 namespace qqq {
 
-__device__ __forceinline__ float half_bits_to_float(uint32_t h16) {
-  return (float)__builtin_bit_cast(_Float16, (uint16_t)h16);
-}
-
-// |max| over the 8 fp16 values of a 128-bit vector, on the bit patterns (for finite values the
-// magnitude order of fp16 equals the integer order of the bits with the sign cleared)
-__device__ __forceinline__ uint32_t absmax_bits(uint4 v, uint32_t cur) {
-  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const uint32_t lo = w[i] & 0x7FFFu, hi = (w[i] >> 16) & 0x7FFFu;
-    cur = max(cur, max(lo, hi));
-  }
-  return cur;
-}
-
-__device__ __forceinline__ uint32_t quant4(uint32_t w0, uint32_t w1, float s) {
-  // four fp16 values (two dwords) -> four int8 codes packed in one dword
-  const float x0 = half_bits_to_float(w0 & 0xFFFFu), x1 = half_bits_to_float(w0 >> 16);
-  const float x2 = half_bits_to_float(w1 & 0xFFFFu), x3 = half_bits_to_float(w1 >> 16);
-  // IEEE fp32 division (never a reciprocal multiply), then round half to even, then the guard clamp
-  const int q0 = (int)fminf(fmaxf(__builtin_rintf(x0 / s), -127.0f), 127.0f);
-  const int q1 = (int)fminf(fmaxf(__builtin_rintf(x1 / s), -127.0f), 127.0f);
-  const int q2 = (int)fminf(fmaxf(__builtin_rintf(x2 / s), -127.0f), 127.0f);
-  const int q3 = (int)fminf(fmaxf(__builtin_rintf(x3 / s), -127.0f), 127.0f);
-  return (uint32_t)(q0 & 0xFF) | ((uint32_t)(q1 & 0xFF) << 8) | ((uint32_t)(q2 & 0xFF) << 16) |
-         ((uint32_t)(q3 & 0xFF) << 24);
-}
-
 __device__ __forceinline__ uint32_t block_max_u32(uint32_t v, uint32_t* smem) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v = max(v, (uint32_t)__shfl_xor((int)v, off, 64));
+  v = wave_max_u32(v);
   const int wave = threadIdx.x >> 6;
   if ((threadIdx.x & 63) == 0) smem[wave] = v;
   __syncthreads();

@@ -42,6 +42,10 @@ def test_size_queries(L):
     ws = L.qqq_gemm_workspace_bytes(16, 4096, 4096)
     assert ws >= 16 * 4096 * 4 + 4096 // 16 * 4
     assert L.qqq_gemm_workspace_bytes(1, 4097, 4096) == 0
+    # linear workspace = GEMM workspace + fp32 token scales + int8 activations (256-byte aligned parts)
+    lw = L.qqq_linear_workspace_bytes(16, 4096, 4096)
+    assert lw >= ws + 16 * 4 + 16 * 4096 and lw <= ws + 16 * 4 + 16 * 4096 + 512
+    assert L.qqq_linear_workspace_bytes(1, 4096, 4097) == 0
     assert L.qqq_version() >= 100
 
 
@@ -69,6 +73,19 @@ def test_host_side_argument_errors(L):
     assert L.qqq_gemm_w4a8_pergroup(bad, bad, bad, None, bad, 128, 0, bad, None, 4, 128, 128, bad,
                                     1 << 20, None) == 1
     assert b"workspace" in L.qqq_last_error() or len(L.qqq_last_error()) > 0
+    # one-call linear layer: fp16 rows in, same validation order (shape, null, alignment, workspace)
+    lin = (bad, bad, bad, None)                       # w_packed, s_w, y, acc_out
+    assert L.qqq_linear_w4a8_perchannel(bad, 128, *lin, 4, 100, 128, bad, 1 << 20, None) == 2
+    assert L.qqq_linear_w4a8_perchannel(bad, 64, *lin, 4, 128, 128, bad, 1 << 20, None) == 2   # lda < K
+    assert L.qqq_linear_w4a8_perchannel(bad, 132, *lin, 4, 128, 128, bad, 1 << 20, None) == 2  # lda % 8
+    assert L.qqq_linear_w4a8_perchannel(None, 128, *lin, 4, 128, 128, bad, 1 << 20, None) == 1
+    assert L.qqq_linear_w4a8_perchannel(bad, 128, *lin, 4, 128, 128, None, 0, None) == 1
+    assert L.qqq_linear_w4a8_perchannel(bad, 128, *lin, 4, 128, 128, bad, 16, None) == 3
+    assert L.qqq_linear_w4a8_perchannel(bad, 128, *lin, 0, 128, 128, None, 0, None) == 0       # M == 0
+    assert L.qqq_linear_w4a8_pergroup(bad, 128, bad, bad, bad, 64, 0, bad, None, 4, 128, 128, bad,
+                                      1 << 20, None) == 2                                      # group
+    assert L.qqq_linear_w4a8_pergroup(bad, 128, bad, bad, bad, 128, 128, bad, None, 4, 128, 128, bad,
+                                      1 << 20, None) == 2                                      # sg_max
 
 
 def test_binding_refuses_cpu_tensors():

@@ -1,0 +1,150 @@
+"""GPU parity of the one-call linear layer (activation quantisation + W4A8 GEMM) against the
+CPU oracle's quant_act -> gemm pipeline.
+
+Bars as for the separate calls: int32 accumulators bit-exact, fp16 outputs within 1 fp16 ulp.
+The fused decode kernel (few rows) and the two-kernel route must also agree with each other
+bit for bit, since they share the quantisation arithmetic.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import qqq_oracle as orc
+from paper_2406_09904_amd import binding as qqq
+from paper_2406_09904_amd import synth
+from tests.util import f16_bits, to_dev, ulp_distance
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def _reset_overrides():
+    yield
+    qqq.set_fused_quant(1)
+    qqq.set_group_mode_override(0)
+    qqq.set_skinny_tuning(0, 0, 0, 0)
+
+
+def run_linear(a, w_nat, s_w, K, s_g=None, sg_max=0, fused=1, d_a=None):
+    M, N = a.shape[0], w_nat.shape[0]
+    if d_a is None:
+        d_a = to_dev(a.view(np.uint16), torch)
+    d_w = qqq.qqq_pack_w4(to_dev(w_nat, torch), K)
+    d_sw = to_dev(s_w.view(np.uint16), torch)
+    ws = qqq.new_linear_workspace(M, N, K)
+    gemm_ws_bytes = qqq.qqq_gemm_workspace_bytes(M, N, K)
+    acc = torch.full((M, N), -12345, dtype=torch.int32, device="cuda")
+    qqq.set_fused_quant(fused)
+    if s_g is None:
+        y = qqq.qqq_linear_w4a8_perchannel(d_a, d_w, d_sw, ws, acc_out=acc)
+    else:
+        y = qqq.qqq_linear_w4a8_pergroup(d_a, d_w, to_dev(s_g, torch), d_sw, ws, sg_max=sg_max, acc_out=acc)
+    torch.cuda.synchronize()
+    assert not ws[:gemm_ws_bytes].any(), "split-K part of the workspace not returned to zero"
+    return acc.cpu().numpy(), f16_bits(y)
+
+
+def oracle_linear(a, w_nat, s_w, s_g=None):
+    a_q, s_a = orc.quant_act(a.view(np.uint16))
+    if s_g is None:
+        acc, _, y = orc.gemm_perchannel(a_q, s_a, w_nat, s_w.view(np.uint16))
+    else:
+        acc, _, y = orc.gemm_pergroup(a_q, s_a, w_nat, s_g, s_w.view(np.uint16))
+    return acc, y
+
+
+def check(acc, y, o_acc, o_y):
+    assert np.array_equal(acc, o_acc), "int32 accumulators differ: %d of %d" % (
+        int((acc != o_acc).sum()), acc.size)
+    d = ulp_distance(y, o_y)
+    assert d.max() <= 1, "fp16 output off by %d ulp" % int(d.max())
+
+
+# M <= 4 with M*K <= 8192 takes the fused kernel; the rest the two-kernel route
+SHAPES = [(1, 128, 16), (1, 4096, 1024), (2, 1152, 272), (3, 2688, 208), (4, 2048, 4096),
+          (1, 8192, 48), (1, 5120, 13824), (2, 4096, 32), (2, 4224, 64), (1, 8320, 64),
+          (3, 5120, 208), (1, 65536, 48), (5, 1024, 256), (16, 4096, 512), (70, 1024, 512),
+          (200, 384, 528)]
+
+
+@pytest.mark.parametrize("M,K,N", SHAPES)
+def test_linear_perchannel(M, K, N):
+    a = synth.activations_fp16(M, K, 31 * M + K + N)
+    if M >= 3:
+        a[1, :] = 0                                # all-zero token: scale 0, output 0
+    w = synth.random_w_nat(N, K, 5 + N)
+    s_w = synth.weight_scales_fp16(N, 6 + N, 0.005, 0.02)
+    o_acc, o_y = oracle_linear(a, w, s_w)
+    acc, y = run_linear(a, w, s_w, K)
+    check(acc, y, o_acc, o_y)
+    acc2, y2 = run_linear(a, w, s_w, K, fused=0)
+    assert np.array_equal(acc, acc2) and np.array_equal(y, y2)
+
+
+@pytest.mark.parametrize("M,K,N", SHAPES)
+@pytest.mark.parametrize("hi,sg_max", [(15, 15), (16, 16), (127, 0)])
+def test_linear_pergroup(M, K, N, hi, sg_max):
+    a = synth.activations_fp16(M, K, 17 * M + K + N + hi)
+    w = synth.random_w_nat(N, K, 7 + N)
+    s_g = synth.group_scales(K, N, 8 + N, 1, hi)
+    s_w = synth.weight_scales_fp16(N, 9 + N, 0.001, 0.005)
+    o_acc, o_y = oracle_linear(a, w, s_w, s_g)
+    acc, y = run_linear(a, w, s_w, K, s_g=s_g, sg_max=sg_max)
+    check(acc, y, o_acc, o_y)
+    acc2, y2 = run_linear(a, w, s_w, K, s_g=s_g, sg_max=sg_max, fused=0)
+    assert np.array_equal(acc, acc2) and np.array_equal(y, y2)
+
+
+@pytest.mark.parametrize("group_mode", [1, 2, 3])
+def test_linear_fused_every_group_route(group_mode):
+    M, K, N = 3, 2560, 336            # fused: 7680 activations
+    a = synth.activations_fp16(M, K, 77)
+    w = synth.random_w_nat(N, K, 78)
+    s_g = synth.group_scales(K, N, 79, 1, 16)
+    s_w = synth.weight_scales_fp16(N, 80, 0.001, 0.005)
+    o_acc, o_y = oracle_linear(a, w, s_w, s_g)
+    qqq.set_group_mode_override(group_mode)
+    acc, y = run_linear(a, w, s_w, K, s_g=s_g, sg_max=16)
+    check(acc, y, o_acc, o_y)
+
+
+@pytest.mark.parametrize("nt,S", [(1, 1), (2, 1), (4, 1), (1, 3), (4, 4), (2, 7)])
+def test_linear_fused_launch_shapes(nt, S):
+    """Every channel-group width and K split of the fused kernel gives the same integers."""
+    M, K, N = 2, 3584, 448            # fused: 7168 activations
+    a = synth.activations_fp16(M, K, 91)
+    w = synth.random_w_nat(N, K, 92)
+    s_w = synth.weight_scales_fp16(N, 93, 0.005, 0.02)
+    o_acc, o_y = oracle_linear(a, w, s_w)
+    qqq.set_skinny_tuning(nt, S, 0, 0)
+    acc, y = run_linear(a, w, s_w, K)
+    check(acc, y, o_acc, o_y)
+
+
+def test_linear_row_stride_and_extremes():
+    M, K, N = 4, 1024, 128            # fused
+    wide = synth.activations_fp16(M, 2 * K, 3)
+    wide[0, :K] = np.float16(65504.0)
+    wide[0, 1:K:2] = np.float16(-65504.0)
+    wide[2, :K] = np.float16(2.0 ** -24)
+    wide[3, :K] = 0
+    wide[3, 7] = np.float16(-3.0)
+    a = np.ascontiguousarray(wide[:, :K])
+    w = synth.random_w_nat(N, K, 4)
+    s_w = synth.weight_scales_fp16(N, 5, 0.0001, 0.0002)
+    o_acc, o_y = oracle_linear(a, w, s_w)
+    d_wide = to_dev(wide.view(np.uint16), torch)
+    acc, y = run_linear(a, w, s_w, K, d_a=d_wide[:, :K])
+    check(acc, y, o_acc, o_y)
+
+
+def test_linear_argument_errors():
+    M, K, N = 2, 256, 32
+    a = to_dev(synth.activations_fp16(M, K, 1).view(np.uint16), torch)
+    w = qqq.qqq_pack_w4(to_dev(synth.random_w_nat(N, K, 2), torch), K)
+    s_w = to_dev(synth.weight_scales_fp16(N, 3, 0.005, 0.02).view(np.uint16), torch)
+    small = torch.zeros((16,), dtype=torch.uint8, device="cuda")
+    with pytest.raises(qqq.QQQError) as e:
+        qqq.qqq_linear_w4a8_perchannel(a, w, s_w, small)
+    assert e.value.code == 3
+    assert qqq.qqq_linear_workspace_bytes(M, N, K + 1) == 0
