@@ -14,7 +14,12 @@
  *               per-group:   int4 code times the fused per-group scale, as int8
  *                            (FusedDequantQuant followed by the FP16->INT8 step)
  *                            [Sec. 3.3.2, Fig. 4-6]; here the fused scale is an
- *                            integer and the product saturates to [-128,127]
+ *                            integer and the product saturates to [-128,127];
+ *                            the "_f16" functions take the paper's real-valued fp16
+ *                            fused scale s*_Wg = s_Wg / s_Wc instead and follow the
+ *                            steps of Sec. 3.3.2 (FastINT4toFP16, one fp16 FMA that
+ *                            multiplies by the scale and adds 128 + 1024, low byte,
+ *                            XOR 0x80), with no saturation, as the paper describes
  *   acc         INT8 GEMM with an integer accumulator wide enough not to overflow
  *               [Sec. 3.3, second consideration]
  *   Y           Dequant: acc * s_A[m] * s_W[n] (per-group: s_Wc[n]) -> fp16
@@ -248,6 +253,69 @@ int qqq_oracle_gemm_pergroup(const int8_t* a_q, const float* s_a, const uint32_t
   int8_t* w8 = (int8_t*)malloc((size_t)N * (size_t)K);
   if (!w8) return ORC_SHAPE;
   int rc = qqq_oracle_w8_pergroup(w_nat, s_g, N, K, group, w8);
+  if (rc == ORC_OK) rc = gemm_common(a_q, s_a, w8, s_w_fp16, M, N, K, acc32, y32, y_fp16);
+  free(w8);
+  return rc;
+}
+
+/* ---------- Sec. 3.3.2 with the paper's real-valued fused scale ---------- */
+
+/* double -> fp16 bits, round to nearest even, overflow to infinity, subnormals kept.
+ * Scaling by a power of two is exact, so one rint() (default rounding mode: nearest
+ * even) is the only rounding. */
+uint16_t qqq_oracle_double_to_half(double x) {
+  const uint16_t sign = signbit(x) ? 0x8000u : 0u;
+  double a = fabs(x);
+  if (isnan(a)) return (uint16_t)(sign | 0x7E00u);
+  if (a >= 65520.0) return (uint16_t)(sign | 0x7C00u); /* 65520 is the midpoint above the largest fp16 */
+  if (a < 6.103515625e-05) {                            /* below 2^-14: subnormal spacing 2^-24 */
+    const double q = rint(ldexp(a, 24));
+    return (uint16_t)(sign | (uint16_t)q);              /* q == 1024 is the smallest normal */
+  }
+  int e;
+  (void)frexp(a, &e); /* a = f * 2^e, f in [0.5,1): a in [2^(e-1), 2^e) */
+  e -= 1;
+  double q = rint(ldexp(a, 10 - e)); /* in [1024, 2048] */
+  if (q >= 2048.0) {
+    q = 1024.0;
+    e += 1;
+  }
+  if (e > 15) return (uint16_t)(sign | 0x7C00u);
+  return (uint16_t)(sign | (uint16_t)((e + 15) << 10) | (uint16_t)((int)q - 1024));
+}
+
+/* One weight, in the paper's order: the int4 code as fp16 (FastINT4toFP16 is exact), then
+ * FusedDequantQuant and the first half of FastFP16toINT8 as ONE fp16 fused multiply-add
+ * x = code * s + (128 + 1024), then the low mantissa byte, then XOR 0x80.  The product and
+ * the sum are exact in double (15 + 11 significant bits, exponent span < 53 bits), so the
+ * single fp16 rounding of the FMA is the conversion below.  Where code*s rounds into
+ * [-128,127] the result is that integer (round half to even); outside, it is whatever the
+ * byte extraction gives: no saturation, as in the paper. */
+int8_t qqq_oracle_w8_f16scale_one(int code, uint16_t s_bits) {
+  const double s = (double)qqq_oracle_half_to_float(s_bits);
+  const uint16_t x = qqq_oracle_double_to_half((double)code * s + 1152.0);
+  return (int8_t)(uint8_t)((x & 0xFFu) ^ 0x80u);
+}
+
+int qqq_oracle_w8_pergroup_f16(const uint32_t* w_nat, const uint16_t* s_g_fp16, int64_t N,
+                               int64_t K, int64_t group, int8_t* w8) {
+  if (!w_nat || !s_g_fp16 || !w8) return ORC_NULL;
+  if (N <= 0 || K <= 0 || K % 8 || group <= 0 || K % group) return ORC_SHAPE;
+  for (int64_t n = 0; n < N; ++n)
+    for (int64_t k = 0; k < K; ++k)
+      w8[n * K + k] = qqq_oracle_w8_f16scale_one(code_at(w_nat, K, n, k), s_g_fp16[(k / group) * N + n]);
+  return ORC_OK;
+}
+
+int qqq_oracle_gemm_pergroup_f16(const int8_t* a_q, const float* s_a, const uint32_t* w_nat,
+                                 const uint16_t* s_g_fp16, const uint16_t* s_w_fp16, int64_t group,
+                                 int64_t M, int64_t N, int64_t K, int32_t* acc32, float* y32,
+                                 uint16_t* y_fp16) {
+  if (!a_q || !s_a || !w_nat || !s_g_fp16 || !s_w_fp16) return ORC_NULL;
+  if (M < 0 || N <= 0 || K <= 0 || K % 8 || group <= 0 || K % group) return ORC_SHAPE;
+  int8_t* w8 = (int8_t*)malloc((size_t)N * (size_t)K);
+  if (!w8) return ORC_SHAPE;
+  int rc = qqq_oracle_w8_pergroup_f16(w_nat, s_g_fp16, N, K, group, w8);
   if (rc == ORC_OK) rc = gemm_common(a_q, s_a, w8, s_w_fp16, M, N, K, acc32, y32, y_fp16);
   free(w8);
   return rc;

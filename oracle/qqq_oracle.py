@@ -66,6 +66,13 @@ def lib():
                                                    pi32, pf32, pu16]
             L.qqq_oracle_gemm_samples.argtypes = [pi8, pf32, pu32, pi8, pu16, i64, i64, i64, i64,
                                                   pi64, pi64, i64, pi64, pu16]
+            L.qqq_oracle_double_to_half.argtypes = [ctypes.c_double]
+            L.qqq_oracle_double_to_half.restype = ctypes.c_uint16
+            L.qqq_oracle_w8_f16scale_one.argtypes = [ctypes.c_int, ctypes.c_uint16]
+            L.qqq_oracle_w8_f16scale_one.restype = ctypes.c_int8
+            L.qqq_oracle_w8_pergroup_f16.argtypes = [pu32, pu16, i64, i64, i64, pi8]
+            L.qqq_oracle_gemm_pergroup_f16.argtypes = [pi8, pf32, pu32, pu16, pu16, i64, i64, i64,
+                                                       i64, pi32, pf32, pu16]
             _lib = L
     return _lib
 
@@ -190,6 +197,49 @@ def gemm_pergroup(a_q, s_a, w_nat, s_g, s_w_fp16_bits, group=128, want_y=True):
                                           _p(s_w, ctypes.c_uint16), group, M, N, K,
                                           _p(acc, ctypes.c_int32), _p(y32, ctypes.c_float),
                                           _p(y16, ctypes.c_uint16)))
+    return acc, y32, y16
+
+
+def double_to_half(x: float) -> int:
+    """fp16 bit pattern of a double, round to nearest even (the oracle's own conversion)."""
+    return int(lib().qqq_oracle_double_to_half(float(x)))
+
+
+def w8_f16scale_one(code: int, s_bits: int) -> int:
+    """One weight of the real-valued per-group path (Sec. 3.3.2): int8 from code and fp16 scale bits."""
+    return int(lib().qqq_oracle_w8_f16scale_one(int(code), int(s_bits)))
+
+
+def w8_pergroup_f16(w_nat, s_g_fp16_bits, K, group=128):
+    w = _c(w_nat, np.uint32)
+    g = _c(s_g_fp16_bits, np.uint16)
+    N = w.shape[0]
+    assert w.shape[1] * 8 == K and g.shape == (K // group, N)
+    out = np.empty((N, K), np.int8)
+    _check(lib().qqq_oracle_w8_pergroup_f16(_p(w, ctypes.c_uint32), _p(g, ctypes.c_uint16), N, K,
+                                            group, _p(out, ctypes.c_int8)))
+    return out
+
+
+def gemm_pergroup_f16(a_q, s_a, w_nat, s_g_fp16_bits, s_w_fp16_bits, group=128, want_y=True):
+    """Per-group GEMM with the paper's real-valued fp16 fused scale -> (acc, y32, y fp16 bits)."""
+    a = _c(a_q, np.int8)
+    s_a = _c(s_a, np.float32)
+    w = _c(w_nat, np.uint32)
+    g = _c(s_g_fp16_bits, np.uint16)
+    s_w = _c(s_w_fp16_bits, np.uint16)
+    M, K = a.shape
+    N = w.shape[0]
+    assert w.shape[1] * 8 == K and s_w.shape == (N,) and s_a.shape == (M,)
+    assert g.shape == (K // group, N)
+    acc = np.empty((M, N), np.int32)
+    y32 = np.empty((M, N), np.float32) if want_y else None
+    y16 = np.empty((M, N), np.uint16) if want_y else None
+    _check(lib().qqq_oracle_gemm_pergroup_f16(_p(a, ctypes.c_int8), _p(s_a, ctypes.c_float),
+                                              _p(w, ctypes.c_uint32), _p(g, ctypes.c_uint16),
+                                              _p(s_w, ctypes.c_uint16), group, M, N, K,
+                                              _p(acc, ctypes.c_int32), _p(y32, ctypes.c_float),
+                                              _p(y16, ctypes.c_uint16)))
     return acc, y32, y16
 
 
