@@ -100,6 +100,21 @@ int qqq_gemm_w4a8_pergroup(const int8_t* a_q, const float* s_a, const void* w_pa
                            void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Per-group W4A8 GEMM with the paper's real-valued fused scale (Sec. 3.3.2, Fig. 4-6, as printed):
+ *   s_g_fp16 [K/128, N] fp16 row-major holds s*_Wg = s_Wg / s_Wc (computed offline, Fig. 5);
+ *   W8[n,k] = FastFP16toINT8( fp16_fma( fp16(code[n,k]), s*_Wg[k/128][n], 128 + 1024 ) ):
+ *   the FMA's single rounding in the [1024,2048) binade rounds code*s to an integer (half to
+ *   even), the low mantissa byte XOR 0x80 is that integer as int8.  NO saturation: the caller's
+ *   scales must keep |code * s| within int8 (|s| <= 15.875 is always safe); outside, the byte
+ *   extraction wraps, exactly as the steps above do.  Then the same int8 MFMA and Dequant with
+ *   s_w (s_Wc).  Other arguments as in qqq_gemm_w4a8_pergroup; s_g_fp16 must be 4-byte aligned.
+ */
+int qqq_gemm_w4a8_pergroup_f16scale(const int8_t* a_q, const float* s_a, const void* w_packed,
+                                    const void* s_g_fp16, const void* s_w_fp16, int group,
+                                    void* y_fp16, int32_t* acc_out, int64_t M, int64_t N, int64_t K,
+                                    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Linear layer in one call (Sec. 4.1 per-token activation quantisation feeding Sec. 3.3's W4A8
  * GEMM): the result is exactly that of qqq_quant_act followed by qqq_gemm_w4a8_perchannel /
  * qqq_gemm_w4a8_pergroup on the same inputs (acc_out bit-identical, y_fp16 bit-identical).

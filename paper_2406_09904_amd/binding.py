@@ -18,7 +18,7 @@ GROUP = 128
 SYMBOLS = [
     "qqq_version", "qqq_last_error", "qqq_quant_act", "qqq_packed_w4_bytes", "qqq_pack_w4",
     "qqq_unpack_w4", "qqq_gemm_workspace_bytes", "qqq_gemm_w4a8_perchannel",
-    "qqq_gemm_w4a8_pergroup", "qqq_linear_workspace_bytes", "qqq_linear_w4a8_perchannel",
+    "qqq_gemm_w4a8_pergroup", "qqq_gemm_w4a8_pergroup_f16scale", "qqq_linear_workspace_bytes", "qqq_linear_w4a8_perchannel",
     "qqq_linear_w4a8_pergroup", "qqq_set_fused_quant", "qqq_set_kernel_override",
     "qqq_set_group_mode_override", "qqq_set_skinny_tuning", "qqq_set_prefill_tuning",
 ]
@@ -54,6 +54,8 @@ def lib():
         L.qqq_gemm_w4a8_perchannel.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, sz, vp]
         L.qqq_gemm_w4a8_pergroup.argtypes = [vp, vp, vp, vp, vp, ci, ci, vp, vp, i64, i64, i64,
                                              vp, sz, vp]
+        L.qqq_gemm_w4a8_pergroup_f16scale.argtypes = [vp, vp, vp, vp, vp, ci, vp, vp, i64, i64, i64,
+                                                      vp, sz, vp]
         L.qqq_linear_workspace_bytes.argtypes = [i64, i64, i64]
         L.qqq_linear_workspace_bytes.restype = sz
         L.qqq_linear_w4a8_perchannel.argtypes = [vp, i64, vp, vp, vp, vp, i64, i64, i64, vp, sz, vp]
@@ -158,6 +160,21 @@ def qqq_gemm_w4a8_pergroup(a_q, s_a, w_packed, s_g, s_w, workspace, sg_max=0, y=
     _check(lib().qqq_gemm_w4a8_pergroup(
         _ptr(a_q, torch.int8), _ptr(s_a, torch.float32), _ptr(w_packed, torch.uint8),
         _ptr(s_g, torch.int8), _ptr(s_w, torch.float16), group, sg_max, _ptr(y, torch.float16),
+        _ptr(acc_out, torch.int32), M, N, K, _ptr(workspace, torch.uint8), workspace.numel(),
+        _stream()))
+    return y
+
+
+def qqq_gemm_w4a8_pergroup_f16scale(a_q, s_a, w_packed, s_g_fp16, s_w, workspace, y=None,
+                                    acc_out=None, group=GROUP):
+    """Per-group GEMM with the real-valued fp16 fused scale s*_Wg [K/128, N] (no saturation)."""
+    M, K = a_q.shape
+    N = s_w.shape[0]
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=a_q.device)
+    _check(lib().qqq_gemm_w4a8_pergroup_f16scale(
+        _ptr(a_q, torch.int8), _ptr(s_a, torch.float32), _ptr(w_packed, torch.uint8),
+        _ptr(s_g_fp16, torch.float16), _ptr(s_w, torch.float16), group, _ptr(y, torch.float16),
         _ptr(acc_out, torch.int32), M, N, K, _ptr(workspace, torch.uint8), workspace.numel(),
         _stream()))
     return y

@@ -100,6 +100,7 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
   const int tune = get_prefill_tuning();
   if (tune >= 10 && tune <= 12) return launch_gemm_prefill_dma(p, mode, tune - 10, (hipStream_t)stream);
   if (tune == 13) return launch_gemm_prefill_ring(p, mode, (hipStream_t)stream);
+  if (mode == kGroupReal) return launch_gemm_prefill_dma(p, mode, 0, (hipStream_t)stream);
   if (tune == 0) {
     // Measured on MI355X: the persistent kernel wins for the per-channel variant at every K and
     // for the per-group variant when tiles are short (its per-k-step cost is a little higher
@@ -234,6 +235,15 @@ int qqq_gemm_w4a8_pergroup(const int8_t* a_q, const float* s_a, const void* w_pa
     return set_error(QQQ_ERR_SHAPE, "pergroup: sg_max must be in 0..127, got %d", sg_max);
   return gemm_common(a_q, s_a, w_packed, s_g, s_w_fp16, y_fp16, acc_out, M, N, K, workspace,
                      workspace_bytes, stream, group_mode(sg_max, M));
+}
+
+int qqq_gemm_w4a8_pergroup_f16scale(const int8_t* a_q, const float* s_a, const void* w_packed,
+                                    const void* s_g_fp16, const void* s_w_fp16, int group,
+                                    void* y_fp16, int32_t* acc_out, int64_t M, int64_t N, int64_t K,
+                                    void* workspace, size_t workspace_bytes, void* stream) {
+  if (group != QQQ_GROUP) return set_error(QQQ_ERR_SHAPE, "pergroup: group must be 128, got %d", group);
+  return gemm_common(a_q, s_a, w_packed, (const int8_t*)s_g_fp16, s_w_fp16, y_fp16, acc_out, M, N, K,
+                     workspace, workspace_bytes, stream, kGroupReal);
 }
 
 size_t qqq_linear_workspace_bytes(int64_t M, int64_t N, int64_t K) {

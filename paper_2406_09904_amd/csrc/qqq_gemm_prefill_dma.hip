@@ -80,11 +80,14 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
   const int64_t w_step = (int64_t)ntiles * 1024;  // bytes between k-steps of the packed weights
   // group scales of the wave's 32*CT channels: the first 8*CT lanes fetch 4 bytes each, the other
   // lanes (and channels past N) re-read a valid dword; each lane writes its own LDS dword
+  // (fp16 scales of the real-valued variant: the first 16*CT lanes fetch two scales each)
+  constexpr int kSgBytes = (MODE == kGroupReal) ? 2 : 1;  // bytes per group scale
+  constexpr int kSgPerLane = 4 / kSgBytes, kSgLanes = 32 * CT / kSgPerLane;
   const int8_t* sg_src = nullptr;
   if constexpr (MODE != kPerChannel) {
-    int c0 = n_wave + 4 * (lane < 8 * CT ? lane : 8 * CT - 1);
-    if (c0 > N - 4) c0 = N - 4;
-    sg_src = p.s_g + c0;
+    int c0 = n_wave + kSgPerLane * (lane < kSgLanes ? lane : kSgLanes - 1);
+    if (c0 > N - kSgPerLane) c0 = N - kSgPerLane;
+    sg_src = p.s_g + (int64_t)c0 * kSgBytes;
   }
 
   // The DMA loads are issued through inline assembly so that the compiler's wait-count pass does
@@ -110,7 +113,7 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
     for (int j = 0; j < S::kWChunks; ++j)
       dma16(w_src[j] + (int64_t)t * w_step, base + S::kAStage + wave_u * S::kWWave + j * 1024);
     if constexpr (MODE != kPerChannel)
-      dma4(sg_src + (int64_t)t * N, base + S::kAStage + S::kWStage + wave_u * 256);
+      dma4(sg_src + (int64_t)t * N * kSgBytes, base + S::kAStage + S::kWStage + wave_u * 256);
   };
   // DMA loads per wave per k-step
   constexpr int kDmaPerStep = S::kAPieces + S::kWChunks + (MODE != kPerChannel ? 1 : 0);
@@ -127,7 +130,7 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
 #pragma unroll
   for (int s = 0; s < 4; ++s) a_off[s] = n32 * 128 + (((2 * s + h) ^ (n32 & 7)) << 4);
   const int w_off = S::kAStage + wave * S::kWWave + (n32 >> 4) * 1024 + ((n32 & 15) + 16 * h) * 16;
-  const int sg_off = S::kAStage + S::kWStage + wave * 256 + n32;
+  const int sg_off = S::kAStage + S::kWStage + wave * 256 + n32 * kSgBytes;
 
   int col[CT];
   bool nvalid[CT];
@@ -163,7 +166,10 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
       wq[c][0] = *(const uint4*)(sb + w_off + c * 2048);
       wq[c][1] = *(const uint4*)(sb + w_off + c * 2048 + 512);
       sg[c] = 0;
-      if constexpr (MODE != kPerChannel) sg[c] = (int)sb[sg_off + c * 32];
+      if constexpr (MODE == kGroupReal)
+        sg[c] = (int)*(const uint16_t*)(sb + sg_off + c * 64);
+      else if constexpr (MODE != kPerChannel)
+        sg[c] = (int)sb[sg_off + c * 32];
     }
   };
   auto read_a = [&](v4i (&a)[MT], const int8_t* sb, int s) {
@@ -314,6 +320,7 @@ int launch_gemm_prefill_dma(const GemmParams& p, int mode, int shape, hipStream_
     // the tile has many rows, so both clamp-free requests use the per-weight fp16 FMA route here
     case kGroupLinear:
     case kGroupFused: return launch_shape<kGroupFused>(p, shape, st);
+    case kGroupReal: return launch_dma<kGroupReal, 4, 2, 8>(p, st);  // one shape: 128x512, 8 waves
   }
   return set_error(QQQ_ERR_SHAPE, "unknown mode %d", mode);
 }

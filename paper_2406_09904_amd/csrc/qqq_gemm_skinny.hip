@@ -28,9 +28,18 @@ struct Batch {
 // l requests word l mod 4*NT (one vector-memory instruction for the wave instead of one per
 // tile); when the batch is consumed the words are broadcast from lanes 0..4*NT-1 through scalar
 // registers and each lane picks its byte.
-template <int NT>
+// (The real-valued variant's scales are fp16: 8*NT words, two scales each.)
+template <int NT, int MODE>
 __device__ __forceinline__ int load_group_scales(const int8_t* gp, uint32_t lane) {
-  return reinterpret_cast<const int*>(gp)[lane & (4u * NT - 1u)];
+  constexpr uint32_t kWords = (MODE == kGroupReal ? 8u : 4u) * NT;
+  return reinterpret_cast<const int*>(gp)[lane & (kWords - 1u)];
+}
+
+// fp16 bit pattern of the lane's scale for tile i: half n%2 of word 8*i + n%16/2, fetched from
+// the lane that holds that word
+__device__ __forceinline__ uint32_t pick_group_scale_f16(int sgv, int i, int nl) {
+  const int d = __builtin_amdgcn_ds_bpermute(4 * (8 * i + (nl >> 1)), sgv);
+  return ((uint32_t)d >> ((nl & 1) * 16)) & 0xFFFFu;
 }
 
 // lane's scale for tile i: byte 16*i + n%16 of the wave's scale words
@@ -72,7 +81,8 @@ __device__ __forceinline__ void load_batch_w(Batch<NT, MT, U>& b, const GemmPara
       b.w[u][i] = make_uint4((uint32_t)raw[0], (uint32_t)raw[1], (uint32_t)raw[2], (uint32_t)raw[3]);
     }
     if constexpr (MODE != kPerChannel)
-      b.sgv[u] = load_group_scales<NT>(p.s_g + (int64_t)t * p.N + (int64_t)ng * NT * 16, lane);
+      b.sgv[u] = load_group_scales<NT, MODE>(
+          p.s_g + ((int64_t)t * p.N + (int64_t)ng * NT * 16) * (MODE == kGroupReal ? 2 : 1), lane);
   }
 }
 
@@ -114,7 +124,10 @@ __device__ __forceinline__ void consume_batch(const Batch<NT, MT, U>& b, v4i (&a
       const uint32_t d[4] = {b.w[u][i].x, b.w[u][i].y, b.w[u][i].z, b.w[u][i].w};
       int o[8];
       int sg = 0;
-      if constexpr (MODE != kPerChannel) sg = pick_group_scale<NT>(b.sgv[u], i, nl);
+      if constexpr (MODE == kGroupReal)
+        sg = (int)pick_group_scale_f16(b.sgv[u], i, nl);
+      else if constexpr (MODE != kPerChannel)
+        sg = pick_group_scale<NT>(b.sgv[u], i, nl);
       if constexpr (MODE == kPerChannel || MODE == kGroupLinear) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) unpack_x16(d[j], o[2 * j], o[2 * j + 1]);
@@ -123,6 +136,10 @@ __device__ __forceinline__ void consume_batch(const Batch<NT, MT, U>& b, v4i (&a
         const h2 s2 = {hs, hs};
 #pragma unroll
         for (int j = 0; j < 4; ++j) unpack_group_clamp(d[j], s2, o[2 * j], o[2 * j + 1]);
+      } else if constexpr (MODE == kGroupReal) {
+        const h2 s2 = as_h2((uint32_t)sg | ((uint32_t)sg << 16));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) unpack_group_real(d[j], s2, o[2 * j], o[2 * j + 1]);
       } else {
         const GroupFusedConsts g = make_group_fused(sg);
 #pragma unroll
@@ -470,6 +487,7 @@ int launch_gemm_skinny(const GemmParams& p, int mode, hipStream_t st) {
     case kGroupLinear: return launch_mode<kGroupLinear>(p, st);
     case kGroupClamp: return launch_mode<kGroupClamp>(p, st);
     case kGroupFused: return launch_mode<kGroupFused>(p, st);
+    case kGroupReal: return launch_mode<kGroupReal>(p, st);
   }
   return set_error(QQQ_ERR_SHAPE, "unknown mode %d", mode);
 }

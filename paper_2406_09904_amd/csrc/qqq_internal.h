@@ -19,6 +19,8 @@ enum Mode : int {
                       // the group's partial int32 sum instead of to each weight (same integers)
   kGroupClamp = 2,    // Sec. 3.3.2, general: code*s_g saturated to int8 per weight (fp16 route)
   kGroupFused = 3,    // Sec. 3.3.2 with s_g <= 16: per-weight fp16 FMA + byte extract, no clamp
+  kGroupReal = 4,     // Sec. 3.3.2 as printed: real-valued fp16 fused scale s*_Wg, one fp16 FMA with
+                      // 128 + 1024, low byte, XOR 0x80, no saturation; s_g then points at fp16 data
 };
 
 struct GemmParams {
@@ -179,6 +181,29 @@ __device__ __forceinline__ uint32_t quant4(uint32_t w0, uint32_t w1, float s) {
   const int q3 = (int)fminf(fmaxf(__builtin_rintf(x3 / s), -127.0f), 127.0f);
   return (uint32_t)(q0 & 0xFF) | ((uint32_t)(q1 & 0xFF) << 8) | ((uint32_t)(q2 & 0xFF) << 16) |
          ((uint32_t)(q3 & 0xFF) << 24);
+}
+
+// Sec. 3.3.2 with the real-valued fused scale, step by step: FastINT4toFP16 (0x6400|u is 1024+u,
+// 0x5400|(u<<4) is 64+u, each minus its offset and the +8 code bias gives the exact fp16 code),
+// FusedDequantQuant fused with the first half of FastFP16toINT8 as one fp16 FMA
+// code * s + (128 + 1024), whose single rounding in the [1024,2048) binade rounds code*s to an
+// integer (half to even), then the low mantissa bytes (v_perm_b32, the PRMT of the paper) and
+// XOR 0x80.  No saturation: the caller's scales keep |code*s| inside int8.
+__device__ __forceinline__ void unpack_group_real(uint32_t x, h2 s2, int& lo, int& hi) {
+  const uint32_t y = x ^ 0x88888888u;  // two's complement nibble -> code + 8
+  const uint32_t y8 = y >> 8;
+  const h2 off_lo = {(_Float16)1032.0f, (_Float16)1032.0f}, off_hi = {(_Float16)72.0f, (_Float16)72.0f};
+  const h2 magic = {(_Float16)1152.0f, (_Float16)1152.0f};
+  const h2 c0 = as_h2((y & 0x000F000Fu) | 0x64006400u) - off_lo;   // nibbles 0,4
+  const h2 c1 = as_h2((y & 0x00F000F0u) | 0x54005400u) - off_hi;   // nibbles 1,5
+  const h2 c2 = as_h2((y8 & 0x000F000Fu) | 0x64006400u) - off_lo;  // nibbles 2,6
+  const h2 c3 = as_h2((y8 & 0x00F000F0u) | 0x54005400u) - off_hi;  // nibbles 3,7
+  const h2 f0 = __builtin_elementwise_fma(c0, s2, magic);
+  const h2 f1 = __builtin_elementwise_fma(c1, s2, magic);
+  const h2 f2 = __builtin_elementwise_fma(c2, s2, magic);
+  const h2 f3 = __builtin_elementwise_fma(c3, s2, magic);
+  lo = (int)(__builtin_amdgcn_perm(as_u32(f2), as_u32(f0), 0x06020400u) ^ 0x80808080u);
+  hi = (int)(__builtin_amdgcn_perm(as_u32(f3), as_u32(f1), 0x06020400u) ^ 0x80808080u);
 }
 
 // Dequant (Sec. 3.3.1/3.3.2 last step): int32 -> fp32 -> two fp32 multiplies -> fp16 (RNE).

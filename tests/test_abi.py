@@ -73,6 +73,12 @@ def test_host_side_argument_errors(L):
     assert L.qqq_gemm_w4a8_pergroup(bad, bad, bad, None, bad, 128, 0, bad, None, 4, 128, 128, bad,
                                     1 << 20, None) == 1
     assert b"workspace" in L.qqq_last_error() or len(L.qqq_last_error()) > 0
+    # real-valued fp16 group scales: same validation
+    assert L.qqq_gemm_w4a8_pergroup_f16scale(*g, 64, bad, None, 4, 128, 128, bad, 1 << 20, None) == 2
+    assert L.qqq_gemm_w4a8_pergroup_f16scale(bad, bad, bad, None, bad, 128, bad, None, 4, 128, 128, bad,
+                                             1 << 20, None) == 1
+    assert L.qqq_gemm_w4a8_pergroup_f16scale(bad, bad, bad, ctypes.c_void_p(0x1002), bad, 128, bad, None,
+                                             4, 128, 128, bad, 1 << 20, None) == 2     # misaligned scales
     # one-call linear layer: fp16 rows in, same validation order (shape, null, alignment, workspace)
     lin = (bad, bad, bad, None)                       # w_packed, s_w, y, acc_out
     assert L.qqq_linear_w4a8_perchannel(bad, 128, *lin, 4, 100, 128, bad, 1 << 20, None) == 2

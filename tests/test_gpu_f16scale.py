@@ -1,0 +1,119 @@
+"""GPU parity of the per-group GEMM with the real-valued fp16 fused scale (Sec. 3.3.2 of the QQQ
+paper as printed) against the CPU oracle: int32 accumulators bit-exact, fp16 outputs within 1 ulp.
+
+The conversion int4 x fp16 scale -> int8 is checked for EVERY finite fp16 scale and every code, in
+and out of the no-overflow domain, through one-hot activation rows that expose single weights.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import qqq_oracle as orc
+from paper_2406_09904_amd import binding as qqq
+from paper_2406_09904_amd import synth
+from tests.util import f16_bits, to_dev, ulp_distance
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def _reset_overrides():
+    yield
+    qqq.set_kernel_override(0)
+    qqq.set_skinny_tuning(0, 0, 0, 0)
+
+
+def run(a_q, s_a, w_nat, s_g_bits, s_w, K, family=0):
+    M, N = a_q.shape[0], w_nat.shape[0]
+    d_w = qqq.qqq_pack_w4(to_dev(w_nat, torch), K)
+    ws = qqq.new_workspace(M, N, K)
+    acc = torch.full((M, N), -12345, dtype=torch.int32, device="cuda")
+    qqq.set_kernel_override(family)
+    y = qqq.qqq_gemm_w4a8_pergroup_f16scale(to_dev(a_q, torch), to_dev(s_a, torch), d_w,
+                                            to_dev(s_g_bits, torch), to_dev(s_w.view(np.uint16), torch),
+                                            ws, acc_out=acc)
+    torch.cuda.synchronize()
+    assert not ws.any(), "workspace not returned to zero"
+    return acc.cpu().numpy(), f16_bits(y)
+
+
+def check(acc, y, o_acc, o_y):
+    assert np.array_equal(acc, o_acc), "int32 accumulators differ: %d of %d" % (
+        int((acc != o_acc).sum()), acc.size)
+    d = ulp_distance(y, o_y)
+    assert d.max() <= 1, "fp16 output off by %d ulp" % int(d.max())
+
+
+@pytest.mark.parametrize("family", [1, 2])
+def test_every_fp16_scale_times_every_code(family):
+    """4 groups x 16384 channels = all 65536 fp16 patterns as scales (inf/NaN replaced by 1.0);
+    row 16*g + c is one-hot on the positions of code c-8 in group g, so acc = 8 * W8(code, scale)."""
+    G, N = 4, 16384
+    K, M = 128 * G, 16 * G
+    s_bits = np.arange(G * N, dtype=np.uint32).astype(np.uint16).reshape(G, N)
+    s_bits[((s_bits >> 10) & 0x1F) == 31] = np.float16(1.0).view(np.uint16)
+    k = np.arange(K)
+    codes = np.broadcast_to((k % 16) - 8, (N, K))
+    w = synth.codes_to_w_nat(codes)
+    a_q = np.zeros((M, K), np.int8)
+    for g in range(G):
+        for c in range(16):
+            a_q[16 * g + c, (k // 128 == g) & (k % 16 == c)] = 1
+    s_a = synth.token_scales(M, 5)
+    s_w = synth.weight_scales_fp16(N, 6, 0.001, 0.005)
+    o_acc, _, o_y = orc.gemm_pergroup_f16(a_q, s_a, w, s_bits, s_w.view(np.uint16))
+    # the oracle's accumulators are 8 x the single-weight conversion (ties the GEMM to the pins)
+    assert o_acc[16 * 1 + 3, 77] == 8 * orc.w8_f16scale_one(3 - 8, int(s_bits[1, 77]))
+    acc, y = run(a_q, s_a, w, s_bits, s_w, K, family=family)
+    check(acc, y, o_acc, o_y)
+
+
+SHAPES = [(1, 128, 16), (1, 4096, 1024), (3, 1152, 272), (16, 2048, 512), (33, 640, 336),
+          (64, 384, 4096), (65, 512, 528), (130, 1024, 512), (300, 384, 1040)]
+
+
+@pytest.mark.parametrize("M,K,N", SHAPES)
+def test_random_scales_in_domain(M, K, N):
+    g = synth.rng(1000 + M + K + N)
+    a_q = synth.int8_activations(M, K, M + K)
+    s_a = synth.token_scales(M, M + 1)
+    w = synth.random_w_nat(N, K, N + 2)
+    s_g = (g.uniform(0.02, 15.8, (K // 128, N)) * g.choice([1.0, 1.0, 1.0, -1.0], (K // 128, N))
+           ).astype(np.float16)
+    s_w = synth.weight_scales_fp16(N, N + 3, 0.001, 0.005)
+    o_acc, _, o_y = orc.gemm_pergroup_f16(a_q, s_a, w, s_g.view(np.uint16), s_w.view(np.uint16))
+    acc, y = run(a_q, s_a, w, s_g.view(np.uint16), s_w, K)
+    check(acc, y, o_acc, o_y)
+
+
+@pytest.mark.parametrize("nt,S,W", [(1, 1, 4), (2, 1, 8), (4, 1, 16), (1, 3, 8), (4, 4, 8), (2, 5, 4)])
+def test_decode_launch_shapes(nt, S, W):
+    M, K, N = 5, 2560, 448
+    g = synth.rng(77)
+    a_q = synth.int8_activations(M, K, 1)
+    s_a = synth.token_scales(M, 2)
+    w = synth.random_w_nat(N, K, 3)
+    s_g = g.uniform(0.02, 15.8, (K // 128, N)).astype(np.float16)
+    s_w = synth.weight_scales_fp16(N, 4, 0.001, 0.005)
+    o_acc, _, o_y = orc.gemm_pergroup_f16(a_q, s_a, w, s_g.view(np.uint16), s_w.view(np.uint16))
+    qqq.set_skinny_tuning(nt, S, W, 0)
+    acc, y = run(a_q, s_a, w, s_g.view(np.uint16), s_w, K)
+    check(acc, y, o_acc, o_y)
+
+
+def test_integer_valued_scales_match_the_integer_scale_entry_point():
+    """Integer scales 1..15 as fp16: same accumulators as qqq_gemm_w4a8_pergroup (nothing saturates)."""
+    M, K, N = 7, 1024, 256
+    a_q = synth.int8_activations(M, K, 11)
+    s_a = synth.token_scales(M, 12)
+    w = synth.random_w_nat(N, K, 13)
+    s_int = synth.group_scales(K, N, 14, 1, 15)
+    s_w = synth.weight_scales_fp16(N, 15, 0.001, 0.005)
+    acc, y = run(a_q, s_a, w, s_int.astype(np.float16).view(np.uint16), s_w, K)
+    d_w = qqq.qqq_pack_w4(to_dev(w, torch), K)
+    ws = qqq.new_workspace(M, N, K)
+    acc2 = torch.empty((M, N), dtype=torch.int32, device="cuda")
+    y2 = qqq.qqq_gemm_w4a8_pergroup(to_dev(a_q, torch), to_dev(s_a, torch), d_w, to_dev(s_int, torch),
+                                    to_dev(s_w.view(np.uint16), torch), ws, sg_max=15, acc_out=acc2)
+    torch.cuda.synchronize()
+    assert np.array_equal(acc, acc2.cpu().numpy()) and np.array_equal(y, f16_bits(y2))
