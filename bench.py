@@ -183,6 +183,44 @@ def measure(case, torch, steps, warmup, use_graph):
     return step_ms, gemm_ms, quant_ms, graphed
 
 
+def real_scale_lines(wls, torch, qqq, args, use_graph):
+    """The per-group GEMM with the paper's real-valued fp16 fused scale (Sec. 3.3.2 as printed) on
+    the two per-group layer shapes: GEMM kernel only, same rotation of weight copies."""
+    import numpy as np
+    lines = []
+    for name in ("cfg2_pg_m1_k4096_n11008", "cfg4_pg_m4096_k11008_n4096"):
+        wl = wls[name]
+        big = wl.M >= 1024
+        c = Case(wl, torch, qqq, rotate_bytes=(1 << 28) if big else (1 << 30))
+        c.quant()
+        sg16 = torch.from_numpy(wl.s_g_f16()).cuda()
+        sgs = [sg16] + [sg16.clone() for _ in range(c.copies - 1)]
+
+        def gemm(i, c=c, sgs=sgs):
+            r = i % c.copies
+            qqq.qqq_gemm_w4a8_pergroup_f16scale(c.a_q, c.s_a, c.w[r], sgs[r], c.s_w, c.ws, y=c.y)
+
+        st = max(5, min(args.steps, 20 if big else 100))
+        ms, _ = timed(torch, gemm, st, min(args.warmup, 5), use_graph)
+        nbytes = c.bytes + wl.K // 128 * wl.N       # fp16 scales: one more byte per group scale
+        t_mem = nbytes / (HBM_PEAK_GBS * 1e9)
+        t_mfma = c.ops / (MFMA_I8_PEAK_TOPS * 1e12)
+        if t_mem >= t_mfma:
+            ach = nbytes / (ms * 1e-3) / 1e9
+            roof = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(ach / HBM_PEAK_GBS, 4)}
+        else:
+            ach = c.ops / (ms * 1e-3) / 1e12
+            roof = {"bound": "mfma", "achieved": round(ach, 1), "peak": MFMA_I8_PEAK_TOPS,
+                    "unit": "TOP/s", "frac": round(ach / MFMA_I8_PEAK_TOPS, 4)}
+        lines.append({"shape_of": name, "entry": "qqq_gemm_w4a8_pergroup_f16scale", "steps": st,
+                      "gemm_us": round(ms * 1e3, 3), "tops": round(c.ops / (ms * 1e-3) / 1e12, 3),
+                      "roofline": roof})
+        del c, sgs, sg16
+        torch.cuda.empty_cache()
+    return lines
+
+
 def cpu_baseline(wl, budget_s=12.0):
     """The oracle, as it stands, on this machine's host cores: whole path on the workload (repeated
     until the time budget is used when one pass is short, on a row subset when one pass is long)."""
@@ -297,6 +335,9 @@ def main():
             del c2
             torch.cuda.empty_cache()
         out["sweep"] = sweep
+
+    if not args.no_sweep:
+        out["real_valued_group_scale"] = real_scale_lines(wls, torch, qqq, args, use_graph)
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)

@@ -351,3 +351,26 @@ int qqq_oracle_gemm_samples(const int8_t* a_q, const float* s_a, const uint32_t*
   }
   return ORC_OK;
 }
+
+/* the same for the real-valued fp16 group scale of Sec. 3.3.2 */
+int qqq_oracle_gemm_samples_f16(const int8_t* a_q, const float* s_a, const uint32_t* w_nat,
+                                const uint16_t* s_g_fp16, const uint16_t* s_w_fp16, int64_t group,
+                                int64_t M, int64_t N, int64_t K, const int64_t* idx_m,
+                                const int64_t* idx_n, int64_t count, int64_t* acc_out,
+                                uint16_t* y_fp16) {
+  if (!a_q || !s_a || !w_nat || !s_g_fp16 || !s_w_fp16 || !idx_m || !idx_n || !acc_out) return ORC_NULL;
+  if (M <= 0 || N <= 0 || K <= 0 || K % 8 || group <= 0 || K % group) return ORC_SHAPE;
+  for (int64_t i = 0; i < count; ++i)
+    if (idx_m[i] < 0 || idx_m[i] >= M || idx_n[i] < 0 || idx_n[i] >= N) return ORC_SHAPE;
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < count; ++i) {
+    const int64_t m = idx_m[i], n = idx_n[i];
+    int64_t s = 0;
+    for (int64_t k = 0; k < K; ++k)
+      s += (int64_t)a_q[m * K + k] *
+           (int64_t)qqq_oracle_w8_f16scale_one(code_at(w_nat, K, n, k), s_g_fp16[(k / group) * N + n]);
+    acc_out[i] = s;
+    if (y_fp16) y_fp16[i] = dequant_one(s, s_a[m], s_w_fp16[n], NULL);
+  }
+  return ORC_OK;
+}

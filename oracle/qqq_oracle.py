@@ -73,6 +73,8 @@ def lib():
             L.qqq_oracle_w8_pergroup_f16.argtypes = [pu32, pu16, i64, i64, i64, pi8]
             L.qqq_oracle_gemm_pergroup_f16.argtypes = [pi8, pf32, pu32, pu16, pu16, i64, i64, i64,
                                                        i64, pi32, pf32, pu16]
+            L.qqq_oracle_gemm_samples_f16.argtypes = [pi8, pf32, pu32, pu16, pu16, i64, i64, i64, i64,
+                                                      pi64, pi64, i64, pi64, pu16]
             _lib = L
     return _lib
 
@@ -261,4 +263,25 @@ def gemm_samples(a_q, s_a, w_nat, s_g, s_w_fp16_bits, idx_m, idx_n, group=128):
                                          _p(s_w, ctypes.c_uint16), group, M, N, K,
                                          _p(im, ctypes.c_int64), _p(jn, ctypes.c_int64), im.size,
                                          _p(acc, ctypes.c_int64), _p(y16, ctypes.c_uint16)))
+    return acc, y16
+
+
+def gemm_samples_f16(a_q, s_a, w_nat, s_g_fp16_bits, s_w_fp16_bits, idx_m, idx_n, group=128):
+    """Selected outputs of the real-valued per-group variant. -> (acc int64 [S], y fp16 bits [S])."""
+    a = _c(a_q, np.int8)
+    s_a = _c(s_a, np.float32)
+    w = _c(w_nat, np.uint32)
+    g = _c(s_g_fp16_bits, np.uint16)
+    s_w = _c(s_w_fp16_bits, np.uint16)
+    im = _c(idx_m, np.int64)
+    jn = _c(idx_n, np.int64)
+    M, K = a.shape
+    N = w.shape[0]
+    acc = np.empty(im.shape, np.int64)
+    y16 = np.empty(im.shape, np.uint16)
+    _check(lib().qqq_oracle_gemm_samples_f16(_p(a, ctypes.c_int8), _p(s_a, ctypes.c_float),
+                                             _p(w, ctypes.c_uint32), _p(g, ctypes.c_uint16),
+                                             _p(s_w, ctypes.c_uint16), group, M, N, K,
+                                             _p(im, ctypes.c_int64), _p(jn, ctypes.c_int64), im.size,
+                                             _p(acc, ctypes.c_int64), _p(y16, ctypes.c_uint16)))
     return acc, y16

@@ -76,6 +76,13 @@ def group_scales(K: int, N: int, seed: int, lo: int = 1, hi: int = 15) -> np.nda
     return rng(seed).integers(lo, hi + 1, size=(K // GROUP, N), dtype=np.int8)
 
 
+def group_scales_f16(K: int, N: int, seed: int, lo: float = 0.5, hi: float = 15.5) -> np.ndarray:
+    """fp16 [K/128, N] real-valued fused group scales s*_Wg = s_Wg / s_Wc, uniform in [lo,hi]
+    (|code * s| stays inside int8 for hi <= 15.875)."""
+    assert K % GROUP == 0
+    return rng(seed).uniform(lo, hi, size=(K // GROUP, N)).astype(np.float16)
+
+
 @dataclass(frozen=True)
 class Workload:
     """One benchmark configuration: variant, shape and the distributions of its inputs."""
@@ -105,6 +112,10 @@ class Workload:
 
     def s_g(self) -> np.ndarray:
         return group_scales(self.K, self.N, self.seed + 4, self.sg_lo, self.sg_hi)
+
+    def s_g_f16(self) -> np.ndarray:
+        """Real-valued fp16 fused scales for the same layer (the paper's own per-group form)."""
+        return group_scales_f16(self.K, self.N, self.seed + 5, 0.5, float(self.sg_hi) + 0.5)
 
 
 def _pc(name, M, K, N, cfg):

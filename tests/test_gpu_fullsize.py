@@ -91,3 +91,29 @@ def test_full_size_workload(name):
             f_acc, _, f_y = orc.gemm_perchannel(o_q, o_sa, w_nat, s_w.view(np.uint16))
         assert np.array_equal(acc.cpu().numpy(), f_acc), "int32 accumulators differ"
         assert ulp_distance(f16_bits(y), f_y).max() <= 1, "fp16 outputs differ by more than 1 ulp"
+
+
+@pytest.mark.parametrize("name", ["cfg2_pg_m1_k4096_n11008", "cfg4_pg_m4096_k11008_n4096",
+                                  "cfg5_pg_m16_k8192_n28672"])
+def test_full_size_real_valued_group_scale(name):
+    """The per-group layer shapes through qqq_gemm_w4a8_pergroup_f16scale (Sec. 3.3.2 as printed),
+    sampled outputs against the oracle's one-by-one evaluation."""
+    wl = WORKLOADS[name]
+    M, K, N = wl.M, wl.K, wl.N
+    a = wl.activations()
+    w_nat, d_w = _weights(wl.seed, N, K)
+    s_w, s_g = wl.s_w(), wl.s_g_f16()
+    d_q, d_sa = qqq.qqq_quant_act(torch.from_numpy(a).cuda())
+    ws = qqq.new_workspace(M, N, K)
+    acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
+    y = qqq.qqq_gemm_w4a8_pergroup_f16scale(d_q, d_sa, d_w, torch.from_numpy(s_g).cuda(),
+                                            torch.from_numpy(s_w).cuda(), ws, acc_out=acc)
+    torch.cuda.synchronize()
+    assert not ws.any().item(), "workspace not returned to zero"
+    o_q, o_sa = orc.quant_act(a.view(np.uint16))
+    im, jn = sample_positions(M, N, 3000, wl.seed + 9)
+    o_acc, o_y = orc.gemm_samples_f16(o_q, o_sa, w_nat, s_g.view(np.uint16), s_w.view(np.uint16), im, jn)
+    t_im, t_jn = torch.from_numpy(im).cuda(), torch.from_numpy(jn).cuda()
+    assert np.array_equal(acc[t_im, t_jn].cpu().numpy().astype(np.int64), o_acc)
+    assert ulp_distance(f16_bits(y[t_im, t_jn]), o_y).max() <= 1
+    assert np.abs(o_acc).max() > 0

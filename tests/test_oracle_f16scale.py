@@ -167,3 +167,16 @@ def test_f16scale_shape_and_null_errors():
     w = synth.random_w_nat(16, 128, 1)
     with pytest.raises(AssertionError):
         orc.w8_pergroup_f16(w, np.zeros((2, 16), np.uint16), 128)
+
+
+def test_sampled_evaluation_equals_the_full_product():
+    M, N, K = 5, 48, 512
+    a = synth.int8_activations(M, K, 1)
+    sa = synth.token_scales(M, 2)
+    w = synth.random_w_nat(N, K, 3)
+    sg = synth.group_scales_f16(K, N, 4).view(np.uint16)
+    sw = synth.weight_scales_fp16(N, 5, 0.001, 0.005).view(np.uint16)
+    acc, _, y = orc.gemm_pergroup_f16(a, sa, w, sg, sw)
+    im, jn = np.repeat(np.arange(M), N), np.tile(np.arange(N), M)
+    a2, y2 = orc.gemm_samples_f16(a, sa, w, sg, sw, im, jn)
+    assert np.array_equal(a2.reshape(M, N), acc) and np.array_equal(y2.reshape(M, N), y)
