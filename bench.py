@@ -85,6 +85,10 @@ class Case:
         self.ops = 2 * M * N * K
         self.bytes = algorithmic_bytes(M, N, K, self.pg)
         self.fused = is_fused(M, K)
+        # the GEMM-only timing reads a_q/s_a: fill them with the workload's real codes first (MFMA
+        # power, hence clock and speed, depends on the operand values)
+        self.quant()
+        torch.cuda.synchronize()
 
     def quant(self):
         self.qqq.qqq_quant_act(self.a, self.a_q, self.s_a)

@@ -242,3 +242,4 @@ def set_skinny_tuning(channel_tiles: int, k_slices: int, waves: int = 0, depth: 
 
 def set_prefill_tuning(waves: int) -> int:
     return lib().qqq_set_prefill_tuning(waves)
+

@@ -48,6 +48,7 @@ static int group_mode(int sg_max, int64_t M) {
 }
 
 static size_t ws_rows(int64_t M) { return (size_t)(M < kSkinnyMaxM ? M : kSkinnyMaxM); }
+static size_t ws_counter_bytes(int64_t N) { return ((size_t)(N / 16) * 4 + 255) & ~(size_t)255; }
 
 static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed, const int8_t* s_g,
                        const void* s_w, void* y, int32_t* acc_out, int64_t M, int64_t N, int64_t K,
@@ -94,18 +95,41 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
       return set_error(QQQ_ERR_WORKSPACE, "gemm: workspace %zu bytes < %zu needed", workspace_bytes,
                        need);
     p.ws_cnt = (int32_t*)workspace;
-    p.ws_acc = (int32_t*)((char*)workspace + (((size_t)(N / 16) * 4 + 255) & ~(size_t)255));
+    p.ws_acc = (int32_t*)((char*)workspace + ws_counter_bytes(N));
     return launch_gemm_skinny(p, mode, (hipStream_t)stream);
   }
+  const int64_t tiles = ((M + 127) / 128) * ((N + 511) / 512);
   const int tune = get_prefill_tuning();
-  if (tune >= 10 && tune <= 12) return launch_gemm_prefill_dma(p, mode, tune - 10, (hipStream_t)stream);
+  if ((tune >= 10 && tune <= 12) || (tune >= 15 && tune <= 17))
+    return launch_gemm_prefill_dma(p, mode, tune >= 15 ? tune - 12 : tune - 10, (hipStream_t)stream);
   if (tune == 13) return launch_gemm_prefill_ring(p, mode, (hipStream_t)stream);
-  if (mode == kGroupReal) return launch_gemm_prefill_dma(p, mode, 0, (hipStream_t)stream);
   if (tune == 0) {
+    // Tile shape from a cost model measured on MI355X (microseconds per k-step of one workgroup,
+    // alone on its CU / with the chip saturated): few rows want many small tiles, many rows the
+    // large tile with the most reuse.
+    const int cus = num_cus();
+    struct Cand { int shape, bm, bn; bool one_per_cu; double alone, saturated; };
+    const Cand cands[4] = {{0, 128, 512, true, 1.34, 1.50}, {3, 128, 256, true, 0.88, 0.90},
+                           {4, 128, 128, false, 0.63, 0.52}, {5, 64, 128, false, 0.45, 0.275}};
+    int best = 0;
+    double best_cost = 0.0;
+    for (int i = 0; i < 4; ++i) {
+      const Cand& c = cands[i];
+      const int64_t wgs = ((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
+      double cost = c.alone;
+      if (wgs > cus)  // whole rounds where only one workgroup fits a CU, a smooth load otherwise
+        cost = c.saturated * (c.one_per_cu ? (double)((wgs + cus - 1) / cus) : (double)wgs / cus);
+      if (i == 0 || cost < best_cost * (best == 0 ? 0.95 : 1.0)) {  // leaving the large tile has to pay
+        best = c.shape;
+        best_cost = cost;
+      }
+    }
+    if (best != 0) return launch_gemm_prefill_dma(p, mode, best, (hipStream_t)stream);
+    if (mode == kGroupReal) return launch_gemm_prefill_dma(p, mode, 0, (hipStream_t)stream);
     // Measured on MI355X: the persistent kernel wins for the per-channel variant at every K and
     // for the per-group variant when tiles are short (its per-k-step cost is a little higher
     // there, its per-tile cost much lower).
-    const bool tiles_repeat = ((M + 127) / 128) * ((N + 511) / 512) > num_cus();
+    const bool tiles_repeat = tiles > num_cus();
     if (mode == kPerChannel || (tiles_repeat && K <= 3072))
       return launch_gemm_prefill_ring(p, mode, (hipStream_t)stream);
     return launch_gemm_prefill_dma(p, mode, 0, (hipStream_t)stream);
@@ -190,6 +214,7 @@ int qqq_set_prefill_tuning(int waves) {
   return 0;
 }
 
+
 size_t qqq_packed_w4_bytes(int64_t N, int64_t K) {
   if (N < 16 || N % 16 != 0 || K < 128 || K % 128 != 0 || K > 131072 || N > 0x7FFFFFF0) return 0;
   return (size_t)N * (size_t)K / 2;
@@ -214,8 +239,7 @@ int qqq_unpack_w4(const void* w_packed, int64_t N, int64_t K, uint32_t* w_nat, v
 
 size_t qqq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
   if (!gemm_shape_ok(M, N, K)) return 0;
-  const size_t cnt = ((size_t)(N / 16) * 4 + 255) & ~(size_t)255;
-  return cnt + ws_rows(M) * (size_t)N * 4;
+  return ws_counter_bytes(N) + ws_rows(M) * (size_t)N * 4;
 }
 
 int qqq_gemm_w4a8_perchannel(const int8_t* a_q, const float* s_a, const void* w_packed,

@@ -8,6 +8,8 @@
 //            activation fragment read from LDS feeds 4 MFMAs instead of 2
 //   <8,2,4>  256 x 256, 4 waves, 256 accumulator registers: each converted weight fragment feeds
 //            8 MFMAs instead of 4 (the per-group conversion is the VALU-heavy part)
+//   <4,1,8>  128 x 256, <4,1,4>  128 x 128, <2,1,4>  64 x 128: narrow tiles for mid-size M, where
+//            a few large tiles would leave most CUs idle
 //
 // Why a DMA ring on gfx950.  The int8 MFMA pipe retires a 32x32x32 tile in 32 clocks, so one
 // k-step (128 k) is 1-2 thousand clocks of MFMA per wave; a global load that misses L2 takes
@@ -307,11 +309,16 @@ static int launch_shape(const GemmParams& p, int shape, hipStream_t st) {
   switch (shape) {
     case 1: return launch_dma<MODE, 4, 4, 4>(p, st);
     case 2: return launch_dma<MODE, 8, 2, 4>(p, st);
+    case 3: return launch_dma<MODE, 4, 1, 8>(p, st);
+    case 4: return launch_dma<MODE, 4, 1, 4>(p, st);
+    case 5: return launch_dma<MODE, 2, 1, 4>(p, st);
     default: return launch_dma<MODE, 4, 2, 8>(p, st);
   }
 }
 
-// shape: 0 = 128x512 tile with 8 waves, 1 = 128x512 with 4 waves, 2 = 256x256 with 4 waves
+// shape: 0 = 128x512 tile with 8 waves, 1 = 128x512 with 4 waves, 2 = 256x256 with 4 waves;
+// narrow tiles for shapes with few rows, where the number of workgroups matters more than the
+// reuse inside one: 3 = 128x256 with 8 waves, 4 = 128x128 with 4 waves, 5 = 64x128 with 4 waves
 int launch_gemm_prefill_dma(const GemmParams& p, int mode, int shape, hipStream_t st) {
   switch (mode) {
     case kPerChannel: return launch_shape<kPerChannel>(p, shape, st);
@@ -320,7 +327,7 @@ int launch_gemm_prefill_dma(const GemmParams& p, int mode, int shape, hipStream_
     // the tile has many rows, so both clamp-free requests use the per-weight fp16 FMA route here
     case kGroupLinear:
     case kGroupFused: return launch_shape<kGroupFused>(p, shape, st);
-    case kGroupReal: return launch_dma<kGroupReal, 4, 2, 8>(p, st);  // one shape: 128x512, 8 waves
+    case kGroupReal: return launch_shape<kGroupReal>(p, shape, st);
   }
   return set_error(QQQ_ERR_SHAPE, "unknown mode %d", mode);
 }

@@ -1,0 +1,81 @@
+"""GPU parity for mid-size M (65..1024 rows), where the prefill path picks narrower tiles so that
+enough workgroups exist, against the CPU oracle: every tile shape forced on ragged shapes, and the
+automatic choice on shapes that select each of them.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import qqq_oracle as orc
+from paper_2406_09904_amd import binding as qqq
+from paper_2406_09904_amd import synth
+from tests.util import f16_bits, to_dev, ulp_distance
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def _reset():
+    yield
+    qqq.set_prefill_tuning(0)
+
+
+def run(variant, a_q, s_a, w_nat, s_w, K, s_g=None, sg_max=0):
+    M, N = a_q.shape[0], w_nat.shape[0]
+    d_w = qqq.qqq_pack_w4(to_dev(w_nat, torch), K)
+    d_sw = to_dev(s_w.view(np.uint16), torch)
+    ws = qqq.new_workspace(M, N, K)
+    acc = torch.full((M, N), -12345, dtype=torch.int32, device="cuda")
+    d_a, d_sa = to_dev(a_q, torch), to_dev(s_a, torch)
+    if variant == "pc":
+        y = qqq.qqq_gemm_w4a8_perchannel(d_a, d_sa, d_w, d_sw, ws, acc_out=acc)
+    elif variant == "pg":
+        y = qqq.qqq_gemm_w4a8_pergroup(d_a, d_sa, d_w, to_dev(s_g, torch), d_sw, ws, sg_max=sg_max, acc_out=acc)
+    else:
+        y = qqq.qqq_gemm_w4a8_pergroup_f16scale(d_a, d_sa, d_w, to_dev(s_g, torch), d_sw, ws, acc_out=acc)
+    torch.cuda.synchronize()
+    return acc.cpu().numpy(), f16_bits(y)
+
+
+def reference(variant, a_q, s_a, w, s_w, K, N, seed, hi=16):
+    if variant == "pc":
+        s_g = None
+        o_acc, _, o_y = orc.gemm_perchannel(a_q, s_a, w, s_w.view(np.uint16))
+    elif variant == "pg":
+        s_g = synth.group_scales(K, N, seed, 1, hi)
+        o_acc, _, o_y = orc.gemm_pergroup(a_q, s_a, w, s_g, s_w.view(np.uint16))
+    else:
+        s_g = synth.group_scales_f16(K, N, seed).view(np.uint16)
+        o_acc, _, o_y = orc.gemm_pergroup_f16(a_q, s_a, w, s_g, s_w.view(np.uint16))
+    return s_g, o_acc, o_y
+
+
+def inputs(M, K, N, seed):
+    return (synth.int8_activations(M, K, seed), synth.token_scales(M, seed + 1),
+            synth.random_w_nat(N, K, seed + 2), synth.weight_scales_fp16(N, seed + 3, 0.001, 0.01))
+
+
+def check(acc, y, o_acc, o_y):
+    assert np.array_equal(acc, o_acc), "int32 accumulators differ: %d of %d" % (
+        int((acc != o_acc).sum()), acc.size)
+    assert ulp_distance(y, o_y).max() <= 1
+
+
+@pytest.mark.parametrize("tune", [15, 16, 17])
+@pytest.mark.parametrize("variant,hi,sg_max", [("pc", 0, 0), ("pg", 16, 16), ("pg", 127, 0), ("real", 0, 0)])
+def test_forced_narrow_tiles_on_ragged_shapes(tune, variant, hi, sg_max):
+    for (M, K, N) in ((150, 640, 784), (65, 128, 16), (333, 256, 400)):   # ragged in M and N
+        a_q, s_a, w, s_w = inputs(M, K, N, M + K + N)
+        s_g, o_acc, o_y = reference(variant, a_q, s_a, w, s_w, K, N, 7, hi or 16)
+        qqq.set_prefill_tuning(tune)
+        check(*run(variant, a_q, s_a, w, s_w, K, s_g=s_g, sg_max=sg_max), o_acc, o_y)
+
+
+# automatic choice: 64x128 tiles, 128x128, 128x256, and the large tile
+@pytest.mark.parametrize("M,K,N", [(96, 1024, 4096), (128, 640, 13824), (200, 512, 11008),
+                                   (512, 384, 13824), (1024, 256, 8192), (1000, 256, 2064)])
+@pytest.mark.parametrize("variant", ["pc", "pg", "real"])
+def test_automatic_choice(M, K, N, variant):
+    a_q, s_a, w, s_w = inputs(M, K, N, M + K + N + 1)
+    s_g, o_acc, o_y = reference(variant, a_q, s_a, w, s_w, K, N, 9, 15)
+    check(*run(variant, a_q, s_a, w, s_w, K, s_g=s_g, sg_max=15), o_acc, o_y)
