@@ -225,6 +225,50 @@ def real_scale_lines(wls, torch, qqq, args, use_graph):
     return lines
 
 
+def token_sweep(torch, qqq, synth, use_graph):
+    """The paper's own GEMM-study shape (Sec. 4.4: N=8192, K=21760) over a sweep of token counts:
+    GEMM-kernel time of the per-channel, the integer per-group and the real-valued per-group
+    variant, with the box's fp16 GEMM (torch.matmul, i.e. hipBLASLt/rocBLAS) timed in the same run
+    as context for the speed-up ratios of Fig. 8.  Synthetic inputs as for the other workloads."""
+    import numpy as np
+    N, K = 8192, 21760
+    rows = []
+    w_nat = torch.from_numpy(synth.random_w_nat(N, K, 77).view(np.int32)).cuda()
+    packed = qqq.qqq_pack_w4(w_nat, K)
+    del w_nat
+    copies = 12                                  # 12 x 85 MiB > 1 GiB: cold weights at small M
+    ws_ = [packed] + [packed.clone() for _ in range(copies - 1)]
+    s_w = torch.from_numpy(synth.weight_scales_fp16(N, 78, 0.001, 0.005)).cuda()
+    sg_i = torch.from_numpy(synth.group_scales(K, N, 79, 1, 15)).cuda()
+    sg_f = torch.from_numpy(synth.group_scales_f16(K, N, 80)).cuda()
+    w16 = [torch.randn((N, K), dtype=torch.float16, device="cuda") * 0.02 for _ in range(3)]
+    for M in (1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024, 2048, 4096):
+        a = torch.from_numpy(synth.activations_fp16(M, K, 81 + M)).cuda()
+        a_q, s_a = qqq.qqq_quant_act(a)
+        y = torch.empty((M, N), dtype=torch.float16, device="cuda")
+        wsp = qqq.new_workspace(M, N, K)
+        st = 50 if M <= 64 else (20 if M <= 1024 else 8)
+        fns = {
+            "perchannel_us": lambda i: qqq.qqq_gemm_w4a8_perchannel(a_q, s_a, ws_[i % copies], s_w, wsp, y=y),
+            "pergroup_us": lambda i: qqq.qqq_gemm_w4a8_pergroup(a_q, s_a, ws_[i % copies], sg_i, s_w, wsp,
+                                                                 sg_max=15, y=y),
+            "pergroup_f16scale_us": lambda i: qqq.qqq_gemm_w4a8_pergroup_f16scale(
+                a_q, s_a, ws_[i % copies], sg_f, s_w, wsp, y=y),
+            "fp16_matmul_us": lambda i: torch.matmul(a, w16[i % 3].t(), out=y),
+        }
+        row = {"M": M}
+        for key, fn in fns.items():
+            ms, _ = timed(torch, fn, st, 3, use_graph)
+            row[key] = round(ms * 1e3, 2)
+        row["speedup_perchannel_vs_fp16"] = round(row["fp16_matmul_us"] / row["perchannel_us"], 2)
+        row["speedup_pergroup_vs_fp16"] = round(row["fp16_matmul_us"] / row["pergroup_us"], 2)
+        rows.append(row)
+        print("token sweep M=%d: %s" % (M, row), file=sys.stderr, flush=True)
+    return {"shape": {"N": N, "K": K}, "note": "GEMM kernel only, HIP graph replay, weight copies "
+            "rotated (12 x 85 MiB); fp16_matmul is torch.matmul on fp16 weights (3 copies rotated)",
+            "rows": rows}
+
+
 def cpu_baseline(wl, budget_s=12.0):
     """The oracle, as it stands, on this machine's host cores: whole path on the workload (repeated
     until the time budget is used when one pass is short, on a row subset when one pass is long)."""
@@ -276,6 +320,8 @@ def main():
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="time eager launches, no HIP graph")
+    ap.add_argument("--token-sweep", action="store_true",
+                    help="instead of the benchmark line: the paper's N=8192, K=21760 token sweep")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -297,6 +343,9 @@ def main():
         return 2
 
     use_graph = not args.eager
+    if args.token_sweep:
+        print(json.dumps({"token_sweep": token_sweep(torch, qqq, synth, use_graph)}), flush=True)
+        return 0
     wl = wls[args.workload]
     case = Case(wl, torch, qqq)
     step_ms, gemm_ms, quant_ms, graphed = measure(case, torch, args.steps, args.warmup, use_graph)
