@@ -66,9 +66,14 @@ int qqq_pack_w4(const uint32_t* w_nat, int64_t N, int64_t K, void* w_packed, voi
 int qqq_unpack_w4(const void* w_packed, int64_t N, int64_t K, uint32_t* w_nat, void* stream);
 
 /*
- * Scratch for split-K partial sums and tile counters.  The caller zero-fills it ONCE after
- * allocation; every GEMM call leaves it zero again.  One workspace must not be shared by GEMM
- * calls that may run concurrently (different streams).  Size depends on N only through this call.
+ * Scratch of the GEMM calls.  Its first part (arrival counters and split-K partial sums of the
+ * decode kernel; the whole workspace for M <= 64) must be zero on entry: the caller zero-fills the
+ * workspace ONCE after allocation and every call leaves that part zero again.  For M > 64 it is
+ * followed by scratch of the per-group variant's pre-pass (per-group row sums of the activations
+ * and a transposed copy of the group scales), which a call overwrites and no call relies on.  The
+ * decode kernel (M <= 64) requires the workspace; for M > 64 it is optional (without it, or with a
+ * smaller one, the per-group variant uses its costlier per-weight conversion).  One workspace must
+ * not be shared by GEMM calls that may run concurrently (different streams).
  */
 size_t qqq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 

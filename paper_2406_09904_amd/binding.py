@@ -134,6 +134,12 @@ def qqq_gemm_workspace_bytes(M: int, N: int, K: int) -> int:
     return int(lib().qqq_gemm_workspace_bytes(M, N, K))
 
 
+def split_k_part(workspace: torch.Tensor, M: int, N: int, K: int) -> torch.Tensor:
+    """The part of a GEMM workspace that every call leaves zero (arrival counters and split-K partial
+    sums); what follows it for M > 64 is scratch of the per-group pre-pass and holds no invariant."""
+    return workspace[:qqq_gemm_workspace_bytes(min(M, 64), N, K)]
+
+
 def new_workspace(M: int, N: int, K: int, device="cuda") -> torch.Tensor:
     """Zero-filled workspace (zeroed once here; every GEMM call leaves it zero)."""
     return torch.zeros((max(qqq_gemm_workspace_bytes(M, N, K), 16),), dtype=torch.uint8, device=device)

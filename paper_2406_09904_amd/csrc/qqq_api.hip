@@ -48,6 +48,14 @@ static int group_mode(int sg_max, int64_t M) {
 }
 
 static size_t ws_rows(int64_t M) { return (size_t)(M < kSkinnyMaxM ? M : kSkinnyMaxM); }
+static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+// pre-pass buffers of the biased per-group route (prefill only): Rl, Rh [M][Gp], Bc [N][Gp]
+static size_t bias_rows_bytes(int64_t M, int64_t K) {
+  return M > kSkinnyMaxM ? align256((size_t)M * (size_t)(((K / 128) + 31) & ~31)) : 0;
+}
+static size_t bias_cols_bytes(int64_t M, int64_t N, int64_t K) {
+  return M > kSkinnyMaxM ? align256((size_t)N * (size_t)(((K / 128) + 31) & ~31)) : 0;
+}
 static size_t ws_counter_bytes(int64_t N) { return ((size_t)(N / 16) * 4 + 255) & ~(size_t)255; }
 
 static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed, const int8_t* s_g,
@@ -85,6 +93,7 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
   p.T = (int)(K / 128);
   p.ws_cnt = nullptr;
   p.ws_acc = nullptr;
+  p.r_lo = p.r_hi = p.bias_w = nullptr;
   p.a_fp16 = (const uint4*)a_fp16;
   p.lda_vec = lda / 8;
   if (fused && family != 1) return set_error(QQQ_ERR_SHAPE, "gemm: fused quantisation needs the decode kernel");
@@ -100,6 +109,21 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
   }
   const int64_t tiles = ((M + 127) / 128) * ((N + 511) / 512);
   const int tune = get_prefill_tuning();
+  // Clamp-free per-group request with a workspace of the queried size: the biased integer
+  // conversion (a pre-pass computes the per-group row sums it needs) instead of the fp16 FMA one
+  if (mode == kGroupFused && g_group_mode == 0 && workspace &&
+      workspace_bytes >= qqq_gemm_workspace_bytes(M, N, K) && (tune == 0 || tune == 10 || tune >= 15)) {
+    char* base = (char*)workspace + ws_counter_bytes(N) + align256(ws_rows(M) * (size_t)N * 4);
+    int8_t* r_lo = (int8_t*)base;
+    int8_t* r_hi = (int8_t*)(base + bias_rows_bytes(M, K));
+    int8_t* bc = (int8_t*)(base + 2 * bias_rows_bytes(M, K));
+    const int rc = launch_group_bias_prepass(a_q, s_g, M, N, K, r_lo, r_hi, bc, (hipStream_t)stream);
+    if (rc != QQQ_OK) return rc;
+    p.r_lo = r_lo;
+    p.r_hi = r_hi;
+    p.bias_w = bc;
+    mode = kGroupBias;
+  }
   if ((tune >= 10 && tune <= 12) || (tune >= 15 && tune <= 17))
     return launch_gemm_prefill_dma(p, mode, tune >= 15 ? tune - 12 : tune - 10, (hipStream_t)stream);
   if (tune == 13) return launch_gemm_prefill_ring(p, mode, (hipStream_t)stream);
@@ -125,7 +149,8 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
       }
     }
     if (best != 0) return launch_gemm_prefill_dma(p, mode, best, (hipStream_t)stream);
-    if (mode == kGroupReal) return launch_gemm_prefill_dma(p, mode, 0, (hipStream_t)stream);
+    if (mode == kGroupReal || mode == kGroupBias)
+      return launch_gemm_prefill_dma(p, mode, 0, (hipStream_t)stream);
     // Measured on MI355X: the persistent kernel wins for the per-channel variant at every K and
     // for the per-group variant when tiles are short (its per-k-step cost is a little higher
     // there, its per-tile cost much lower).
@@ -136,8 +161,6 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
   }
   return launch_gemm_prefill(p, mode, (hipStream_t)stream);
 }
-
-static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 static bool fused_ok(int64_t M, int64_t K) {
   return g_override == 0 && g_fuse_quant && M >= 1 && M <= kFusedMaxM && M * K <= kFusedLdsBytes;
@@ -239,7 +262,8 @@ int qqq_unpack_w4(const void* w_packed, int64_t N, int64_t K, uint32_t* w_nat, v
 
 size_t qqq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
   if (!gemm_shape_ok(M, N, K)) return 0;
-  return ws_counter_bytes(N) + ws_rows(M) * (size_t)N * 4;
+  return ws_counter_bytes(N) + align256(ws_rows(M) * (size_t)N * 4) + 2 * bias_rows_bytes(M, K) +
+         bias_cols_bytes(M, N, K);
 }
 
 int qqq_gemm_w4a8_perchannel(const int8_t* a_q, const float* s_a, const void* w_packed,

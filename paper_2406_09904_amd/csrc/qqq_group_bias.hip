@@ -1,0 +1,69 @@
+// Pre-pass of the per-group prefill GEMM's "biased" conversion route (integer group scales <= 16).
+//
+// That route forms the int8 weight of Sec. 3.3.2 with integer byte arithmetic instead of the fp16
+// FMA: with u = code + 8 in [0,15], u*s fits a byte for s <= 16 (one 16-bit packed multiply scales
+// four of them) and flipping the top bit reads it as the signed value u*s - 128 = code*s + (8s-128).
+// The GEMM therefore accumulates  acc' = acc + sum_g (8*s_g[g][n] - 128) * R[m][g]  with
+// R[m][g] = sum of the activation codes of row m in group g, and takes that correction out at the
+// end.  The correction is itself a small int8 GEMM over the groups: -R = 128*Rh + Rl with
+// Rl in [0,127], Rh in [-127,127] (|R| <= 127*128), and Bc[n][g] = 8*s_g[g][n] - 128 in [-128,0].
+// This kernel writes Rl, Rh ([M][Gp]) and Bc ([N][Gp]), Gp = groups rounded up to 32, zero padded.
+#include "qqq_internal.h"
+
+namespace qqq {
+
+// one workgroup per activation row; 8 lanes sum one group (16 bytes each)
+__global__ __launch_bounds__(256) void group_rowsum_kernel(const int8_t* __restrict__ a_q, int K, int G,
+                                                           int Gp, int8_t* __restrict__ r_lo,
+                                                           int8_t* __restrict__ r_hi) {
+  const int64_t m = blockIdx.x;
+  const v4i* row = reinterpret_cast<const v4i*>(a_q + m * (int64_t)K);
+  const int chunks = K >> 4;  // 16-byte pieces; 8 per group
+  for (int c0 = 0; c0 < chunks; c0 += 256) {
+    const int c = c0 + (int)threadIdx.x;
+    int sum = 0;
+    if (c < chunks) {
+      const v4i v = row[c];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) sum = __builtin_amdgcn_sdot4(v[i], 0x01010101, sum, false);
+    }
+    // lanes 8j..8j+7 hold one group (chunks is a multiple of 8, so a group never straddles waves)
+    sum += __shfl_xor(sum, 1, 64);
+    sum += __shfl_xor(sum, 2, 64);
+    sum += __shfl_xor(sum, 4, 64);
+    if ((threadIdx.x & 7) == 0 && c < chunks) {
+      const int g = c >> 3;
+      const int neg = -sum;  // the GEMM adds the correction, so the negated sum is stored
+      r_lo[m * Gp + g] = (int8_t)(neg & 127);
+      r_hi[m * Gp + g] = (int8_t)(neg >> 7);
+    }
+  }
+  for (int g = G + (int)threadIdx.x; g < Gp; g += 256) {
+    r_lo[m * Gp + g] = 0;
+    r_hi[m * Gp + g] = 0;
+  }
+}
+
+// Bc[n][g] = 8*s_g[g][n] - 128, zero for the padded groups
+__global__ __launch_bounds__(256) void group_bias_weights_kernel(const int8_t* __restrict__ s_g, int N,
+                                                                 int G, int Gp, int8_t* __restrict__ bc) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;  // over [Gp][N], n fastest (coalesced reads)
+  if (idx >= (int64_t)Gp * N) return;
+  const int g = (int)(idx / N);
+  const int n = (int)(idx - (int64_t)g * N);
+  bc[(int64_t)n * Gp + g] = (g < G) ? (int8_t)(8 * (int)s_g[idx] - 128) : (int8_t)0;
+}
+
+int launch_group_bias_prepass(const int8_t* a_q, const int8_t* s_g, int64_t M, int64_t N, int64_t K,
+                              int8_t* r_lo, int8_t* r_hi, int8_t* bc, hipStream_t st) {
+  const int G = (int)(K / 128), Gp = (G + 31) & ~31;
+  hipLaunchKernelGGL(group_rowsum_kernel, dim3((unsigned)M), dim3(256), 0, st, a_q, (int)K, G, Gp, r_lo, r_hi);
+  const int64_t total = (int64_t)Gp * N;
+  hipLaunchKernelGGL(group_bias_weights_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                     s_g, (int)N, G, Gp, bc);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return set_error(QQQ_ERR_HIP, "group bias pre-pass launch: %s", hipGetErrorString(e));
+  return QQQ_OK;
+}
+
+}  // namespace qqq

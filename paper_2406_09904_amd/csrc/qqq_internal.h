@@ -19,6 +19,9 @@ enum Mode : int {
                       // the group's partial int32 sum instead of to each weight (same integers)
   kGroupClamp = 2,    // Sec. 3.3.2, general: code*s_g saturated to int8 per weight (fp16 route)
   kGroupFused = 3,    // Sec. 3.3.2 with s_g <= 16: per-weight fp16 FMA + byte extract, no clamp
+  kGroupBias = 5,     // Sec. 3.3.2 with s_g <= 16, prefill: byte-wise integer multiply of code+8, sign by a
+                      // top-bit flip; the constant 8*s_g - 128 per weight is taken out again through
+                      // per-group row sums of the activations (see qqq_group_bias.hip)
   kGroupReal = 4,     // Sec. 3.3.2 as printed: real-valued fp16 fused scale s*_Wg, one fp16 FMA with
                       // 128 + 1024, low byte, XOR 0x80, no saturation; s_g then points at fp16 data
 };
@@ -34,6 +37,10 @@ struct GemmParams {
   int32_t* ws_cnt;      // [N/16] arrival counters (zero between calls)
   int32_t* ws_acc;      // [ws_rows,N] split-K partial sums (zero between calls)
   int M, N, K, T;       // T = K/128
+  // kGroupBias only: pre-pass outputs, [M][Gp], [M][Gp], [N][Gp] int8, Gp = K/128 rounded up to 32
+  const int8_t* r_lo;
+  const int8_t* r_hi;
+  const int8_t* bias_w;
   // fused activation quantisation (decode kernel only): fp16 rows instead of a_q/s_a
   const uint4* a_fp16;  // [M, lda] fp16 as 128-bit vectors, or nullptr
   int64_t lda_vec;      // row stride of a_fp16 in 128-bit vectors
@@ -49,6 +56,8 @@ int launch_quant_act(const void* a, int64_t M, int64_t K, int64_t lda, int8_t* a
 int launch_pack(const uint32_t* w_nat, int64_t N, int64_t K, uint32_t* w_packed, bool inverse,
                 hipStream_t st);
 int launch_gemm_skinny(const GemmParams& p, int mode, hipStream_t st);
+int launch_group_bias_prepass(const int8_t* a_q, const int8_t* s_g, int64_t M, int64_t N, int64_t K,
+                              int8_t* r_lo, int8_t* r_hi, int8_t* bc, hipStream_t st);
 int launch_gemm_prefill(const GemmParams& p, int mode, hipStream_t st);
 void set_skinny_tuning(int nt, int s, int w, int u);
 void set_prefill_tuning(int waves);
@@ -181,6 +190,20 @@ __device__ __forceinline__ uint32_t quant4(uint32_t w0, uint32_t w1, float s) {
   const int q3 = (int)fminf(fmaxf(__builtin_rintf(x3 / s), -127.0f), 127.0f);
   return (uint32_t)(q0 & 0xFF) | ((uint32_t)(q1 & 0xFF) << 8) | ((uint32_t)(q2 & 0xFF) << 16) |
          ((uint32_t)(q3 & 0xFF) << 24);
+}
+
+// Sec. 3.3.2, integer scale s <= 16, biased route: u = code + 8 per nibble, four u per dword scaled
+// by one 16-bit packed multiply (u*s <= 240 stays inside its byte), top bit flipped: each byte
+// is then code*s + (8s - 128) as int8.  7 VALU ops per 8 weights.
+__device__ __forceinline__ void unpack_group_bias(uint32_t x, uint32_t s2, int& lo, int& hi) {
+  const uint32_t ulo = (x ^ 0x88888888u) & 0x0F0F0F0Fu;
+  const uint32_t uhi = ((x >> 4) ^ 0x08080808u) & 0x0F0F0F0Fu;
+  typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+  const us2 sv = __builtin_bit_cast(us2, s2);
+  const us2 plo = __builtin_bit_cast(us2, ulo) * sv;
+  const us2 phi = __builtin_bit_cast(us2, uhi) * sv;
+  lo = (int)(__builtin_bit_cast(uint32_t, plo) ^ 0x80808080u);
+  hi = (int)(__builtin_bit_cast(uint32_t, phi) ^ 0x80808080u);
 }
 
 // Sec. 3.3.2 with the real-valued fused scale, step by step: FastINT4toFP16 (0x6400|u is 1024+u,

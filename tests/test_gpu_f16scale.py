@@ -33,7 +33,7 @@ def run(a_q, s_a, w_nat, s_g_bits, s_w, K, family=0):
                                             to_dev(s_g_bits, torch), to_dev(s_w.view(np.uint16), torch),
                                             ws, acc_out=acc)
     torch.cuda.synchronize()
-    assert not ws.any(), "workspace not returned to zero"
+    assert not qqq.split_k_part(ws, M, N, K).any(), "workspace not returned to zero"
     return acc.cpu().numpy(), f16_bits(y)
 
 

@@ -32,7 +32,6 @@ def run_linear(a, w_nat, s_w, K, s_g=None, sg_max=0, fused=1, d_a=None):
     d_w = qqq.qqq_pack_w4(to_dev(w_nat, torch), K)
     d_sw = to_dev(s_w.view(np.uint16), torch)
     ws = qqq.new_linear_workspace(M, N, K)
-    gemm_ws_bytes = qqq.qqq_gemm_workspace_bytes(M, N, K)
     acc = torch.full((M, N), -12345, dtype=torch.int32, device="cuda")
     qqq.set_fused_quant(fused)
     if s_g is None:
@@ -40,7 +39,7 @@ def run_linear(a, w_nat, s_w, K, s_g=None, sg_max=0, fused=1, d_a=None):
     else:
         y = qqq.qqq_linear_w4a8_pergroup(d_a, d_w, to_dev(s_g, torch), d_sw, ws, sg_max=sg_max, acc_out=acc)
     torch.cuda.synchronize()
-    assert not ws[:gemm_ws_bytes].any(), "split-K part of the workspace not returned to zero"
+    assert not qqq.split_k_part(ws, M, N, K).any(), "split-K part of the workspace not returned to zero"
     return acc.cpu().numpy(), f16_bits(y)
 
 

@@ -41,7 +41,7 @@ def run_gemm(a_q, s_a, w_nat, s_w, K, s_g=None, sg_max=0, family=0, group_mode=0
         y = qqq.qqq_gemm_w4a8_pergroup(d_a, d_sa, d_w, to_dev(s_g, torch), d_sw, ws, sg_max=sg_max,
                                        acc_out=acc)
     torch.cuda.synchronize()
-    return acc.cpu().numpy(), f16_bits(y), ws.cpu().numpy()
+    return acc.cpu().numpy(), f16_bits(y), qqq.split_k_part(ws, M, N, K).cpu().numpy()
 
 
 def check(acc, y, ws, o_acc, o_y):
