@@ -44,23 +44,41 @@ __global__ __launch_bounds__(256) void group_rowsum_kernel(const int8_t* __restr
   }
 }
 
-// Bc[n][g] = 8*s_g[g][n] - 128, zero for the padded groups
+// Bc[n][g] = 8*s_g[g][n] - 128, zero for the padded groups: a transpose of [G][N] into [N][Gp]
+// through a 32 x 64 LDS tile, so that reads (along n) and writes (along g) are both contiguous
 __global__ __launch_bounds__(256) void group_bias_weights_kernel(const int8_t* __restrict__ s_g, int N,
                                                                  int G, int Gp, int8_t* __restrict__ bc) {
-  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;  // over [Gp][N], n fastest (coalesced reads)
-  if (idx >= (int64_t)Gp * N) return;
-  const int g = (int)(idx / N);
-  const int n = (int)(idx - (int64_t)g * N);
-  bc[(int64_t)n * Gp + g] = (g < G) ? (int8_t)(8 * (int)s_g[idx] - 128) : (int8_t)0;
+  __shared__ int8_t tile[32][64 + 4];
+  const int g0 = blockIdx.y * 32, n0 = blockIdx.x * 64;
+  const int tid = threadIdx.x;
+  // 32 rows (groups) x 64 columns (channels): 8 passes of 256 threads
+#pragma unroll
+  for (int pass = 0; pass < 8; ++pass) {
+    const int r = pass * 4 + (tid >> 6), c = tid & 63;
+    const int g = g0 + r, n = n0 + c;
+    tile[r][c] = (g < G && n < N) ? (int8_t)(8 * (int)s_g[(int64_t)g * N + n] - 128) : (int8_t)0;
+  }
+  __syncthreads();
+  // 64 channels x 32 groups out: thread -> channel tid/4, 8 consecutive groups
+  const int c = tid >> 2, r0 = (tid & 3) * 8;
+  const int n = n0 + c;
+  if (n < N) {
+    uint32_t lo = 0, hi = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      lo |= (uint32_t)(uint8_t)tile[r0 + i][c] << (8 * i);
+      hi |= (uint32_t)(uint8_t)tile[r0 + 4 + i][c] << (8 * i);
+    }
+    *reinterpret_cast<uint2*>(bc + (int64_t)n * Gp + g0 + r0) = make_uint2(lo, hi);
+  }
 }
 
 int launch_group_bias_prepass(const int8_t* a_q, const int8_t* s_g, int64_t M, int64_t N, int64_t K,
                               int8_t* r_lo, int8_t* r_hi, int8_t* bc, hipStream_t st) {
   const int G = (int)(K / 128), Gp = (G + 31) & ~31;
   hipLaunchKernelGGL(group_rowsum_kernel, dim3((unsigned)M), dim3(256), 0, st, a_q, (int)K, G, Gp, r_lo, r_hi);
-  const int64_t total = (int64_t)Gp * N;
-  hipLaunchKernelGGL(group_bias_weights_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                     s_g, (int)N, G, Gp, bc);
+  hipLaunchKernelGGL(group_bias_weights_kernel, dim3((unsigned)((N + 63) / 64), (unsigned)(Gp / 32)),
+                     dim3(256), 0, st, s_g, (int)N, G, Gp, bc);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return set_error(QQQ_ERR_HIP, "group bias pre-pass launch: %s", hipGetErrorString(e));
   return QQQ_OK;
