@@ -13,10 +13,9 @@
 namespace qqq {
 
 // one workgroup per activation row; 8 lanes sum one group (16 bytes each)
-__global__ __launch_bounds__(256) void group_rowsum_kernel(const int8_t* __restrict__ a_q, int K, int G,
-                                                           int Gp, int8_t* __restrict__ r_lo,
-                                                           int8_t* __restrict__ r_hi) {
-  const int64_t m = blockIdx.x;
+__device__ __forceinline__ void group_rowsum(const int8_t* __restrict__ a_q, int K, int G, int Gp,
+                                             int8_t* __restrict__ r_lo, int8_t* __restrict__ r_hi,
+                                             int64_t m) {
   const v4i* row = reinterpret_cast<const v4i*>(a_q + m * (int64_t)K);
   const int chunks = K >> 4;  // 16-byte pieces; 8 per group
   for (int c0 = 0; c0 < chunks; c0 += 256) {
@@ -46,10 +45,10 @@ __global__ __launch_bounds__(256) void group_rowsum_kernel(const int8_t* __restr
 
 // Bc[n][g] = 8*s_g[g][n] - 128, zero for the padded groups: a transpose of [G][N] into [N][Gp]
 // through a 32 x 64 LDS tile, so that reads (along n) and writes (along g) are both contiguous
-__global__ __launch_bounds__(256) void group_bias_weights_kernel(const int8_t* __restrict__ s_g, int N,
-                                                                 int G, int Gp, int8_t* __restrict__ bc) {
+__device__ __forceinline__ void group_bias_weights(const int8_t* __restrict__ s_g, int N, int G, int Gp,
+                                                   int8_t* __restrict__ bc, int tile_n, int tile_g) {
   __shared__ int8_t tile[32][64 + 4];
-  const int g0 = blockIdx.y * 32, n0 = blockIdx.x * 64;
+  const int g0 = tile_g * 32, n0 = tile_n * 64;
   const int tid = threadIdx.x;
   // 32 rows (groups) x 64 columns (channels): 8 passes of 256 threads
 #pragma unroll
@@ -73,12 +72,28 @@ __global__ __launch_bounds__(256) void group_bias_weights_kernel(const int8_t* _
   }
 }
 
+// both parts in one launch: workgroups [0, M) sum the activation rows, the rest transpose the scales
+__global__ __launch_bounds__(256) void group_bias_prepass_kernel(const int8_t* __restrict__ a_q,
+                                                                 const int8_t* __restrict__ s_g, int M,
+                                                                 int N, int K, int G, int Gp,
+                                                                 int8_t* __restrict__ r_lo,
+                                                                 int8_t* __restrict__ r_hi,
+                                                                 int8_t* __restrict__ bc) {
+  if ((int)blockIdx.x < M) {
+    group_rowsum(a_q, K, G, Gp, r_lo, r_hi, (int64_t)blockIdx.x);
+  } else {
+    const int t = (int)blockIdx.x - M, tiles_n = (N + 63) / 64;
+    group_bias_weights(s_g, N, G, Gp, bc, t % tiles_n, t / tiles_n);
+  }
+}
+
 int launch_group_bias_prepass(const int8_t* a_q, const int8_t* s_g, int64_t M, int64_t N, int64_t K,
                               int8_t* r_lo, int8_t* r_hi, int8_t* bc, hipStream_t st) {
   const int G = (int)(K / 128), Gp = (G + 31) & ~31;
-  hipLaunchKernelGGL(group_rowsum_kernel, dim3((unsigned)M), dim3(256), 0, st, a_q, (int)K, G, Gp, r_lo, r_hi);
-  hipLaunchKernelGGL(group_bias_weights_kernel, dim3((unsigned)((N + 63) / 64), (unsigned)(Gp / 32)),
-                     dim3(256), 0, st, s_g, (int)N, G, Gp, bc);
+  const int64_t blocks = M + (int64_t)((N + 63) / 64) * (Gp / 32);
+  if (blocks > 0x7FFFFFFF) return set_error(QQQ_ERR_SHAPE, "group bias pre-pass: grid too large");
+  hipLaunchKernelGGL(group_bias_prepass_kernel, dim3((unsigned)blocks), dim3(256), 0, st, a_q, s_g, (int)M,
+                     (int)N, (int)K, G, Gp, r_lo, r_hi, bc);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return set_error(QQQ_ERR_HIP, "group bias pre-pass launch: %s", hipGetErrorString(e));
   return QQQ_OK;
