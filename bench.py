@@ -225,6 +225,56 @@ def real_scale_lines(wls, torch, qqq, args, use_graph):
     return lines
 
 
+def conversion_ablation(torch, qqq, wls, use_graph):
+    """Per-group prefill GEMM on the cfg4 shape with each way of turning int4 code x group scale into
+    int8 (Sec. 3.3.2; the paper's Fig. 9 ablates FastFP16toINT8 against the conventional conversion
+    instruction).  Same kernel family and tile shape; only the conversion differs.  The per-channel
+    GEMM on the same shape is the no-conversion reference."""
+    wl = wls["cfg4_pg_m4096_k11008_n4096"]
+    c = Case(wl, torch, qqq, rotate_bytes=1 << 28)
+    sg16 = torch.from_numpy(wl.s_g_f16()).cuda()
+    rows = []
+
+    def t(fn):
+        ms, _ = timed(torch, fn, 20, 5, use_graph)
+        return round(ms * 1e3, 1)
+
+    def pg(i):
+        qqq.qqq_gemm_w4a8_pergroup(c.a_q, c.s_a, c.w[i % c.copies], c.s_g[i % c.copies], c.s_w, c.ws,
+                                   sg_max=15, y=c.y)
+
+    def pg_any(i):
+        qqq.qqq_gemm_w4a8_pergroup(c.a_q, c.s_a, c.w[i % c.copies], c.s_g[i % c.copies], c.s_w, c.ws,
+                                   sg_max=0, y=c.y)
+
+    def real(i):
+        qqq.qqq_gemm_w4a8_pergroup_f16scale(c.a_q, c.s_a, c.w[i % c.copies], sg16, c.s_w, c.ws, y=c.y)
+
+    def pc(i):
+        qqq.qqq_gemm_w4a8_perchannel(c.a_q, c.s_a, c.w[i % c.copies], c.s_w, c.ws, y=c.y)
+
+    qqq.set_prefill_tuning(10)                      # one kernel and tile shape for every line
+    rows.append({"route": "per-channel (FastINT4toINT8, no group scale)", "gemm_us": t(pc)})
+    rows.append({"route": "integer scale <= 16: packed 16-bit multiply + bias removal (default)",
+                 "gemm_us": t(pg)})
+    qqq.set_group_mode_override(3)
+    rows.append({"route": "integer scale <= 16: fp16 FMA with folded constants + byte permute",
+                 "gemm_us": t(pg)})
+    qqq.set_group_mode_override(0)
+    rows.append({"route": "integer scale, any: fp16 multiply, clamp, add, byte permute", "gemm_us": t(pg_any)})
+    rows.append({"route": "real-valued scale: FastINT4toFP16 + FMA(128+1024) + permute + XOR (paper)",
+                 "gemm_us": t(real)})
+    qqq.set_group_mode_override(4)
+    rows.append({"route": "real-valued scale: fp16 multiply + conventional round/convert + packing",
+                 "gemm_us": t(real)})
+    qqq.set_group_mode_override(0)
+    qqq.set_prefill_tuning(0)
+    for r in rows:
+        r["tops"] = round(c.ops / (r["gemm_us"] * 1e-6) / 1e12, 1)
+    return {"shape": {"M": wl.M, "K": wl.K, "N": wl.N}, "kernel": "gemm_prefill_dma_kernel, 128x512 tile",
+            "rows": rows}
+
+
 def token_sweep(torch, qqq, synth, use_graph):
     """The paper's own GEMM-study shape (Sec. 4.4: N=8192, K=21760) over a sweep of token counts:
     GEMM-kernel time of the per-channel, the integer per-group and the real-valued per-group
@@ -320,6 +370,9 @@ def main():
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="time eager launches, no HIP graph")
+    ap.add_argument("--conversion-ablation", action="store_true",
+                    help="instead of the benchmark line: the int4->int8 conversion routes of the "
+                         "per-group prefill GEMM on the cfg4 shape (Sec. 4.5.2, Fig. 9)")
     ap.add_argument("--token-sweep", action="store_true",
                     help="instead of the benchmark line: the paper's N=8192, K=21760 token sweep")
     args = ap.parse_args()
@@ -343,6 +396,9 @@ def main():
         return 2
 
     use_graph = not args.eager
+    if args.conversion_ablation:
+        print(json.dumps({"conversion_ablation": conversion_ablation(torch, qqq, wls, use_graph)}), flush=True)
+        return 0
     if args.token_sweep:
         print(json.dumps({"token_sweep": token_sweep(torch, qqq, synth, use_graph)}), flush=True)
         return 0

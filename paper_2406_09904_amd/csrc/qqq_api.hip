@@ -43,7 +43,7 @@ static bool gemm_shape_ok(int64_t M, int64_t N, int64_t K) {
 static int group_mode(int sg_max, int64_t M) {
   int mode = kGroupClamp;
   if (sg_max >= 1 && sg_max <= 16) mode = (M <= kSkinnyMaxM) ? kGroupLinear : kGroupFused;
-  if (g_group_mode != 0) mode = g_group_mode;
+  if (g_group_mode >= 1 && g_group_mode <= 3) mode = g_group_mode;
   return mode;
 }
 
@@ -109,6 +109,7 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
   }
   const int64_t tiles = ((M + 127) / 128) * ((N + 511) / 512);
   const int tune = get_prefill_tuning();
+  if (mode == kGroupCvt) return launch_gemm_prefill_dma(p, mode, 0, (hipStream_t)stream);
   // Clamp-free per-group request with a workspace of the queried size: the biased integer
   // conversion (a pre-pass computes the per-group row sums it needs) instead of the fp16 FMA one
   if (mode == kGroupFused && g_group_mode == 0 && workspace &&
@@ -223,7 +224,7 @@ int qqq_quant_act(const void* a_fp16, int64_t M, int64_t K, int64_t lda, int8_t*
 
 int qqq_set_group_mode_override(int mode) {
   const int old = g_group_mode;
-  if (mode >= 0 && mode <= 3) g_group_mode = mode;
+  if (mode >= 0 && mode <= 4) g_group_mode = mode;
   return old;
 }
 
@@ -290,8 +291,10 @@ int qqq_gemm_w4a8_pergroup_f16scale(const int8_t* a_q, const float* s_a, const v
                                     void* y_fp16, int32_t* acc_out, int64_t M, int64_t N, int64_t K,
                                     void* workspace, size_t workspace_bytes, void* stream) {
   if (group != QQQ_GROUP) return set_error(QQQ_ERR_SHAPE, "pergroup: group must be 128, got %d", group);
+  // knob 4: the conventional-conversion ablation of Fig. 9 (prefill kernel only)
+  const int mode = (g_group_mode == 4 && M > kSkinnyMaxM) ? kGroupCvt : kGroupReal;
   return gemm_common(a_q, s_a, w_packed, (const int8_t*)s_g_fp16, s_w_fp16, y_fp16, acc_out, M, N, K,
-                     workspace, workspace_bytes, stream, kGroupReal);
+                     workspace, workspace_bytes, stream, mode);
 }
 
 size_t qqq_linear_workspace_bytes(int64_t M, int64_t N, int64_t K) {

@@ -83,7 +83,7 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
   // group scales of the wave's 32*CT channels: the first 8*CT lanes fetch 4 bytes each, the other
   // lanes (and channels past N) re-read a valid dword; each lane writes its own LDS dword
   // (fp16 scales of the real-valued variant: the first 16*CT lanes fetch two scales each)
-  constexpr int kSgBytes = (MODE == kGroupReal) ? 2 : 1;  // bytes per group scale
+  constexpr int kSgBytes = (MODE == kGroupReal || MODE == kGroupCvt) ? 2 : 1;  // bytes per group scale
   constexpr int kSgPerLane = 4 / kSgBytes, kSgLanes = 32 * CT / kSgPerLane;
   const int8_t* sg_src = nullptr;
   if constexpr (MODE != kPerChannel) {
@@ -168,7 +168,7 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
       wq[c][0] = *(const uint4*)(sb + w_off + c * 2048);
       wq[c][1] = *(const uint4*)(sb + w_off + c * 2048 + 512);
       sg[c] = 0;
-      if constexpr (MODE == kGroupReal)
+      if constexpr (MODE == kGroupReal || MODE == kGroupCvt)
         sg[c] = (int)*(const uint16_t*)(sb + sg_off + c * 64);
       else if constexpr (MODE != kPerChannel)
         sg[c] = (int)sb[sg_off + c * 32];
@@ -360,6 +360,7 @@ int launch_gemm_prefill_dma(const GemmParams& p, int mode, int shape, hipStream_
     case kGroupLinear:
     case kGroupFused: return launch_shape<kGroupFused>(p, shape, st);
     case kGroupReal: return launch_shape<kGroupReal>(p, shape, st);
+    case kGroupCvt: return launch_dma<kGroupCvt, 4, 2, 8>(p, st);  // timing ablation: one shape
     case kGroupBias:  // the 8-wave shapes only (the others gain nothing from it)
       if (shape == 3) return launch_dma<kGroupBias, 4, 1, 8>(p, st);
       if (shape == 4) return launch_dma<kGroupBias, 4, 1, 4>(p, st);

@@ -22,6 +22,8 @@ enum Mode : int {
   kGroupBias = 5,     // Sec. 3.3.2 with s_g <= 16, prefill: byte-wise integer multiply of code+8, sign by a
                       // top-bit flip; the constant 8*s_g - 128 per weight is taken out again through
                       // per-group row sums of the activations (see qqq_group_bias.hip)
+  kGroupCvt = 6,      // ablation only (Sec. 4.5.2, Fig. 9): the real-valued scale through conventional
+                      // conversion instructions instead of FastFP16toINT8
   kGroupReal = 4,     // Sec. 3.3.2 as printed: real-valued fp16 fused scale s*_Wg, one fp16 FMA with
                       // 128 + 1024, low byte, XOR 0x80, no saturation; s_g then points at fp16 data
 };
@@ -227,6 +229,24 @@ __device__ __forceinline__ void unpack_group_real(uint32_t x, h2 s2, int& lo, in
   const h2 f3 = __builtin_elementwise_fma(c3, s2, magic);
   lo = (int)(__builtin_amdgcn_perm(as_u32(f2), as_u32(f0), 0x06020400u) ^ 0x80808080u);
   hi = (int)(__builtin_amdgcn_perm(as_u32(f3), as_u32(f1), 0x06020400u) ^ 0x80808080u);
+}
+
+// Ablation counterpart of unpack_group_real (Sec. 4.5.2, Fig. 9: what FastFP16toINT8 replaces): the
+// same fp16 code and scale, but a plain fp16 multiply followed by the conventional conversion
+// instructions (round to nearest even, fp16 -> int16) and byte packing.  Two roundings instead of
+// one, so it equals the FMA route only where code*s is exact in fp16 (e.g. scales that are
+// multiples of 1/16); it exists to be timed, not used.
+__device__ __forceinline__ void unpack_group_cvt(uint32_t x, h2 s2, int& lo, int& hi) {
+  const uint32_t y = x ^ 0x88888888u;
+  const uint32_t y8 = y >> 8;
+  const h2 off_lo = {(_Float16)1032.0f, (_Float16)1032.0f}, off_hi = {(_Float16)72.0f, (_Float16)72.0f};
+  const h2 p0 = (as_h2((y & 0x000F000Fu) | 0x64006400u) - off_lo) * s2;   // nibbles 0,4
+  const h2 p1 = (as_h2((y & 0x00F000F0u) | 0x54005400u) - off_hi) * s2;   // nibbles 1,5
+  const h2 p2 = (as_h2((y8 & 0x000F000Fu) | 0x64006400u) - off_lo) * s2;  // nibbles 2,6
+  const h2 p3 = (as_h2((y8 & 0x00F000F0u) | 0x54005400u) - off_hi) * s2;  // nibbles 3,7
+  auto to_byte = [](_Float16 v) { return (uint32_t)((int)(short)__builtin_rintf16(v)) & 0xFFu; };
+  lo = (int)(to_byte(p0[0]) | (to_byte(p2[0]) << 8) | (to_byte(p0[1]) << 16) | (to_byte(p2[1]) << 24));
+  hi = (int)(to_byte(p1[0]) | (to_byte(p3[0]) << 8) | (to_byte(p1[1]) << 16) | (to_byte(p3[1]) << 24));
 }
 
 // Dequant (Sec. 3.3.1/3.3.2 last step): int32 -> fp32 -> two fp32 multiplies -> fp16 (RNE).

@@ -23,11 +23,16 @@ __device__ __forceinline__ v4i convert_b(uint32_t d0, uint32_t d1, int sg) {
     const uint32_t s2 = (uint32_t)sg | ((uint32_t)sg << 16);
     unpack_group_bias(d0, s2, o[0], o[1]);
     unpack_group_bias(d1, s2, o[2], o[3]);
-  } else if constexpr (MODE == kGroupReal) {
+  } else if constexpr (MODE == kGroupReal || MODE == kGroupCvt) {
     // sg carries the fp16 bit pattern of the fused scale
     const h2 s2 = as_h2((uint32_t)sg | ((uint32_t)sg << 16));
-    unpack_group_real(d0, s2, o[0], o[1]);
-    unpack_group_real(d1, s2, o[2], o[3]);
+    if constexpr (MODE == kGroupReal) {
+      unpack_group_real(d0, s2, o[0], o[1]);
+      unpack_group_real(d1, s2, o[2], o[3]);
+    } else {
+      unpack_group_cvt(d0, s2, o[0], o[1]);
+      unpack_group_cvt(d1, s2, o[2], o[3]);
+    }
   } else {
     const GroupFusedConsts g = make_group_fused(sg);
     unpack_group_fused(d0, g, o[0], o[1]);

@@ -117,3 +117,23 @@ def test_integer_valued_scales_match_the_integer_scale_entry_point():
                                     to_dev(s_w.view(np.uint16), torch), ws, sg_max=15, acc_out=acc2)
     torch.cuda.synchronize()
     assert np.array_equal(acc, acc2.cpu().numpy()) and np.array_equal(y, f16_bits(y2))
+
+
+def test_conventional_conversion_ablation_on_exact_products():
+    """Knob 4 (the Fig. 9 ablation route: fp16 multiply, round, fp16->int16, byte packing) rounds twice;
+    with scales that are multiples of 1/8 below 16 every product code*s is exact in fp16, so it must
+    give the oracle's integers."""
+    M, K, N = 200, 640, 528
+    g = synth.rng(5)
+    a_q = synth.int8_activations(M, K, 21)
+    s_a = synth.token_scales(M, 22)
+    w = synth.random_w_nat(N, K, 23)
+    s_g = (g.integers(-127, 128, (K // 128, N)) / 8.0).astype(np.float16)
+    s_w = synth.weight_scales_fp16(N, 24, 0.001, 0.005)
+    o_acc, _, o_y = orc.gemm_pergroup_f16(a_q, s_a, w, s_g.view(np.uint16), s_w.view(np.uint16))
+    old = qqq.set_group_mode_override(4)
+    try:
+        acc, y = run(a_q, s_a, w, s_g.view(np.uint16), s_w, K)
+    finally:
+        qqq.set_group_mode_override(old)
+    check(acc, y, o_acc, o_y)
