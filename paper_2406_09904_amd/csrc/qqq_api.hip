@@ -56,12 +56,27 @@ static size_t bias_rows_bytes(int64_t M, int64_t K) {
 static size_t bias_cols_bytes(int64_t M, int64_t N, int64_t K) {
   return M > kSkinnyMaxM ? align256((size_t)N * (size_t)(((K / 128) + 31) & ~31)) : 0;
 }
+static size_t ws_counter_bytes(int64_t N);
+static size_t ws_rows(int64_t M);
+static void bias_buffers(void* workspace, int64_t M, int64_t N, int64_t K, int8_t*& r_lo, int8_t*& r_hi,
+                         int8_t*& bc);
 static size_t ws_counter_bytes(int64_t N) { return ((size_t)(N / 16) * 4 + 255) & ~(size_t)255; }
+
+static void bias_buffers(void* workspace, int64_t M, int64_t N, int64_t K, int8_t*& r_lo, int8_t*& r_hi,
+                         int8_t*& bc) {
+  char* base = (char*)workspace + ws_counter_bytes(N) + align256(ws_rows(M) * (size_t)N * 4);
+  r_lo = (int8_t*)base;
+  r_hi = (int8_t*)(base + bias_rows_bytes(M, K));
+  bc = (int8_t*)(base + 2 * bias_rows_bytes(M, K));
+}
+
+// does gemm_common take the biased per-group route for this call? (same conditions as in there)
+static bool takes_bias_route(int mode, int64_t M, int tune);
 
 static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed, const int8_t* s_g,
                        const void* s_w, void* y, int32_t* acc_out, int64_t M, int64_t N, int64_t K,
                        void* workspace, size_t workspace_bytes, void* stream, int mode,
-                       const void* a_fp16 = nullptr, int64_t lda = 0) {
+                       const void* a_fp16 = nullptr, int64_t lda = 0, bool row_sums_ready = false) {
   if (!gemm_shape_ok(M, N, K))
     return set_error(QQQ_ERR_SHAPE, "gemm: unsupported shape M=%lld N=%lld K=%lld (need N%%16==0, "
                      "K%%128==0, 128<=K<=131072)", (long long)M, (long long)N, (long long)K);
@@ -112,13 +127,11 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
   if (mode == kGroupCvt) return launch_gemm_prefill_dma(p, mode, 0, (hipStream_t)stream);
   // Clamp-free per-group request with a workspace of the queried size: the biased integer
   // conversion (a pre-pass computes the per-group row sums it needs) instead of the fp16 FMA one
-  if (mode == kGroupFused && g_group_mode == 0 && workspace &&
-      workspace_bytes >= qqq_gemm_workspace_bytes(M, N, K) && (tune == 0 || tune == 10 || tune >= 15)) {
-    char* base = (char*)workspace + ws_counter_bytes(N) + align256(ws_rows(M) * (size_t)N * 4);
-    int8_t* r_lo = (int8_t*)base;
-    int8_t* r_hi = (int8_t*)(base + bias_rows_bytes(M, K));
-    int8_t* bc = (int8_t*)(base + 2 * bias_rows_bytes(M, K));
-    const int rc = launch_group_bias_prepass(a_q, s_g, M, N, K, r_lo, r_hi, bc, (hipStream_t)stream);
+  if (takes_bias_route(mode, M, tune) && workspace && workspace_bytes >= qqq_gemm_workspace_bytes(M, N, K)) {
+    int8_t *r_lo, *r_hi, *bc;
+    bias_buffers(workspace, M, N, K, r_lo, r_hi, bc);
+    const int rc = launch_group_bias_prepass(a_q, s_g, M, N, K, r_lo, r_hi, bc, !row_sums_ready,
+                                             (hipStream_t)stream);
     if (rc != QQQ_OK) return rc;
     p.r_lo = r_lo;
     p.r_hi = r_hi;
@@ -163,6 +176,11 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
   return launch_gemm_prefill(p, mode, (hipStream_t)stream);
 }
 
+static bool takes_bias_route(int mode, int64_t M, int tune) {
+  return mode == kGroupFused && M > kSkinnyMaxM && g_group_mode == 0 && g_override != 1 &&
+         (tune == 0 || tune == 10 || tune >= 15);
+}
+
 static bool fused_ok(int64_t M, int64_t K) {
   return g_override == 0 && g_fuse_quant && M >= 1 && M <= kFusedMaxM && M * K <= kFusedLdsBytes;
 }
@@ -189,9 +207,15 @@ static int linear_common(const void* a_fp16, int64_t lda, const void* w_packed, 
                        stream, mode, a_fp16, lda);
   float* s_a = (float*)((char*)workspace + gemm_ws);
   int8_t* a_q = (int8_t*)((char*)workspace + gemm_ws + align256((size_t)M * 4));
-  const int rc = launch_quant_act(a_fp16, M, K, lda, a_q, s_a, (hipStream_t)stream);
+  // the per-group prefill GEMM's biased route wants per-group row sums of the codes: the quantiser
+  // has them in registers, so it writes them on the way
+  int8_t *r_lo = nullptr, *r_hi = nullptr, *bc = nullptr;
+  const bool sums = takes_bias_route(mode, M, get_prefill_tuning());
+  if (sums) bias_buffers(workspace, M, N, K, r_lo, r_hi, bc);
+  const int rc = launch_quant_act(a_fp16, M, K, lda, a_q, s_a, (hipStream_t)stream, r_lo, r_hi);
   if (rc != QQQ_OK) return rc;
-  return gemm_common(a_q, s_a, w_packed, s_g, s_w, y, acc_out, M, N, K, workspace, gemm_ws, stream, mode);
+  return gemm_common(a_q, s_a, w_packed, s_g, s_w, y, acc_out, M, N, K, workspace, gemm_ws, stream, mode,
+                     nullptr, 0, sums);
 }
 
 }  // namespace qqq

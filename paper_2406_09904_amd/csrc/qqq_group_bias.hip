@@ -87,9 +87,11 @@ __global__ __launch_bounds__(256) void group_bias_prepass_kernel(const int8_t* _
   }
 }
 
+// with_row_sums == false: the activation quantiser already wrote Rl/Rh (one-call linear path)
 int launch_group_bias_prepass(const int8_t* a_q, const int8_t* s_g, int64_t M, int64_t N, int64_t K,
-                              int8_t* r_lo, int8_t* r_hi, int8_t* bc, hipStream_t st) {
+                              int8_t* r_lo, int8_t* r_hi, int8_t* bc, bool with_row_sums, hipStream_t st) {
   const int G = (int)(K / 128), Gp = (G + 31) & ~31;
+  if (!with_row_sums) M = 0;
   const int64_t blocks = M + (int64_t)((N + 63) / 64) * (Gp / 32);
   if (blocks > 0x7FFFFFFF) return set_error(QQQ_ERR_SHAPE, "group bias pre-pass: grid too large");
   hipLaunchKernelGGL(group_bias_prepass_kernel, dim3((unsigned)blocks), dim3(256), 0, st, a_q, s_g, (int)M,

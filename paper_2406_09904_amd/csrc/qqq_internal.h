@@ -54,12 +54,12 @@ int num_cus();
 
 // launchers; each returns QQQ_OK or QQQ_ERR_HIP/QQQ_ERR_SHAPE
 int launch_quant_act(const void* a, int64_t M, int64_t K, int64_t lda, int8_t* a_q, float* s_a,
-                     hipStream_t st);
+                     hipStream_t st, int8_t* r_lo = nullptr, int8_t* r_hi = nullptr);
 int launch_pack(const uint32_t* w_nat, int64_t N, int64_t K, uint32_t* w_packed, bool inverse,
                 hipStream_t st);
 int launch_gemm_skinny(const GemmParams& p, int mode, hipStream_t st);
 int launch_group_bias_prepass(const int8_t* a_q, const int8_t* s_g, int64_t M, int64_t N, int64_t K,
-                              int8_t* r_lo, int8_t* r_hi, int8_t* bc, hipStream_t st);
+                              int8_t* r_lo, int8_t* r_hi, int8_t* bc, bool with_row_sums, hipStream_t st);
 int launch_gemm_prefill(const GemmParams& p, int mode, hipStream_t st);
 void set_skinny_tuning(int nt, int s, int w, int u);
 void set_prefill_tuning(int waves);
