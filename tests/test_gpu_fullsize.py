@@ -1,7 +1,8 @@
 """GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
 
 Every workload of ``synth.workloads()`` runs the whole hot path on the GPU (qqq_quant_act, then the
-GEMM of its variant with automatic kernel selection).  The activation codes and token scales are
+GEMM of its variant with automatic kernel selection; then the same through the one-call
+qqq_linear_* entry point, which must agree bit for bit).  The activation codes and token scales are
 compared in full (bit-exact).  The int32 accumulators and fp16 outputs are compared on sampled
 entries that the oracle computes one by one (all four corners, the last row/column, tile borders
 and seeded random positions); shapes whose full product the oracle finishes in seconds are also
@@ -83,6 +84,21 @@ def test_full_size_workload(name):
     assert np.array_equal(g_acc, o_acc), "sampled int32 accumulators differ"
     assert ulp_distance(g_y, o_y).max() <= 1, "sampled fp16 outputs differ by more than 1 ulp"
     assert np.abs(o_acc).max() > 0 and np.isfinite(o_y.view(np.float16).astype(np.float32)).all()
+
+    # the one-call entry point bench.py times (fused decode kernel / quantiser that also writes the
+    # per-group row sums + GEMM) must reproduce the two-call result bit for bit, everywhere
+    lws = qqq.new_linear_workspace(M, N, K)
+    acc_l = torch.empty((M, N), dtype=torch.int32, device="cuda")
+    d_a = torch.from_numpy(a).cuda()
+    if pg:
+        y_l = qqq.qqq_linear_w4a8_pergroup(d_a, d_w, torch.from_numpy(s_g).cuda(), d_sw, lws,
+                                           sg_max=wl.sg_hi, acc_out=acc_l)
+    else:
+        y_l = qqq.qqq_linear_w4a8_perchannel(d_a, d_w, d_sw, lws, acc_out=acc_l)
+    torch.cuda.synchronize()
+    assert torch.equal(acc_l, acc), "one-call path: accumulators differ from the two-call path"
+    assert torch.equal(y_l.view(torch.int16), y.view(torch.int16)), "one-call path: outputs differ"
+    del lws, acc_l, y_l, d_a
 
     if float(M) * N * K <= FULL_COMPARE_MACS:
         if pg:
