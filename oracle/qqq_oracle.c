@@ -374,3 +374,115 @@ int qqq_oracle_gemm_samples_f16(const int8_t* a_q, const float* s_a, const uint3
   }
   return ORC_OK;
 }
+
+/* ---------- Offline front-end: symmetric round-to-nearest int4 weights from fp16 ----------
+ *
+ * What the offline (blue) boxes of Fig. 5 and the "scale adjusted offline" remark of
+ * Sec. 3.3.1 need as input: int4 codes and their scales.  The paper says only that the
+ * quantisation is symmetric (Sec. 3.3, first paragraph); the readings taken here:
+ *   scale  = max|w| / 7 over the channel (per-channel) or the group of 128 (per-group),
+ *            fp32 correctly rounded division, stored as fp16 (round to nearest even);
+ *   code   = clamp(rne(w / scale), -7, 7) with the STORED fp16 scale, fp32 correctly
+ *            rounded division, ties to even; the symmetric range keeps |code * s*| inside
+ *            int8 for every scale the per-group rule below can produce;
+ *   a zero scale (all-zero channel/group, or max|w|/7 below half the smallest fp16) gives
+ *   codes 0.
+ * Per-group additionally (Fig. 4, Fig. 5):
+ *   dequantised weight  w~ = code * s_Wg   (exact in fp32: 3 x 11 significant bits)
+ *   s_Wc[n]  = max_k |w~[n,k]| / 127, fp32 division, stored as fp16   (fp16 -> int8 scale)
+ *   s*_Wg    = s_Wg / s_Wc, fp32 division, stored as fp16, and never above 18.203125, the
+ *              largest fp16 value whose product with a code of +-7 still rounds inside
+ *              [-127,127]; the cap can only bind where s_Wc is subnormal in fp16 (a channel
+ *              whose largest weight is below about 0.008).  s_Wc = 0 gives s* = 0.
+ *   integer form of the fused scale (for the integer-scale GEMM): clamp(rne(s*), 1, 18).
+ */
+
+static uint16_t scale_bits(float amax, double qmax) {
+  return qqq_oracle_float_to_half((float)((double)amax / qmax));
+}
+
+static int rtn_code(float w, float s) {
+  if (s == 0.0f) return 0;
+  const float q = (float)((double)w / (double)s);
+  double r = nearbyint((double)q);
+  if (r > 7.0) r = 7.0;
+  if (r < -7.0) r = -7.0;
+  return (int)r;
+}
+
+static void put_code(uint32_t* w_nat, int64_t K, int64_t n, int64_t k, int code) {
+  uint32_t* word = &w_nat[n * (K / 8) + k / 8];
+  const int sh = 4 * (int)(k % 8);
+  *word = (*word & ~(0xFu << sh)) | ((uint32_t)(code & 0xF) << sh);
+}
+
+/* Sec. 3.3.1: per-channel scale s_W[n] and codes.  w_fp16 [N, ldw]; w_nat [N, K/8]; s_w [N]. */
+int qqq_oracle_quantize_w4_perchannel(const uint16_t* w_fp16, int64_t N, int64_t K, int64_t ldw,
+                                      uint32_t* w_nat, uint16_t* s_w_fp16) {
+  if (!w_fp16 || !w_nat || !s_w_fp16) return ORC_NULL;
+  if (N < 0 || K <= 0 || K % 8 != 0 || ldw < K) return ORC_SHAPE;
+#pragma omp parallel for schedule(static)
+  for (int64_t n = 0; n < N; ++n) {
+    const uint16_t* row = w_fp16 + n * ldw;
+    float amax = 0.0f;
+    for (int64_t k = 0; k < K; ++k) {
+      const float v = fabsf(qqq_oracle_half_to_float(row[k]));
+      if (v > amax) amax = v;
+    }
+    s_w_fp16[n] = scale_bits(amax, 7.0);
+    const float s = qqq_oracle_half_to_float(s_w_fp16[n]);
+    for (int64_t k = 0; k < K; ++k) put_code(w_nat, K, n, k, rtn_code(qqq_oracle_half_to_float(row[k]), s));
+  }
+  return ORC_OK;
+}
+
+/* Sec. 3.3.2, Fig. 5 (offline part).  Outputs: w_nat [N,K/8]; s_wg [K/group, N] (may be NULL);
+ * s_star [K/group, N]; s_int [K/group, N] (may be NULL); s_wc [N]. */
+int qqq_oracle_quantize_w4_pergroup(const uint16_t* w_fp16, int64_t N, int64_t K, int64_t ldw,
+                                    int64_t group, uint32_t* w_nat, uint16_t* s_wg_fp16,
+                                    uint16_t* s_star_fp16, int8_t* s_int, uint16_t* s_wc_fp16) {
+  if (!w_fp16 || !w_nat || !s_star_fp16 || !s_wc_fp16) return ORC_NULL;
+  if (N < 0 || K <= 0 || group <= 0 || group % 8 != 0 || K % group != 0 || ldw < K) return ORC_SHAPE;
+  const int64_t G = K / group;
+#pragma omp parallel for schedule(static)
+  for (int64_t n = 0; n < N; ++n) {
+    const uint16_t* row = w_fp16 + n * ldw;
+    uint16_t* sg = (uint16_t*)malloc((size_t)G * sizeof(uint16_t));
+    float dmax = 0.0f; /* max_k |w~[n,k]| */
+    for (int64_t g = 0; g < G; ++g) {
+      float amax = 0.0f;
+      for (int64_t k = g * group; k < (g + 1) * group; ++k) {
+        const float v = fabsf(qqq_oracle_half_to_float(row[k]));
+        if (v > amax) amax = v;
+      }
+      sg[g] = scale_bits(amax, 7.0);
+      const float s = qqq_oracle_half_to_float(sg[g]);
+      for (int64_t k = g * group; k < (g + 1) * group; ++k) {
+        const int code = rtn_code(qqq_oracle_half_to_float(row[k]), s);
+        put_code(w_nat, K, n, k, code);
+        const float wd = fabsf((float)code * s);
+        if (wd > dmax) dmax = wd;
+      }
+    }
+    s_wc_fp16[n] = scale_bits(dmax, 127.0);
+    const float s_wc = qqq_oracle_half_to_float(s_wc_fp16[n]);
+    for (int64_t g = 0; g < G; ++g) {
+      uint16_t star = 0;
+      if (s_wc != 0.0f) {
+        const float q = (float)((double)qqq_oracle_half_to_float(sg[g]) / (double)s_wc);
+        star = qqq_oracle_float_to_half(q);
+        if (qqq_oracle_half_to_float(star) > 18.203125f) star = qqq_oracle_float_to_half(18.203125f);
+      }
+      s_star_fp16[g * N + n] = star;
+      if (s_wg_fp16) s_wg_fp16[g * N + n] = sg[g];
+      if (s_int) {
+        double r = nearbyint((double)qqq_oracle_half_to_float(star));
+        if (r < 1.0) r = 1.0;
+        if (r > 18.0) r = 18.0;
+        s_int[g * N + n] = (int8_t)r;
+      }
+    }
+    free(sg);
+  }
+  return ORC_OK;
+}

@@ -73,6 +73,9 @@ def lib():
             L.qqq_oracle_w8_pergroup_f16.argtypes = [pu32, pu16, i64, i64, i64, pi8]
             L.qqq_oracle_gemm_pergroup_f16.argtypes = [pi8, pf32, pu32, pu16, pu16, i64, i64, i64,
                                                        i64, pi32, pf32, pu16]
+            L.qqq_oracle_quantize_w4_perchannel.argtypes = [pu16, i64, i64, i64, pu32, pu16]
+            L.qqq_oracle_quantize_w4_pergroup.argtypes = [pu16, i64, i64, i64, i64, pu32, pu16, pu16,
+                                                          pi8, pu16]
             L.qqq_oracle_gemm_samples_f16.argtypes = [pi8, pf32, pu32, pu16, pu16, i64, i64, i64, i64,
                                                       pi64, pi64, i64, pi64, pu16]
             _lib = L
@@ -285,3 +288,32 @@ def gemm_samples_f16(a_q, s_a, w_nat, s_g_fp16_bits, s_w_fp16_bits, idx_m, idx_n
                                              _p(im, ctypes.c_int64), _p(jn, ctypes.c_int64), im.size,
                                              _p(acc, ctypes.c_int64), _p(y16, ctypes.c_uint16)))
     return acc, y16
+
+
+def quantize_w4_perchannel(w_fp16_bits):
+    """Offline front-end, per-channel (Sec. 3.3.1): fp16 bits [N,K] -> (w_nat [N,K/8], s_w fp16 bits [N])."""
+    w = _c(w_fp16_bits, np.uint16)
+    N, K = w.shape
+    w_nat = np.zeros((N, K // 8), np.uint32)
+    s_w = np.empty(N, np.uint16)
+    _check(lib().qqq_oracle_quantize_w4_perchannel(_p(w, ctypes.c_uint16), N, K, K,
+                                                   _p(w_nat, ctypes.c_uint32), _p(s_w, ctypes.c_uint16)))
+    return w_nat, s_w
+
+
+def quantize_w4_pergroup(w_fp16_bits, group=128):
+    """Offline front-end, per-group (Sec. 3.3.2, Fig. 5): fp16 bits [N,K] ->
+    (w_nat, s_Wg fp16 bits [G,N], s*_Wg fp16 bits [G,N], integer s* int8 [G,N], s_Wc fp16 bits [N])."""
+    w = _c(w_fp16_bits, np.uint16)
+    N, K = w.shape
+    G = K // group
+    w_nat = np.zeros((N, K // 8), np.uint32)
+    s_wg = np.empty((G, N), np.uint16)
+    s_star = np.empty((G, N), np.uint16)
+    s_int = np.empty((G, N), np.int8)
+    s_wc = np.empty(N, np.uint16)
+    _check(lib().qqq_oracle_quantize_w4_pergroup(_p(w, ctypes.c_uint16), N, K, K, group,
+                                                 _p(w_nat, ctypes.c_uint32), _p(s_wg, ctypes.c_uint16),
+                                                 _p(s_star, ctypes.c_uint16), _p(s_int, ctypes.c_int8),
+                                                 _p(s_wc, ctypes.c_uint16)))
+    return w_nat, s_wg, s_star, s_int, s_wc

@@ -83,6 +83,20 @@ def group_scales_f16(K: int, N: int, seed: int, lo: float = 0.5, hi: float = 15.
     return rng(seed).uniform(lo, hi, size=(K // GROUP, N)).astype(np.float16)
 
 
+def weights_fp16(N: int, K: int, seed: int, outlier_frac: float = 0.001,
+                 outlier_scale: float = 8.0) -> np.ndarray:
+    """fp16 [N,K] stand-in for a trained linear layer: N(0, sigma_n^2) with a per-output-channel
+    sigma_n log-uniform in [0.01, 0.04], and floor(outlier_frac*K) input channels scaled up."""
+    g = rng(seed)
+    sigma = np.exp(g.uniform(np.log(0.01), np.log(0.04), size=(N, 1))).astype(np.float32)
+    w = g.standard_normal((N, K), dtype=np.float32) * sigma
+    n_out = int(outlier_frac * K)
+    if n_out:
+        ch = rng(seed ^ 0xC01).choice(K, size=n_out, replace=False)
+        w[:, ch] *= np.float32(outlier_scale)
+    return w.astype(np.float16)
+
+
 @dataclass(frozen=True)
 class Workload:
     """One benchmark configuration: variant, shape and the distributions of its inputs."""
