@@ -275,6 +275,40 @@ def conversion_ablation(torch, qqq, wls, use_graph):
             "rows": rows}
 
 
+def front_end_lines(torch, qqq, synth, use_graph):
+    """Offline weight front-end (fp16 weights -> int4 codes + scales, then the repack) on the two
+    largest benchmark layers.  HBM-bound streaming passes; algorithmic bytes per weight: 2 in,
+    0.5 out for the quantiser (plus the scale tables), 0.5 in + 0.5 out for the repack."""
+    import numpy as np
+    rows = []
+    for name, N, K in (("cfg5 layer", 28672, 8192), ("cfg4 layer", 4096, 11008)):
+        w = torch.from_numpy(synth.weights_fp16(N, K, 31).view(np.int16)).cuda().view(torch.float16)
+        G = K // 128
+        for variant in ("perchannel", "pergroup"):
+            if variant == "perchannel":
+                fn = lambda i: qqq.qqq_quantize_w4_perchannel(w)
+                nbytes = N * K * 2.5 + N * 2
+            else:
+                fn = lambda i: qqq.qqq_quantize_w4_pergroup(w)
+                nbytes = N * K * 2.5 + N * 2 + G * N * 5
+            fn(0)
+            torch.cuda.synchronize()
+            ms, _ = timed(torch, fn, 10, 2, False)        # allocates its outputs: eager launches
+            rows.append({"layer": name, "N": N, "K": K, "kernel": "quant_weight_kernel (%s)" % variant,
+                         "us": round(ms * 1e3, 1), "bound": "hbm",
+                         "achieved_gbs": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                         "frac": round(nbytes / (ms * 1e-3) / (HBM_PEAK_GBS * 1e9), 3)})
+        w_nat, _ = qqq.qqq_quantize_w4_perchannel(w)
+        out = qqq.qqq_pack_w4(w_nat, K)
+        ms, _ = timed(torch, lambda i: qqq.qqq_pack_w4(w_nat, K, out=out), 10, 2, use_graph)
+        rows.append({"layer": name, "N": N, "K": K, "kernel": "pack_w4", "us": round(ms * 1e3, 1), "bound": "hbm",
+                     "achieved_gbs": round(N * K / (ms * 1e-3) / 1e9, 1),
+                     "frac": round(N * K / (ms * 1e-3) / (HBM_PEAK_GBS * 1e9), 3)})
+        del w, w_nat, out
+        torch.cuda.empty_cache()
+    return rows
+
+
 def token_sweep(torch, qqq, synth, use_graph):
     """The paper's own GEMM-study shape (Sec. 4.4: N=8192, K=21760) over a sweep of token counts:
     GEMM-kernel time of the per-channel, the integer per-group and the real-valued per-group
@@ -373,6 +407,8 @@ def main():
     ap.add_argument("--conversion-ablation", action="store_true",
                     help="instead of the benchmark line: the int4->int8 conversion routes of the "
                          "per-group prefill GEMM on the cfg4 shape (Sec. 4.5.2, Fig. 9)")
+    ap.add_argument("--front-end", action="store_true",
+                    help="only the offline weight front-end lines (fp16 weights -> int4 codes + scales, repack)")
     ap.add_argument("--token-sweep", action="store_true",
                     help="instead of the benchmark line: the paper's N=8192, K=21760 token sweep")
     args = ap.parse_args()
@@ -398,6 +434,9 @@ def main():
     use_graph = not args.eager
     if args.conversion_ablation:
         print(json.dumps({"conversion_ablation": conversion_ablation(torch, qqq, wls, use_graph)}), flush=True)
+        return 0
+    if args.front_end:
+        print(json.dumps({"weight_front_end": front_end_lines(torch, qqq, synth, use_graph)}), flush=True)
         return 0
     if args.token_sweep:
         print(json.dumps({"token_sweep": token_sweep(torch, qqq, synth, use_graph)}), flush=True)
@@ -447,6 +486,9 @@ def main():
 
     if not args.no_sweep:
         out["real_valued_group_scale"] = real_scale_lines(wls, torch, qqq, args, use_graph)
+
+    if not args.no_sweep:
+        out["weight_front_end"] = front_end_lines(torch, qqq, synth, use_graph)
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)

@@ -53,6 +53,33 @@ int qqq_quant_act(const void* a_fp16, int64_t M, int64_t K, int64_t lda, int8_t*
                   void* stream);
 
 /*
+ * Offline weight front-end: symmetric round-to-nearest int4 codes and scales from fp16 weights
+ * (the inputs of Sec. 3.3.1's offline scale adjustment and of the offline boxes of Fig. 5).
+ * The paper fixes only "symmetric"; the arithmetic below is this library's reading of it.
+ *   per block b (the whole channel, or a group of 128 along K):
+ *     s_b  = fp16_rne( max_k |W[n,k]| / 7 )                       (fp32 division)
+ *     code = clamp( rne( W[n,k] / s_b ), -7, 7 )                  (fp32 division by the STORED s_b,
+ *            ties to even); s_b == 0 gives codes 0.  Non-finite weights are undefined.
+ *   per-channel: s_w[n] = s_b, the s_W of Fig. 3 (the /16 of Sec. 3.3.1 is applied inside the GEMM).
+ *   per-group (Fig. 4, Fig. 5): s_Wg[g][n] = s_b;
+ *     s_wc[n]      = fp16_rne( max_k |code * s_Wg| / 127 )        (fp16 -> int8 scale s_Wc)
+ *     s_star[g][n] = min( fp16_rne( s_Wg / s_wc ), 18.203125 )    (s*_Wg; 0 where s_wc == 0; the cap,
+ *                    the largest fp16 s with rne(7*s) <= 127, binds only where s_wc is subnormal)
+ *     s_int[g][n]  = clamp( rne( s_star ), 1, 18 )                (for the integer-scale GEMM; then
+ *                    pass sg_max = 0 or 18 there, since 16 < 18)
+ *   w_fp16 [N, ldw] fp16 device, 16-byte aligned, ldw >= K, ldw % 8 == 0; K % 8 == 0 (per-group:
+ *   K % 128 == 0).  w_nat [N, K/8] uint32 device, the natural format qqq_pack_w4 takes.
+ *   s_w / s_wc [N] fp16; s_star, s_wg, s_int [K/128, N] row-major; s_int and s_wg may be NULL.
+ *   With |code| <= 7 every product code * s_star rounds inside [-127,127], so the outputs can be fed
+ *   to qqq_gemm_w4a8_pergroup_f16scale as they are.
+ */
+int qqq_quantize_w4_perchannel(const void* w_fp16, int64_t N, int64_t K, int64_t ldw, uint32_t* w_nat,
+                               void* s_w_fp16, void* stream);
+int qqq_quantize_w4_pergroup(const void* w_fp16, int64_t N, int64_t K, int64_t ldw, int group,
+                             uint32_t* w_nat, void* s_star_fp16, int8_t* s_int, void* s_wc_fp16,
+                             void* s_wg_fp16, void* stream);
+
+/*
  * Offline weight repack (Sec. 3.3.1: weights are prepared offline; the kernels load int4).
  *   w_nat: [N, K/8] uint32, natural interchange format: nibble i (bits 4i..4i+3) of word j of
  *          row n is the 4-bit two's-complement code of W[n, 8j+i].

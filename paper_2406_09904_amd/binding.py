@@ -21,6 +21,7 @@ SYMBOLS = [
     "qqq_gemm_w4a8_pergroup", "qqq_gemm_w4a8_pergroup_f16scale", "qqq_linear_workspace_bytes", "qqq_linear_w4a8_perchannel",
     "qqq_linear_w4a8_pergroup", "qqq_set_fused_quant", "qqq_set_kernel_override",
     "qqq_set_group_mode_override", "qqq_set_skinny_tuning", "qqq_set_prefill_tuning",
+    "qqq_quantize_w4_perchannel", "qqq_quantize_w4_pergroup",
 ]
 
 _lib = None
@@ -61,6 +62,8 @@ def lib():
         L.qqq_linear_w4a8_perchannel.argtypes = [vp, i64, vp, vp, vp, vp, i64, i64, i64, vp, sz, vp]
         L.qqq_linear_w4a8_pergroup.argtypes = [vp, i64, vp, vp, vp, ci, ci, vp, vp, i64, i64, i64,
                                                vp, sz, vp]
+        L.qqq_quantize_w4_perchannel.argtypes = [vp, i64, i64, i64, vp, vp, vp]
+        L.qqq_quantize_w4_pergroup.argtypes = [vp, i64, i64, i64, ci, vp, vp, vp, vp, vp, vp]
         L.qqq_set_fused_quant.argtypes = [ci]
         L.qqq_set_kernel_override.argtypes = [ci]
         L.qqq_set_group_mode_override.argtypes = [ci]
@@ -106,6 +109,42 @@ def qqq_quant_act(a_fp16: torch.Tensor, a_q: torch.Tensor = None, s_a: torch.Ten
     _check(lib().qqq_quant_act(ctypes.c_void_p(a_fp16.data_ptr()), M, K, lda,
                                _ptr(a_q, torch.int8), _ptr(s_a, torch.float32), _stream()))
     return a_q, s_a
+
+
+def _weights_arg(w_fp16):
+    if w_fp16.dtype != torch.float16 or w_fp16.dim() != 2 or w_fp16.stride(1) != 1 or not w_fp16.is_cuda:
+        raise ValueError("w_fp16 must be a 2-D fp16 device tensor with unit inner stride")
+    N, K = w_fp16.shape
+    return N, K, (w_fp16.stride(0) if N > 1 else max(K, w_fp16.stride(0)))
+
+
+def qqq_quantize_w4_perchannel(w_fp16: torch.Tensor):
+    """fp16 weights [N,K] -> (w_nat int32 [N,K/8] natural nibble words, s_w fp16 [N])."""
+    N, K, ldw = _weights_arg(w_fp16)
+    w_nat = torch.empty((N, K // 8), dtype=torch.int32, device=w_fp16.device)
+    s_w = torch.empty((N,), dtype=torch.float16, device=w_fp16.device)
+    _check(lib().qqq_quantize_w4_perchannel(ctypes.c_void_p(w_fp16.data_ptr()), N, K, ldw,
+                                            _ptr(w_nat, torch.int32), _ptr(s_w, torch.float16), _stream()))
+    return w_nat, s_w
+
+
+def qqq_quantize_w4_pergroup(w_fp16: torch.Tensor, group: int = 128, want_int: bool = True,
+                             want_wg: bool = True):
+    """fp16 weights [N,K] -> (w_nat, s_star fp16 [K/128,N], s_int int8 [K/128,N] or None, s_wc fp16 [N],
+    s_wg fp16 [K/128,N] or None)."""
+    N, K, ldw = _weights_arg(w_fp16)
+    dev = w_fp16.device
+    G = K // group if group > 0 else 0
+    w_nat = torch.empty((N, K // 8), dtype=torch.int32, device=dev)
+    s_star = torch.empty((G, N), dtype=torch.float16, device=dev)
+    s_int = torch.empty((G, N), dtype=torch.int8, device=dev) if want_int else None
+    s_wg = torch.empty((G, N), dtype=torch.float16, device=dev) if want_wg else None
+    s_wc = torch.empty((N,), dtype=torch.float16, device=dev)
+    _check(lib().qqq_quantize_w4_pergroup(ctypes.c_void_p(w_fp16.data_ptr()), N, K, ldw, group,
+                                          _ptr(w_nat, torch.int32), _ptr(s_star, torch.float16),
+                                          _ptr(s_int, torch.int8), _ptr(s_wc, torch.float16),
+                                          _ptr(s_wg, torch.float16), _stream()))
+    return w_nat, s_star, s_int, s_wc, s_wg
 
 
 def qqq_packed_w4_bytes(N: int, K: int) -> int:

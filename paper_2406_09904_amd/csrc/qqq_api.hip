@@ -246,6 +246,39 @@ int qqq_quant_act(const void* a_fp16, int64_t M, int64_t K, int64_t lda, int8_t*
   return launch_quant_act(a_fp16, M, K, lda, a_q, s_a, (hipStream_t)stream);
 }
 
+static int quantize_w4_check(const char* who, const void* w_fp16, int64_t N, int64_t K, int64_t ldw,
+                             int64_t k_mult, const void* w_nat, const void* s_ch) {
+  if (N < 0 || N > 0x7FFFFFFF || K < k_mult || K % k_mult != 0 || K > (1 << 24) || ldw < K || ldw % 8 != 0)
+    return set_error(QQQ_ERR_SHAPE, "%s: unsupported N=%lld K=%lld ldw=%lld (need K%%%lld==0, ldw%%8==0, "
+                     "ldw>=K)", who, (long long)N, (long long)K, (long long)ldw, (long long)k_mult);
+  if (N == 0) return QQQ_OK;
+  if (!w_fp16 || !w_nat || !s_ch) return set_error(QQQ_ERR_NULL, "%s: null pointer argument", who);
+  if (!aligned16(w_fp16) || (reinterpret_cast<uintptr_t>(w_nat) & 3u) || (reinterpret_cast<uintptr_t>(s_ch) & 1u))
+    return set_error(QQQ_ERR_SHAPE, "%s: w_fp16 must be 16-byte, w_nat 4-byte and the scales 2-byte aligned", who);
+  return QQQ_OK;
+}
+
+int qqq_quantize_w4_perchannel(const void* w_fp16, int64_t N, int64_t K, int64_t ldw, uint32_t* w_nat,
+                               void* s_w_fp16, void* stream) {
+  const int rc = quantize_w4_check("quantize_w4_perchannel", w_fp16, N, K, ldw, 8, w_nat, s_w_fp16);
+  if (rc != QQQ_OK || N == 0) return rc;
+  return launch_quant_weight(w_fp16, N, K, ldw, false, w_nat, (uint16_t*)s_w_fp16, nullptr, nullptr, nullptr,
+                             (hipStream_t)stream);
+}
+
+int qqq_quantize_w4_pergroup(const void* w_fp16, int64_t N, int64_t K, int64_t ldw, int group,
+                             uint32_t* w_nat, void* s_star_fp16, int8_t* s_int, void* s_wc_fp16,
+                             void* s_wg_fp16, void* stream) {
+  if (group != QQQ_GROUP) return set_error(QQQ_ERR_SHAPE, "quantize_w4_pergroup: group must be %d", QQQ_GROUP);
+  const int rc = quantize_w4_check("quantize_w4_pergroup", w_fp16, N, K, ldw, QQQ_GROUP, w_nat, s_wc_fp16);
+  if (rc != QQQ_OK || N == 0) return rc;
+  if (!s_star_fp16) return set_error(QQQ_ERR_NULL, "quantize_w4_pergroup: null s_star_fp16");
+  if ((reinterpret_cast<uintptr_t>(s_star_fp16) & 1u) || (reinterpret_cast<uintptr_t>(s_wg_fp16) & 1u))
+    return set_error(QQQ_ERR_SHAPE, "quantize_w4_pergroup: fp16 scale tables must be 2-byte aligned");
+  return launch_quant_weight(w_fp16, N, K, ldw, true, w_nat, (uint16_t*)s_wc_fp16, (uint16_t*)s_wg_fp16,
+                             (uint16_t*)s_star_fp16, s_int, (hipStream_t)stream);
+}
+
 int qqq_set_group_mode_override(int mode) {
   const int old = g_group_mode;
   if (mode >= 0 && mode <= 4) g_group_mode = mode;

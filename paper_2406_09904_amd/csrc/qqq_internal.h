@@ -55,6 +55,8 @@ int num_cus();
 // launchers; each returns QQQ_OK or QQQ_ERR_HIP/QQQ_ERR_SHAPE
 int launch_quant_act(const void* a, int64_t M, int64_t K, int64_t lda, int8_t* a_q, float* s_a,
                      hipStream_t st, int8_t* r_lo = nullptr, int8_t* r_hi = nullptr);
+int launch_quant_weight(const void* w, int64_t N, int64_t K, int64_t ldw, bool grouped, uint32_t* w_nat,
+                        uint16_t* s_ch, uint16_t* s_wg, uint16_t* s_star, int8_t* s_int, hipStream_t st);
 int launch_pack(const uint32_t* w_nat, int64_t N, int64_t K, uint32_t* w_packed, bool inverse,
                 hipStream_t st);
 int launch_gemm_skinny(const GemmParams& p, int mode, hipStream_t st);

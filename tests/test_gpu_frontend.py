@@ -1,0 +1,162 @@
+"""GPU parity of the offline weight front-end (symmetric round-to-nearest int4 codes and the scales
+of Sec. 3.3.1 / Sec. 3.3.2 Fig. 5 of the QQQ paper, from fp16 weights) against the CPU oracle.
+Codes, fp16 scale bit patterns and integer scales are all compared bit for bit: the two sides take
+every rounding decision in the same precision (fp32 division, one rounding to fp16, ties to even).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import qqq_oracle as orc
+from paper_2406_09904_amd import binding as qqq
+from paper_2406_09904_amd import synth
+from tests.util import f16_bits, to_dev, ulp_distance
+
+pytestmark = pytest.mark.gpu
+
+
+def dev_w(w16):
+    return torch.from_numpy(w16.view(np.int16)).cuda().view(torch.float16)
+
+
+def bits(t):
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def check_perchannel(w16, d_w=None):
+    d_w = dev_w(w16) if d_w is None else d_w
+    w_nat, s_w = qqq.qqq_quantize_w4_perchannel(d_w)
+    torch.cuda.synchronize()
+    o_nat, o_s = orc.quantize_w4_perchannel(np.ascontiguousarray(w16).view(np.uint16))
+    assert np.array_equal(bits(s_w), o_s), "per-channel scales differ"
+    got = w_nat.cpu().numpy().view(np.uint32)
+    assert np.array_equal(got, o_nat), "codes differ in %d words" % int((got != o_nat).sum())
+
+
+def check_pergroup(w16, d_w=None):
+    d_w = dev_w(w16) if d_w is None else d_w
+    w_nat, s_star, s_int, s_wc, s_wg = qqq.qqq_quantize_w4_pergroup(d_w)
+    torch.cuda.synchronize()
+    o_nat, o_wg, o_star, o_int, o_wc = orc.quantize_w4_pergroup(np.ascontiguousarray(w16).view(np.uint16))
+    assert np.array_equal(bits(s_wg), o_wg), "s_Wg differs"
+    got = w_nat.cpu().numpy().view(np.uint32)
+    assert np.array_equal(got, o_nat), "codes differ in %d words" % int((got != o_nat).sum())
+    assert np.array_equal(bits(s_wc), o_wc), "s_Wc differs"
+    assert np.array_equal(bits(s_star), o_star), "s*_Wg differs"
+    assert np.array_equal(s_int.cpu().numpy(), o_int), "integer fused scale differs"
+
+
+# K/8 vectors per row: below one pass of the workgroup, ragged, every register-resident depth, and
+# the any-K variant that reads the row twice
+@pytest.mark.parametrize("N,K", [(33, 8), (16, 264), (50, 2048), (64, 4096), (9, 5120), (12, 11008),
+                                 (6, 21760), (5, 32768), (3, 33000), (2, 65536)])
+def test_perchannel_matches_oracle(N, K):
+    check_perchannel(synth.weights_fp16(N, K, 100 + N))
+
+
+@pytest.mark.parametrize("N,K", [(48, 128), (100, 1024), (31, 1920), (16, 8192), (10, 11008), (6, 21760),
+                                 (4, 32768), (3, 40960)])
+def test_pergroup_matches_oracle(N, K):
+    check_pergroup(synth.weights_fp16(N, K, 200 + N))
+
+
+def test_wide_dynamic_range_zero_blocks_and_tiny_channels():
+    """Magnitudes from fp16 subnormals to thousands; all-zero channels and groups; channels so small
+    that s_Wc is subnormal in fp16 (the cap on the fused scale may bind)."""
+    g = synth.rng(7)
+    N, K = 96, 2048
+    w = g.standard_normal((N, K)) * 10.0 ** g.uniform(-7, 3, size=(N, 1))
+    w *= 10.0 ** g.uniform(-1, 1, size=(N, K // 128)).repeat(128, axis=1)
+    w16 = w.astype(np.float16)
+    w16[3] = 0
+    w16[4, 256:512] = 0
+    w16[5] = np.float16(6e-8)                                 # the smallest subnormal everywhere
+    w16[6, ::2] = np.float16(65504.0)
+    w16[6, 1::2] = np.float16(-65504.0)
+    check_perchannel(w16)
+    check_pergroup(w16)
+
+
+def test_ties_round_to_even():
+    """Weights exactly half-way between two codes: scale 2^-4 per block (a 7/16 in every group)."""
+    N, K = 8, 256
+    halves = np.array([0.5, 1.5, 2.5, 3.5, 4.5, 5.5, 6.5, -0.5, -1.5, -2.5, -6.5]) / 16.0
+    w = synth.rng(8).choice(halves, size=(N, K))
+    w[:, ::128] = 7.0 / 16.0
+    w16 = w.astype(np.float16)
+    check_perchannel(w16)
+    check_pergroup(w16)
+    w_nat, _ = qqq.qqq_quantize_w4_perchannel(dev_w(w16))
+    nat = w_nat.cpu().numpy().view(np.uint32)
+    c = np.empty((N, K), np.int64)
+    for i in range(8):
+        nib = ((nat >> np.uint32(4 * i)) & np.uint32(0xF)).astype(np.int64)
+        c[:, i::8] = np.where(nib >= 8, nib - 16, nib)
+    assert np.array_equal(c, np.rint(w16.astype(np.float64) * 16).astype(np.int64))   # numpy: half to even
+
+
+def test_row_stride():
+    w16 = synth.weights_fp16(20, 1024 + 64, 9)
+    d = dev_w(w16)
+    check_perchannel(w16[:, :1024], d[:, :1024])
+    check_pergroup(w16[:, :1024], d[:, :1024])
+
+
+def test_empty_and_refused_arguments():
+    e = torch.empty((0, 256), dtype=torch.float16, device="cuda")
+    w_nat, s_w = qqq.qqq_quantize_w4_perchannel(e)
+    assert w_nat.shape == (0, 32) and s_w.shape == (0,)
+    qqq.qqq_quantize_w4_pergroup(e)
+    w = dev_w(synth.weights_fp16(4, 192, 10))
+    with pytest.raises(qqq.QQQError):
+        qqq.qqq_quantize_w4_pergroup(w)                       # K % 128 != 0
+    with pytest.raises(qqq.QQQError):
+        qqq.qqq_quantize_w4_pergroup(dev_w(synth.weights_fp16(4, 256, 10)), group=64)
+    with pytest.raises(qqq.QQQError):
+        qqq.qqq_quantize_w4_perchannel(dev_w(synth.weights_fp16(4, 260, 10)))   # K % 8 != 0
+    with pytest.raises(qqq.QQQError):
+        qqq.qqq_quantize_w4_perchannel(dev_w(synth.weights_fp16(4, 264, 10))[:, 4:260])  # misaligned rows
+
+
+@pytest.mark.parametrize("M", [1, 4, 48, 200])
+def test_linear_layer_from_fp16_weights(M):
+    """fp16 weights and activations in, fp16 outputs out, every stage on the GPU; the oracle runs the
+    same chain.  Per-channel, per-group with the real-valued fused scale, and with its integer form."""
+    K, N = 2048, 256
+    w16 = synth.weights_fp16(N, K, 11)
+    a16 = synth.activations_fp16(M, K, 12)
+    d_w, d_a = dev_w(w16), dev_w(a16)
+    a_q, s_a = orc.quant_act(a16.view(np.uint16))
+
+    w_nat, s_w = qqq.qqq_quantize_w4_perchannel(d_w)
+    ws = qqq.new_linear_workspace(M, N, K)
+    y = qqq.qqq_linear_w4a8_perchannel(d_a, qqq.qqq_pack_w4(w_nat, K), s_w, ws)
+    o_nat, o_s = orc.quantize_w4_perchannel(w16.view(np.uint16))
+    _, _, o_y = orc.gemm_perchannel(a_q, s_a, o_nat, o_s)
+    assert ulp_distance(f16_bits(y), o_y).max() <= 1
+
+    w_nat, s_star, s_int, s_wc, _ = qqq.qqq_quantize_w4_pergroup(d_w)
+    d_aq, d_sa = qqq.qqq_quant_act(d_a)
+    ws = qqq.new_workspace(M, N, K)
+    acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
+    y = qqq.qqq_gemm_w4a8_pergroup_f16scale(d_aq, d_sa, qqq.qqq_pack_w4(w_nat, K), s_star, s_wc, ws, acc_out=acc)
+    o_nat, _, o_star, o_int, o_wc = orc.quantize_w4_pergroup(w16.view(np.uint16))
+    o_acc, _, o_y = orc.gemm_pergroup_f16(a_q, s_a, o_nat, o_star, o_wc)
+    assert np.array_equal(acc.cpu().numpy(), o_acc)
+    assert ulp_distance(f16_bits(y), o_y).max() <= 1
+
+    y = qqq.qqq_gemm_w4a8_pergroup(d_aq, d_sa, qqq.qqq_pack_w4(w_nat, K), s_int, s_wc, ws,
+                                   sg_max=18, acc_out=acc)
+    o_acc, _, o_y = orc.gemm_pergroup(a_q, s_a, o_nat, o_int, o_wc)
+    assert np.array_equal(acc.cpu().numpy(), o_acc)
+    assert ulp_distance(f16_bits(y), o_y).max() <= 1
+
+
+@pytest.mark.parametrize("variant", ["perchannel", "pergroup"])
+def test_full_size_layer(variant):
+    """The largest benchmark layer (N=28672, K=8192), every code and scale against the oracle."""
+    w16 = synth.weights_fp16(28672, 8192, 13)
+    if variant == "perchannel":
+        check_perchannel(w16)
+    else:
+        check_pergroup(w16)
