@@ -153,6 +153,35 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
   // re-fetch the last one (in bounds, never read), which keeps every k-step's wait count the same.
   issue_dma(0, 0);
   issue_dma(T > 1 ? 1 : 0, 1);
+
+  // ---- biased per-group route: the conversion adds the constant (8*s_g - 128) to every weight,
+  // which sums to sum_g Bc[n][g] * R[m][g] over a row.  The pre-pass stored -R = 128*Rh + Rl, so
+  // starting the accumulators at 128 x (Bc x Rh) + Bc x Rl takes it out in advance: a small int8
+  // contraction over the groups with the main loop's operand roles (row operand from the
+  // activations' side, column operand from the weights' side), every lane reading its 16 group
+  // entries straight from memory while the first two k-steps of DMA are in flight.
+  if constexpr (MODE == kGroupBias) {
+    const int Gp = (T + 31) & ~31;
+#pragma unroll
+    for (int c = 0; c < CT; ++c) {
+      const int8_t* bp = p.bias_w + (int64_t)(nvalid[c] ? col[c] : N - 1) * Gp + 16 * h;
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        int mrow = m0 + 32 * mt + n32;
+        if (mrow > M - 1) mrow = M - 1;
+        const int8_t* lp = p.r_lo + (int64_t)mrow * Gp + 16 * h;
+        const int8_t* hp = p.r_hi + (int64_t)mrow * Gp + 16 * h;
+        for (int j = 0; j < Gp; j += 32)
+          acc[mt][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(*(const v4i*)(hp + j), *(const v4i*)(bp + j),
+                                                             acc[mt][c], 0, 0, 0);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[mt][c][v] *= 128;
+        for (int j = 0; j < Gp; j += 32)
+          acc[mt][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(*(const v4i*)(lp + j), *(const v4i*)(bp + j),
+                                                             acc[mt][c], 0, 0, 0);
+      }
+    }
+  }
   wait_all_but_newest_step();
 
   // ---- main loop, software-pipelined by hand and branch-free.  The activation fragments of MFMA
@@ -226,38 +255,6 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
   }
   // the clamped DMA requests of the last two k-steps may still be landing in the ring
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-
-  // ---- biased per-group route: take the constant (8*s_g - 128) per weight out again.  It summed to
-  // sum_g Bc[n][g] * R[m][g]; the pre-pass stored -R = 128*Rh + Rl, so accumulating Bc x Rl into the
-  // tile and 128 x (Bc x Rh) on top subtracts it: a small int8 contraction over the groups with
-  // the main loop's operand roles (row operand from the activations' side, column operand from the
-  // weights' side); every lane reads its 16 group entries straight from memory.  One tile at a time
-  // (the accumulators leave few registers).
-  if constexpr (MODE == kGroupBias) {
-    const int Gp = (T + 31) & ~31;
-#pragma unroll
-    for (int c = 0; c < CT; ++c) {
-      const int8_t* bp = p.bias_w + (int64_t)(nvalid[c] ? col[c] : N - 1) * Gp + 16 * h;
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        int mrow = m0 + 32 * mt + n32;
-        if (mrow > M - 1) mrow = M - 1;
-        const int8_t* lp = p.r_lo + (int64_t)mrow * Gp + 16 * h;
-        const int8_t* hp = p.r_hi + (int64_t)mrow * Gp + 16 * h;
-        v16i th;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) th[v] = 0;
-        for (int j = 0; j < Gp; j += 32) {
-          const v4i b = *(const v4i*)(bp + j);
-          acc[mt][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(*(const v4i*)(lp + j), b, acc[mt][c], 0, 0, 0);
-          th = __builtin_amdgcn_mfma_i32_32x32x32_i8(*(const v4i*)(hp + j), b, th, 0, 0, 0);
-        }
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[mt][c][v] += th[v] * 128;
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    }
-  }
 
   // ---- fused Dequant epilogue.  Lane holds column n32 of each tile; register v of a 32x32 tile is
   // row 8*(v/4) + 4*h + v%4.  The ring is free now (nothing reads it after the last barrier and
