@@ -183,15 +183,23 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
   return max(max(r0, r1), max(r2, r3));
 }
 
+// rne(x / s) for |x / s| <= 127 (s = amax / 127), the quotient being the correctly rounded fp32 one,
+// without dividing in the common case: q~ = x * rcp(s) is within 1.5 * 2^-23 relative of x/s, i.e.
+// within 1.5 * 2^-16 absolute, and the rounded quotient within 2^-17; unless q~ lies within 2^-14 of
+// a half-integer the two therefore round to the same integer.  Only near a tie the IEEE division
+// (never a reciprocal multiply) decides.
+__device__ __forceinline__ int quant1(float x, float s, float rs) {
+  const float q = x * rs;
+  float r = __builtin_rintf(q);
+  if (__builtin_fabsf(q - r) > 0.5f - 0x1p-14f) r = __builtin_rintf(x / s);
+  return (int)__builtin_amdgcn_fmed3f(r, -127.0f, 127.0f);  // guard clamp
+}
+
 __device__ __forceinline__ uint32_t quant4(uint32_t w0, uint32_t w1, float s) {
   // four fp16 values (two dwords) -> four int8 codes packed in one dword
-  const float x0 = half_bits_to_float(w0 & 0xFFFFu), x1 = half_bits_to_float(w0 >> 16);
-  const float x2 = half_bits_to_float(w1 & 0xFFFFu), x3 = half_bits_to_float(w1 >> 16);
-  // IEEE fp32 division (never a reciprocal multiply), then round half to even, then the guard clamp
-  const int q0 = (int)fminf(fmaxf(__builtin_rintf(x0 / s), -127.0f), 127.0f);
-  const int q1 = (int)fminf(fmaxf(__builtin_rintf(x1 / s), -127.0f), 127.0f);
-  const int q2 = (int)fminf(fmaxf(__builtin_rintf(x2 / s), -127.0f), 127.0f);
-  const int q3 = (int)fminf(fmaxf(__builtin_rintf(x3 / s), -127.0f), 127.0f);
+  const float rs = __builtin_amdgcn_rcpf(s);
+  const int q0 = quant1(half_bits_to_float(w0 & 0xFFFFu), s, rs), q1 = quant1(half_bits_to_float(w0 >> 16), s, rs);
+  const int q2 = quant1(half_bits_to_float(w1 & 0xFFFFu), s, rs), q3 = quant1(half_bits_to_float(w1 >> 16), s, rs);
   return (uint32_t)(q0 & 0xFF) | ((uint32_t)(q1 & 0xFF) << 8) | ((uint32_t)(q2 & 0xFF) << 16) |
          ((uint32_t)(q3 & 0xFF) << 24);
 }

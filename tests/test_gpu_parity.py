@@ -112,6 +112,26 @@ def test_quant_act_edge_rows_and_row_stride():
     assert np.array_equal(d_q.cpu().numpy(), o_q) and np.array_equal(d_s.cpu().numpy(), o_s)
 
 
+def test_quant_act_every_fp16_value_under_many_scales():
+    """Each row holds every finite fp16 pattern not above the row's |max| (larger ones zeroed): all
+    quotients x/s the quantiser can meet for that scale, exact ties and their neighbours included."""
+    every = np.arange(1 << 16, dtype=np.uint32).astype(np.uint16)
+    every = every[((every >> 10) & 0x1F) != 31]                 # finite only
+    vals = every.view(np.float16).astype(np.float64)
+    amaxes = [127.0, 63.5, 1.0, 254.0, 0.0124, 3.1416, 65504.0, 6.1e-5, 2.0 ** -24, 1016.0, 100.0, 0.333,
+              7.0, 127.0 * 2.0 ** -10, 5.96e-6, 2049.0]
+    a = np.zeros((len(amaxes), every.size), np.uint16)
+    for r, am in enumerate(amaxes):
+        am16 = float(np.float16(am))
+        a[r] = np.where(np.abs(vals) <= am16, every, 0)
+    o_q, o_s = orc.quant_act(a)
+    d_q, d_s = qqq.qqq_quant_act(to_dev(a, torch))
+    torch.cuda.synchronize()
+    assert np.array_equal(d_s.cpu().numpy().view(np.uint32), o_s.view(np.uint32))
+    bad = d_q.cpu().numpy() != o_q
+    assert not bad.any(), "%d codes differ, first at %s" % (int(bad.sum()), np.argwhere(bad)[:3])
+
+
 # ----------------------------------------------------------------------------- GEMM, small shapes
 SKINNY = [(1, 16, 128), (1, 64, 4096), (3, 48, 384), (16, 272, 1024), (16, 4096, 1024),
           (17, 64, 512), (33, 96, 640), (64, 128, 2048), (8, 1024, 5120)]
