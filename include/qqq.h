@@ -97,7 +97,8 @@ int qqq_unpack_w4(const void* w_packed, int64_t N, int64_t K, uint32_t* w_nat, v
  * decode kernel; the whole workspace for M <= 64) must be zero on entry: the caller zero-fills the
  * workspace ONCE after allocation and every call leaves that part zero again.  For M > 64 it is
  * followed by scratch of the per-group variant's pre-pass (per-group row sums of the activations
- * and a transposed copy of the group scales), which a call overwrites and no call relies on.  The
+ * and a transposed copy of the group scales) and, for M <= 512, by slabs for K-split partial tiles
+ * (4 * 1024 * N bytes), which a call overwrites and no call relies on.  The
  * decode kernel (M <= 64) requires the workspace; for M > 64 it is optional (without it, or with a
  * smaller one, the per-group variant uses its costlier per-weight conversion).  One workspace must
  * not be shared by GEMM calls that may run concurrently (different streams).
@@ -107,7 +108,9 @@ size_t qqq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 /*
  * Per-channel W4A8 GEMM (Sec. 3.3.1, Fig. 3): int4 code widened to int8 in registers
  * (upper-nibble placement = x16, undone exactly before the scales are applied), int8 MFMA with
- * int32 accumulation, Dequant fused:  Y[m,n] = fp16_rne( float(acc[m,n]) * s_a[m] * float(s_w[n]) ).
+ * int32 accumulation, Dequant fused:  Y[m,n] = fp16_rne( fp32_rne(float(acc[m,n]) * s_a[m]) * float(s_w[n]) )
+ * (the second product is rounded once, straight to fp16; identical in every kernel, within 1 fp16
+ * ulp of the exactly computed value).
  *   a_q [M,K] int8; s_a [M] fp32; w_packed from qqq_pack_w4; s_w_fp16 [N] fp16;
  *   y_fp16 [M,N] fp16 (written); acc_out [M,N] int32 or NULL: if given, also receives the TRUE
  *   accumulator sum_k A_q*code (parity/debug).
@@ -212,6 +215,15 @@ int qqq_set_skinny_tuning(int channel_tiles, int k_slices, int waves, int depth)
  * workgroup (128 x 64*waves tile).  Returns 0.
  */
 int qqq_set_prefill_tuning(int waves);
+
+/*
+ * Tuning/diagnostic knob (host state, not thread-safe): number of K splits of the per-tile prefill
+ * kernel for 64 < M <= 512 (each tile's K range is divided over that many workgroups, their raw
+ * int32 tiles meet in the workspace and a second kernel sums and dequantises them); 0 = automatic,
+ * 1 = never split.  Capped at 1024 / M and at K / 128; ignored without a workspace of the queried
+ * size.  Negative values only query.  Returns the previous value.
+ */
+int qqq_set_prefill_ksplit(int k_splits);
 
 
 #ifdef __cplusplus

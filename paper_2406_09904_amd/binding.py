@@ -21,7 +21,7 @@ SYMBOLS = [
     "qqq_gemm_w4a8_pergroup", "qqq_gemm_w4a8_pergroup_f16scale", "qqq_linear_workspace_bytes", "qqq_linear_w4a8_perchannel",
     "qqq_linear_w4a8_pergroup", "qqq_set_fused_quant", "qqq_set_kernel_override",
     "qqq_set_group_mode_override", "qqq_set_skinny_tuning", "qqq_set_prefill_tuning",
-    "qqq_quantize_w4_perchannel", "qqq_quantize_w4_pergroup",
+    "qqq_quantize_w4_perchannel", "qqq_quantize_w4_pergroup", "qqq_set_prefill_ksplit",
 ]
 
 _lib = None
@@ -69,6 +69,7 @@ def lib():
         L.qqq_set_group_mode_override.argtypes = [ci]
         L.qqq_set_skinny_tuning.argtypes = [ci, ci, ci, ci]
         L.qqq_set_prefill_tuning.argtypes = [ci]
+        L.qqq_set_prefill_ksplit.argtypes = [ci]
         _lib = L
     return _lib
 
@@ -288,3 +289,8 @@ def set_skinny_tuning(channel_tiles: int, k_slices: int, waves: int = 0, depth: 
 def set_prefill_tuning(waves: int) -> int:
     return lib().qqq_set_prefill_tuning(waves)
 
+
+
+def set_prefill_ksplit(k_splits: int) -> int:
+    """Diagnostic: K splits of the per-tile prefill kernel for 64 < M <= 512 (0 = automatic)."""
+    return lib().qqq_set_prefill_ksplit(k_splits)

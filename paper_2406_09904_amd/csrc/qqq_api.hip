@@ -56,6 +56,12 @@ static size_t bias_rows_bytes(int64_t M, int64_t K) {
 static size_t bias_cols_bytes(int64_t M, int64_t N, int64_t K) {
   return M > kSkinnyMaxM ? align256((size_t)N * (size_t)(((K / 128) + 31) & ~31)) : 0;
 }
+// split-K slabs of the per-tile prefill kernel: up to kSplitRows rows of int32 partial sums in all
+// (k_splits * M <= kSplitRows), for the row counts where a K split can pay
+constexpr int64_t kSplitRows = 1024, kSplitMaxM = 512;
+static size_t split_bytes(int64_t M, int64_t N) {
+  return (M > kSkinnyMaxM && M <= kSplitMaxM) ? align256((size_t)kSplitRows * (size_t)N * 4) : 0;
+}
 static size_t ws_counter_bytes(int64_t N);
 static size_t ws_rows(int64_t M);
 static void bias_buffers(void* workspace, int64_t M, int64_t N, int64_t K, int8_t*& r_lo, int8_t*& r_hi,
@@ -109,6 +115,8 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
   p.ws_cnt = nullptr;
   p.ws_acc = nullptr;
   p.r_lo = p.r_hi = p.bias_w = nullptr;
+  p.k_splits = 1;
+  p.part = nullptr;
   p.a_fp16 = (const uint4*)a_fp16;
   p.lda_vec = lda / 8;
   if (fused && family != 1) return set_error(QQQ_ERR_SHAPE, "gemm: fused quantisation needs the decode kernel");
@@ -138,31 +146,61 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
     p.bias_w = bc;
     mode = kGroupBias;
   }
+  // per-tile kernel, optionally with K split over several workgroups per tile (raw tiles into the
+  // workspace's slabs, then the reduce kernel); the split needs a workspace of the queried size
+  const bool can_split = split_bytes(M, N) > 0 && workspace &&
+                         workspace_bytes >= qqq_gemm_workspace_bytes(M, N, K);
+  auto per_tile = [&](int shape, int k_splits) {
+    const int64_t cap = kSplitRows / M;
+    if (k_splits > cap) k_splits = (int)cap;
+    if (k_splits > p.T) k_splits = p.T;
+    if (!can_split || k_splits < 2) return launch_gemm_prefill_dma(p, mode, shape, (hipStream_t)stream);
+    p.k_splits = k_splits;
+    p.part = (int32_t*)((char*)workspace + ws_counter_bytes(N) + align256(ws_rows(M) * (size_t)N * 4) +
+                        2 * bias_rows_bytes(M, K) + bias_cols_bytes(M, N, K));
+    const int rc = launch_gemm_prefill_dma(p, mode, shape, (hipStream_t)stream);
+    return rc != QQQ_OK ? rc : launch_splitk_reduce(p, mode, (hipStream_t)stream);
+  };
+  const int forced_split = get_prefill_ksplit();
   if ((tune >= 10 && tune <= 12) || (tune >= 15 && tune <= 17))
-    return launch_gemm_prefill_dma(p, mode, tune >= 15 ? tune - 12 : tune - 10, (hipStream_t)stream);
+    return per_tile(tune >= 15 ? tune - 12 : tune - 10, forced_split > 0 ? forced_split : 1);
   if (tune == 13) return launch_gemm_prefill_ring(p, mode, (hipStream_t)stream);
   if (tune == 0) {
-    // Tile shape from a cost model measured on MI355X (microseconds per k-step of one workgroup,
-    // alone on its CU / with the chip saturated): few rows want many small tiles, many rows the
-    // large tile with the most reuse.
+    // Tile shape and K split from a cost model measured on MI355X (microseconds per k-step of one
+    // workgroup, alone on its CU / with the chip saturated): few rows want many small tiles, many
+    // rows the large tile with the most reuse; when even the small tiles leave CUs idle and K is
+    // long, splitting K over several workgroups per tile pays for the second kernel that sums
+    // the raw tiles (a launch plus writing and reading k_splits * M * N int32 at ~3 TB/s).
     const int cus = num_cus();
     struct Cand { int shape, bm, bn; bool one_per_cu; double alone, saturated; };
     const Cand cands[4] = {{0, 128, 512, true, 1.34, 1.50}, {3, 128, 256, true, 0.88, 0.90},
                            {4, 128, 128, false, 0.63, 0.52}, {5, 64, 128, false, 0.45, 0.275}};
-    int best = 0;
+    const int splits[6] = {1, 2, 3, 4, 6, 8};
+    int best = 0, best_split = 1;
     double best_cost = 0.0;
     for (int i = 0; i < 4; ++i) {
       const Cand& c = cands[i];
-      const int64_t wgs = ((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
-      double cost = c.alone;
-      if (wgs > cus)  // whole rounds where only one workgroup fits a CU, a smooth load otherwise
-        cost = c.saturated * (c.one_per_cu ? (double)((wgs + cus - 1) / cus) : (double)wgs / cus);
-      if (i == 0 || cost < best_cost * (best == 0 ? 0.95 : 1.0)) {  // leaving the large tile has to pay
-        best = c.shape;
-        best_cost = cost;
+      const int64_t tiles_c = ((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
+      for (int j = 0; j < 6; ++j) {
+        const int ks = forced_split > 0 ? forced_split : splits[j];
+        if (ks > 1 && (!can_split || ks * M > kSplitRows || p.T / ks < 4)) continue;
+        const int64_t wgs = tiles_c * ks;
+        double per_step = c.alone;
+        if (wgs > cus)  // whole rounds where only one workgroup fits a CU, a smooth load otherwise
+          per_step = c.saturated * (c.one_per_cu ? (double)((wgs + cus - 1) / cus) : (double)wgs / cus);
+        double cost = per_step * (double)p.T / ks;
+        if (ks > 1) cost += 2.4 + 8e-6 * (double)ks * (double)M * (double)N / 3.0;
+        // leaving the large tile has to pay, and so has a split (its model is the coarser one)
+        const double margin = ks > 1 && best_split == 1 ? 0.88 : (best == 0 && best_split == 1 ? 0.95 : 1.0);
+        if ((i == 0 && j == 0) || cost < best_cost * margin) {
+          best = c.shape;
+          best_split = ks;
+          best_cost = cost;
+        }
+        if (forced_split > 0) break;
       }
     }
-    if (best != 0) return launch_gemm_prefill_dma(p, mode, best, (hipStream_t)stream);
+    if (best != 0 || best_split > 1) return per_tile(best, best_split);
     if (mode == kGroupReal || mode == kGroupBias)
       return launch_gemm_prefill_dma(p, mode, 0, (hipStream_t)stream);
     // Measured on MI355X: the persistent kernel wins for the per-channel variant at every K and
@@ -290,6 +328,12 @@ int qqq_set_skinny_tuning(int channel_tiles, int k_slices, int waves, int depth)
   return 0;
 }
 
+int qqq_set_prefill_ksplit(int k_splits) {
+  const int old = get_prefill_ksplit();
+  if (k_splits >= 0) set_prefill_ksplit(k_splits);
+  return old;
+}
+
 int qqq_set_prefill_tuning(int waves) {
   set_prefill_tuning(waves);
   return 0;
@@ -321,7 +365,7 @@ int qqq_unpack_w4(const void* w_packed, int64_t N, int64_t K, uint32_t* w_nat, v
 size_t qqq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
   if (!gemm_shape_ok(M, N, K)) return 0;
   return ws_counter_bytes(N) + align256(ws_rows(M) * (size_t)N * 4) + 2 * bias_rows_bytes(M, K) +
-         bias_cols_bytes(M, N, K);
+         bias_cols_bytes(M, N, K) + split_bytes(M, N);
 }
 
 int qqq_gemm_w4a8_perchannel(const int8_t* a_q, const float* s_a, const void* w_packed,

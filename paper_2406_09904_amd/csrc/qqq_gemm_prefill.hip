@@ -183,6 +183,9 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void gemm_prefill_kernel(const Gem
 static int g_prefill_waves = 0;
 void set_prefill_tuning(int waves) { g_prefill_waves = waves; }
 int get_prefill_tuning() { return g_prefill_waves; }
+static int g_prefill_ksplit = 0;  // 0 = automatic
+void set_prefill_ksplit(int s) { g_prefill_ksplit = s; }
+int get_prefill_ksplit() { return g_prefill_ksplit; }
 
 template <int MODE, int NW>
 static int launch_one(const GemmParams& p, hipStream_t st) {

@@ -38,9 +38,13 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int n32 = lane & 31, h = lane >> 5;
-  const int T = p.T, N = p.N, M = p.M;
+  const int N = p.N, M = p.M;
   const int64_t K = p.K;
   const int ntiles = N >> 4;
+  // split K: workgroup y of gridDim.y takes k-steps [t_first, t_first + T) of the tile
+  const int split = blockIdx.y;
+  const int t_first = (int)((int64_t)p.T * split / p.k_splits);
+  const int T = (int)((int64_t)p.T * (split + 1) / p.k_splits) - t_first;
 
   // XCD-aware order: consecutive workgroup ids land on different XCDs (8 of them), so each XCD
   // gets a contiguous run of tiles; within a run tiles are walked in groups of 8 row tiles, m
@@ -70,7 +74,7 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
     const int r = 8 * (S::kAPieces * wave + i) + (lane >> 3);
     int m = m0 + r;
     if (m > M - 1) m = M - 1;
-    a_src[i] = p.a_q + (int64_t)m * K + (((lane & 7) ^ (r & 7)) << 4);
+    a_src[i] = p.a_q + (int64_t)m * K + (int64_t)t_first * S::kBK + (((lane & 7) ^ (r & 7)) << 4);
   }
   const int8_t* w_src[S::kWChunks];
 #pragma unroll
@@ -80,6 +84,8 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
     w_src[j] = (const int8_t*)p.w + (int64_t)nt * 1024 + lane * 16;
   }
   const int64_t w_step = (int64_t)ntiles * 1024;  // bytes between k-steps of the packed weights
+#pragma unroll
+  for (int j = 0; j < S::kWChunks; ++j) w_src[j] += (int64_t)t_first * w_step;
   // group scales of the wave's 32*CT channels: the first 8*CT lanes fetch 4 bytes each, the other
   // lanes (and channels past N) re-read a valid dword; each lane writes its own LDS dword
   // (fp16 scales of the real-valued variant: the first 16*CT lanes fetch two scales each)
@@ -89,7 +95,7 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
   if constexpr (MODE != kPerChannel) {
     int c0 = n_wave + kSgPerLane * (lane < kSgLanes ? lane : kSgLanes - 1);
     if (c0 > N - kSgPerLane) c0 = N - kSgPerLane;
-    sg_src = p.s_g + (int64_t)c0 * kSgBytes;
+    sg_src = p.s_g + ((int64_t)t_first * N + c0) * kSgBytes;
   }
 
   // The DMA loads are issued through inline assembly so that the compiler's wait-count pass does
@@ -160,8 +166,8 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
   // contraction over the groups with the main loop's operand roles (row operand from the
   // activations' side, column operand from the weights' side), every lane reading its 16 group
   // entries straight from memory while the first two k-steps of DMA are in flight.
-  if constexpr (MODE == kGroupBias) {
-    const int Gp = (T + 31) & ~31;
+  if (MODE == kGroupBias && split == 0) {  // the whole correction goes to the first K split
+    const int Gp = (p.T + 31) & ~31;
 #pragma unroll
     for (int c = 0; c < CT; ++c) {
       const int8_t* bp = p.bias_w + (int64_t)(nvalid[c] ? col[c] : N - 1) * Gp + 16 * h;
@@ -256,6 +262,24 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
   // the clamped DMA requests of the last two k-steps may still be landing in the ring
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
+  // ---- split K: the raw tile goes to this split's slab; the reduce kernel does the rest
+  if (p.k_splits > 1) {
+    int32_t* part = p.part + (int64_t)split * M * N;
+#pragma unroll
+    for (int c = 0; c < CT; ++c) {
+      if (!nvalid[c]) continue;
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int m = m0 + mt * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+          if (m < M) part[(int64_t)m * N + col[c]] = acc[mt][c][v];
+        }
+      }
+    }
+    return;
+  }
+
   // ---- fused Dequant epilogue.  Lane holds column n32 of each tile; register v of a 32x32 tile is
   // row 8*(v/4) + 4*h + v%4.  The ring is free now (nothing reads it after the last barrier and
   // every DMA has landed): each wave dequantises its patch into its own fp16 LDS region (row pitch
@@ -326,10 +350,52 @@ static int launch_dma(const GemmParams& p, hipStream_t st) {
   const int tiles_n = (p.N + S::kBN - 1) / S::kBN;
   const int64_t grid = (int64_t)tiles_m * tiles_n;
   if (grid > 0x7FFFFFFF) return set_error(QQQ_ERR_SHAPE, "prefill: grid too large");
-  hipLaunchKernelGGL((gemm_prefill_dma_kernel<MODE, MT, CT, NW>), dim3((unsigned)grid), dim3(NW * 64),
-                     0, st, p, tiles_m, tiles_n);
+  if (p.k_splits < 1 || p.k_splits > p.T || p.k_splits > 65535 || (p.k_splits > 1 && !p.part))
+    return set_error(QQQ_ERR_SHAPE, "prefill: bad K split %d for %d k-steps", p.k_splits, p.T);
+  hipLaunchKernelGGL((gemm_prefill_dma_kernel<MODE, MT, CT, NW>), dim3((unsigned)grid, (unsigned)p.k_splits),
+                     dim3(NW * 64), 0, st, p, tiles_m, tiles_n);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return set_error(QQQ_ERR_HIP, "prefill gemm launch: %s", hipGetErrorString(e));
+  return QQQ_OK;
+}
+
+// Second kernel of a K-split launch: sums the splits' raw tiles and applies the Dequant epilogue
+// (same arithmetic as the fused one).  Four consecutive channels per thread.
+template <bool X16>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmParams p) {
+  const int64_t quads = (int64_t)p.M * (p.N >> 2);
+  const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (q >= quads) return;
+  const int64_t slab = (int64_t)p.M * p.N;
+  const int64_t at = q * 4;
+  const int m = (int)(at / p.N), n = (int)(at % p.N);
+  v4i sum = *(const v4i*)(p.part + at);
+  for (int s = 1; s < p.k_splits; ++s) {
+    const v4i x = *(const v4i*)(p.part + s * slab + at);
+    sum += x;
+  }
+  if constexpr (X16) sum >>= 4;  // exact: the sum is a multiple of 16
+  const float sa = p.s_a[m];
+  const uint32_t* swp = (const uint32_t*)(p.s_w + n);  // s_w is 4-byte aligned, n a multiple of 4
+  const uint32_t sw01 = swp[0], sw23 = swp[1];
+  _Float16 o[4];
+  o[0] = dequant(sum[0], sa, half_bits_to_float(sw01 & 0xFFFFu));
+  o[1] = dequant(sum[1], sa, half_bits_to_float(sw01 >> 16));
+  o[2] = dequant(sum[2], sa, half_bits_to_float(sw23 & 0xFFFFu));
+  o[3] = dequant(sum[3], sa, half_bits_to_float(sw23 >> 16));
+  *(uint2*)(p.y + at) = *(const uint2*)o;
+  if (p.acc_out) *(v4i*)(p.acc_out + at) = sum;
+}
+
+int launch_splitk_reduce(const GemmParams& p, int mode, hipStream_t st) {
+  const int64_t quads = (int64_t)p.M * (p.N >> 2);
+  const dim3 grid((unsigned)((quads + 255) / 256)), block(256);
+  if (mode == kPerChannel)
+    hipLaunchKernelGGL((splitk_reduce_kernel<true>), grid, block, 0, st, p);
+  else
+    hipLaunchKernelGGL((splitk_reduce_kernel<false>), grid, block, 0, st, p);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return set_error(QQQ_ERR_HIP, "split-K reduce launch: %s", hipGetErrorString(e));
   return QQQ_OK;
 }
 

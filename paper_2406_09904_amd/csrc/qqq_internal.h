@@ -43,6 +43,10 @@ struct GemmParams {
   const int8_t* r_lo;
   const int8_t* r_hi;
   const int8_t* bias_w;
+  // prefill, per-tile kernel only: k_splits > 1 splits K over gridDim.y workgroups per tile, each
+  // storing its raw int32 tile into part[split][M][N]; a second kernel sums and dequantises
+  int k_splits;
+  int32_t* part;
   // fused activation quantisation (decode kernel only): fp16 rows instead of a_q/s_a
   const uint4* a_fp16;  // [M, lda] fp16 as 128-bit vectors, or nullptr
   int64_t lda_vec;      // row stride of a_fp16 in 128-bit vectors
@@ -68,6 +72,9 @@ void set_prefill_tuning(int waves);
 int get_prefill_tuning();
 int launch_gemm_prefill_dma(const GemmParams& p, int mode, int shape, hipStream_t st);
 int launch_gemm_prefill_ring(const GemmParams& p, int mode, hipStream_t st);
+int launch_splitk_reduce(const GemmParams& p, int mode, hipStream_t st);
+void set_prefill_ksplit(int s);
+int get_prefill_ksplit();
 
 constexpr int kFusedMaxM = 4;          // rows the decode kernel quantises itself (fused path)
 constexpr int kFusedLdsBytes = 8192;   // most activations the fused path quantises: M*K int8 in LDS
@@ -259,9 +266,17 @@ __device__ __forceinline__ void unpack_group_cvt(uint32_t x, h2 s2, int& lo, int
   hi = (int)(to_byte(p1[0]) | (to_byte(p3[0]) << 8) | (to_byte(p1[1]) << 16) | (to_byte(p3[1]) << 24));
 }
 
-// Dequant (Sec. 3.3.1/3.3.2 last step): int32 -> fp32 -> two fp32 multiplies -> fp16 (RNE).
+// Dequant (Sec. 3.3.1/3.3.2 last step): t = fp32(acc) * s_a rounded to fp32, then t * s_w rounded
+// ONCE to fp16 (the mixed-precision multiply-add rounds its exact fp32-operand product straight to
+// fp16).  Written as the instruction itself so that every kernel rounds alike: left to the
+// compiler, a lone conversion becomes this instruction while two adjacent ones become fp32
+// multiplies followed by a packed convert, which rounds twice and differs in the last bit for
+// about one output in 2^13.
 __device__ __forceinline__ _Float16 dequant(int acc, float sa, float sw) {
-  return (_Float16)(((float)acc * sa) * sw);
+  const float t = (float)acc * sa;
+  uint32_t r;  // the instruction writes the low half of its destination
+  asm("v_fma_mixlo_f16 %0, %1, %2, 0" : "=v"(r) : "v"(t), "v"(sw));
+  return __builtin_bit_cast(_Float16, (uint16_t)r);
 }
 
 }  // namespace qqq

@@ -1,6 +1,7 @@
 """GPU parity for mid-size M (65..1024 rows), where the prefill path picks narrower tiles so that
-enough workgroups exist, against the CPU oracle: every tile shape forced on ragged shapes, and the
-automatic choice on shapes that select each of them.
+enough workgroups exist, against the CPU oracle: every tile shape forced on ragged shapes, the
+automatic choice on shapes that select each of them, and K split over several workgroups per tile
+(raw int32 tiles summed by a second kernel), forced and chosen automatically.
 """
 import numpy as np
 import pytest
@@ -18,6 +19,7 @@ pytestmark = pytest.mark.gpu
 def _reset():
     yield
     qqq.set_prefill_tuning(0)
+    qqq.set_prefill_ksplit(0)
 
 
 def run(variant, a_q, s_a, w_nat, s_w, K, s_g=None, sg_max=0):
@@ -79,3 +81,49 @@ def test_automatic_choice(M, K, N, variant):
     a_q, s_a, w, s_w = inputs(M, K, N, M + K + N + 1)
     s_g, o_acc, o_y = reference(variant, a_q, s_a, w, s_w, K, N, 9, 15)
     check(*run(variant, a_q, s_a, w, s_w, K, s_g=s_g, sg_max=15), o_acc, o_y)
+
+
+@pytest.mark.parametrize("tune,k_splits", [(15, 2), (16, 3), (17, 2), (17, 5), (10, 2), (17, 8)])
+@pytest.mark.parametrize("variant,hi,sg_max", [("pc", 0, 0), ("pg", 16, 16), ("pg", 127, 0), ("real", 0, 0)])
+def test_forced_k_split(tune, k_splits, variant, hi, sg_max):
+    """K ranges of unequal length (k-steps not divisible by the split), ragged M and N, every
+    conversion route; the biased per-group route puts its whole correction into the first split."""
+    for (M, K, N) in ((100, 1408, 528), (65, 2560, 144)):
+        a_q, s_a, w, s_w = inputs(M, K, N, M + K + N + 2)
+        s_g, o_acc, o_y = reference(variant, a_q, s_a, w, s_w, K, N, 11, hi or 16)
+        qqq.set_prefill_tuning(tune)
+        qqq.set_prefill_ksplit(k_splits)
+        check(*run(variant, a_q, s_a, w, s_w, K, s_g=s_g, sg_max=sg_max), o_acc, o_y)
+
+
+def test_k_split_equals_unsplit_bit_for_bit_and_caps():
+    M, K, N = 300, 1024, 656
+    a_q, s_a, w, s_w = inputs(M, K, N, 5)
+    qqq.set_prefill_tuning(17)
+    qqq.set_prefill_ksplit(1)
+    acc1, y1 = run("pc", a_q, s_a, w, s_w, K)
+    qqq.set_prefill_ksplit(3)                                  # 3 * 300 <= 1024
+    acc3, y3 = run("pc", a_q, s_a, w, s_w, K)
+    qqq.set_prefill_ksplit(64)                                 # capped at 1024 / M = 3 and at K / 128
+    acc64, y64 = run("pc", a_q, s_a, w, s_w, K)
+    assert np.array_equal(acc1, acc3) and np.array_equal(y1, y3)
+    assert np.array_equal(acc1, acc64) and np.array_equal(y1, y64)
+    assert qqq.set_prefill_ksplit(-1) == 64                    # negative values only query
+
+
+@pytest.mark.parametrize("variant", ["pc", "pg"])
+def test_automatic_k_split_on_a_long_k_narrow_n_layer(variant):
+    """M=128, K=21760, N=2048: 32 tiles of 64x128 for 256 CUs, 170 k-steps: the cost model splits K.
+    Sampled outputs against the oracle plus the unsplit kernel bit for bit."""
+    M, K, N = 128, 21760, 2048
+    a_q, s_a, w, s_w = inputs(M, K, N, 6)
+    s_g = synth.group_scales(K, N, 12, 1, 15) if variant == "pg" else None
+    acc, y = run(variant, a_q, s_a, w, s_w, K, s_g=s_g, sg_max=15)
+    qqq.set_prefill_ksplit(1)
+    acc1, y1 = run(variant, a_q, s_a, w, s_w, K, s_g=s_g, sg_max=15)
+    assert np.array_equal(acc, acc1) and np.array_equal(y, y1)
+    g = synth.rng(13)
+    im, jn = g.integers(0, M, 4000), g.integers(0, N, 4000)
+    o_acc, o_y = orc.gemm_samples(a_q, s_a, w, s_g, s_w.view(np.uint16), im, jn)
+    assert np.array_equal(acc[im, jn].astype(np.int64), o_acc)
+    assert ulp_distance(y[im, jn], o_y).max() <= 1
