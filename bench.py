@@ -286,14 +286,15 @@ def front_end_lines(torch, qqq, synth, use_graph):
         G = K // 128
         for variant in ("perchannel", "pergroup"):
             if variant == "perchannel":
-                fn = lambda i: qqq.qqq_quantize_w4_perchannel(w)
+                res = qqq.qqq_quantize_w4_perchannel(w)
+                fn = lambda i, res=res: qqq.qqq_quantize_w4_perchannel(w, out=res)
                 nbytes = N * K * 2.5 + N * 2
             else:
-                fn = lambda i: qqq.qqq_quantize_w4_pergroup(w)
+                res = qqq.qqq_quantize_w4_pergroup(w)
+                fn = lambda i, res=res: qqq.qqq_quantize_w4_pergroup(w, out=res)
                 nbytes = N * K * 2.5 + N * 2 + G * N * 5
-            fn(0)
             torch.cuda.synchronize()
-            ms, _ = timed(torch, fn, 10, 2, False)        # allocates its outputs: eager launches
+            ms, _ = timed(torch, fn, 10, 2, use_graph)
             rows.append({"layer": name, "N": N, "K": K, "kernel": "quant_weight_kernel (%s)" % variant,
                          "us": round(ms * 1e3, 1), "bound": "hbm",
                          "achieved_gbs": round(nbytes / (ms * 1e-3) / 1e9, 1),

@@ -119,28 +119,35 @@ def _weights_arg(w_fp16):
     return N, K, (w_fp16.stride(0) if N > 1 else max(K, w_fp16.stride(0)))
 
 
-def qqq_quantize_w4_perchannel(w_fp16: torch.Tensor):
-    """fp16 weights [N,K] -> (w_nat int32 [N,K/8] natural nibble words, s_w fp16 [N])."""
+def qqq_quantize_w4_perchannel(w_fp16: torch.Tensor, out=None):
+    """fp16 weights [N,K] -> (w_nat int32 [N,K/8] natural nibble words, s_w fp16 [N]); out = a
+    previous result to write into."""
     N, K, ldw = _weights_arg(w_fp16)
-    w_nat = torch.empty((N, K // 8), dtype=torch.int32, device=w_fp16.device)
-    s_w = torch.empty((N,), dtype=torch.float16, device=w_fp16.device)
+    if out is not None:
+        w_nat, s_w = out
+    else:
+        w_nat = torch.empty((N, K // 8), dtype=torch.int32, device=w_fp16.device)
+        s_w = torch.empty((N,), dtype=torch.float16, device=w_fp16.device)
     _check(lib().qqq_quantize_w4_perchannel(ctypes.c_void_p(w_fp16.data_ptr()), N, K, ldw,
                                             _ptr(w_nat, torch.int32), _ptr(s_w, torch.float16), _stream()))
     return w_nat, s_w
 
 
 def qqq_quantize_w4_pergroup(w_fp16: torch.Tensor, group: int = 128, want_int: bool = True,
-                             want_wg: bool = True):
+                             want_wg: bool = True, out=None):
     """fp16 weights [N,K] -> (w_nat, s_star fp16 [K/128,N], s_int int8 [K/128,N] or None, s_wc fp16 [N],
-    s_wg fp16 [K/128,N] or None)."""
+    s_wg fp16 [K/128,N] or None); out = a previous result to write into."""
     N, K, ldw = _weights_arg(w_fp16)
     dev = w_fp16.device
     G = K // group if group > 0 else 0
-    w_nat = torch.empty((N, K // 8), dtype=torch.int32, device=dev)
-    s_star = torch.empty((G, N), dtype=torch.float16, device=dev)
-    s_int = torch.empty((G, N), dtype=torch.int8, device=dev) if want_int else None
-    s_wg = torch.empty((G, N), dtype=torch.float16, device=dev) if want_wg else None
-    s_wc = torch.empty((N,), dtype=torch.float16, device=dev)
+    if out is not None:
+        w_nat, s_star, s_int, s_wc, s_wg = out
+    else:
+        w_nat = torch.empty((N, K // 8), dtype=torch.int32, device=dev)
+        s_star = torch.empty((G, N), dtype=torch.float16, device=dev)
+        s_int = torch.empty((G, N), dtype=torch.int8, device=dev) if want_int else None
+        s_wg = torch.empty((G, N), dtype=torch.float16, device=dev) if want_wg else None
+        s_wc = torch.empty((N,), dtype=torch.float16, device=dev)
     _check(lib().qqq_quantize_w4_pergroup(ctypes.c_void_p(w_fp16.data_ptr()), N, K, ldw, group,
                                           _ptr(w_nat, torch.int32), _ptr(s_star, torch.float16),
                                           _ptr(s_int, torch.int8), _ptr(s_wc, torch.float16),
