@@ -208,13 +208,12 @@ int qqq_set_skinny_tuning(int channel_tiles, int k_slices, int waves, int depth)
 
 /*
  * Tuning/diagnostic knob (host state, not thread-safe) for the prefill path: 0 = automatic;
- * 10, 11, 12 = the DMA-ring kernel, one workgroup per tile, with a 128x512 tile on 8 waves, a
- * 128x512 tile on 4 waves, a 256x256 tile on 4 waves; 15, 16, 17 = the same kernel with the narrow
- * tiles meant for mid-size M: 128x256 on 8 waves, 128x128 on 4 waves, 64x128 on 4 waves;
- * 13 = the persistent DMA-ring kernel (128x512 tiles, one workgroup per CU); 4 or 8 = the register-staged kernel with that many waves per
- * workgroup (128 x 64*waves tile).  Returns 0.
+ * 10 = the DMA-ring kernel, one workgroup per tile, 128x512 tile on 8 waves; 15, 16, 17 = the same
+ * kernel with the narrow tiles meant for mid-size M: 128x256 on 8 waves, 128x128 on 4 waves,
+ * 64x128 on 4 waves; 13 = the persistent DMA-ring kernel (128x512 tiles, one workgroup per CU).
+ * Other values act like 0.  Returns 0.
  */
-int qqq_set_prefill_tuning(int waves);
+int qqq_set_prefill_tuning(int tune);
 
 /*
  * Tuning/diagnostic knob (host state, not thread-safe): number of K splits of the per-tile prefill

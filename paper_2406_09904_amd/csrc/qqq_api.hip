@@ -32,6 +32,13 @@ int num_cus() {
   return cached[dev];
 }
 
+static int g_prefill_tune = 0;    // 0 = automatic, see qqq_set_prefill_tuning
+static int g_prefill_ksplit = 0;  // 0 = automatic
+void set_prefill_tuning(int tune) { g_prefill_tune = tune; }
+int get_prefill_tuning() { return g_prefill_tune; }
+void set_prefill_ksplit(int s) { g_prefill_ksplit = s; }
+int get_prefill_ksplit() { return g_prefill_ksplit; }
+
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 static bool gemm_shape_ok(int64_t M, int64_t N, int64_t K) {
@@ -162,10 +169,10 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
     return rc != QQQ_OK ? rc : launch_splitk_reduce(p, mode, (hipStream_t)stream);
   };
   const int forced_split = get_prefill_ksplit();
-  if ((tune >= 10 && tune <= 12) || (tune >= 15 && tune <= 17))
-    return per_tile(tune >= 15 ? tune - 12 : tune - 10, forced_split > 0 ? forced_split : 1);
+  if (tune == 10 || (tune >= 15 && tune <= 17))
+    return per_tile(tune >= 15 ? tune - 12 : 0, forced_split > 0 ? forced_split : 1);
   if (tune == 13) return launch_gemm_prefill_ring(p, mode, (hipStream_t)stream);
-  if (tune == 0) {
+  {
     // Tile shape and K split from a cost model measured on MI355X (microseconds per k-step of one
     // workgroup, alone on its CU / with the chip saturated): few rows want many small tiles, many
     // rows the large tile with the most reuse; when even the small tiles leave CUs idle and K is
@@ -211,12 +218,11 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
       return launch_gemm_prefill_ring(p, mode, (hipStream_t)stream);
     return launch_gemm_prefill_dma(p, mode, 0, (hipStream_t)stream);
   }
-  return launch_gemm_prefill(p, mode, (hipStream_t)stream);
 }
 
 static bool takes_bias_route(int mode, int64_t M, int tune) {
   return mode == kGroupFused && M > kSkinnyMaxM && g_group_mode == 0 && g_override != 1 &&
-         (tune == 0 || tune == 10 || tune >= 15);
+         tune != 13;  // every route but the forced persistent kernel carries the biased mode
 }
 
 static bool fused_ok(int64_t M, int64_t K) {
@@ -334,8 +340,8 @@ int qqq_set_prefill_ksplit(int k_splits) {
   return old;
 }
 
-int qqq_set_prefill_tuning(int waves) {
-  set_prefill_tuning(waves);
+int qqq_set_prefill_tuning(int tune) {
+  set_prefill_tuning(tune);
   return 0;
 }
 

@@ -4,10 +4,6 @@
 // Shape parameters: NW waves split N; each wave owns MT x CT MFMA tiles of 32 x 32, i.e. a
 // (32*MT) x (32*CT) patch of Y, so the workgroup tile is (32*MT) x (NW*32*CT).  Instances:
 //   <4,2,8>  128 x 512, 8 waves, 128 accumulator registers, two waves per SIMD
-//   <4,4,4>  128 x 512, 4 waves, 256 accumulator registers (AGPRs), one wave per SIMD: each
-//            activation fragment read from LDS feeds 4 MFMAs instead of 2
-//   <8,2,4>  256 x 256, 4 waves, 256 accumulator registers: each converted weight fragment feeds
-//            8 MFMAs instead of 4 (the per-group conversion is the VALU-heavy part)
 //   <4,1,8>  128 x 256, <4,1,4>  128 x 128, <2,1,4>  64 x 128: narrow tiles for mid-size M, where
 //            a few large tiles would leave most CUs idle
 //
@@ -402,8 +398,6 @@ int launch_splitk_reduce(const GemmParams& p, int mode, hipStream_t st) {
 template <int MODE>
 static int launch_shape(const GemmParams& p, int shape, hipStream_t st) {
   switch (shape) {
-    case 1: return launch_dma<MODE, 4, 4, 4>(p, st);
-    case 2: return launch_dma<MODE, 8, 2, 4>(p, st);
     case 3: return launch_dma<MODE, 4, 1, 8>(p, st);
     case 4: return launch_dma<MODE, 4, 1, 4>(p, st);
     case 5: return launch_dma<MODE, 2, 1, 4>(p, st);
@@ -411,9 +405,9 @@ static int launch_shape(const GemmParams& p, int shape, hipStream_t st) {
   }
 }
 
-// shape: 0 = 128x512 tile with 8 waves, 1 = 128x512 with 4 waves, 2 = 256x256 with 4 waves;
-// narrow tiles for shapes with few rows, where the number of workgroups matters more than the
-// reuse inside one: 3 = 128x256 with 8 waves, 4 = 128x128 with 4 waves, 5 = 64x128 with 4 waves
+// shape: 0 = 128x512 tile with 8 waves; narrow tiles for shapes with few rows, where the number
+// of workgroups matters more than the reuse inside one: 3 = 128x256 with 8 waves, 4 = 128x128
+// with 4 waves, 5 = 64x128 with 4 waves
 int launch_gemm_prefill_dma(const GemmParams& p, int mode, int shape, hipStream_t st) {
   switch (mode) {
     case kPerChannel: return launch_shape<kPerChannel>(p, shape, st);

@@ -66,9 +66,8 @@ int launch_pack(const uint32_t* w_nat, int64_t N, int64_t K, uint32_t* w_packed,
 int launch_gemm_skinny(const GemmParams& p, int mode, hipStream_t st);
 int launch_group_bias_prepass(const int8_t* a_q, const int8_t* s_g, int64_t M, int64_t N, int64_t K,
                               int8_t* r_lo, int8_t* r_hi, int8_t* bc, bool with_row_sums, hipStream_t st);
-int launch_gemm_prefill(const GemmParams& p, int mode, hipStream_t st);
 void set_skinny_tuning(int nt, int s, int w, int u);
-void set_prefill_tuning(int waves);
+void set_prefill_tuning(int tune);
 int get_prefill_tuning();
 int launch_gemm_prefill_dma(const GemmParams& p, int mode, int shape, hipStream_t st);
 int launch_gemm_prefill_ring(const GemmParams& p, int mode, hipStream_t st);
