@@ -336,6 +336,10 @@ int launch_gemm_prefill_ring(const GemmParams& p, int mode, hipStream_t st) {
     // the tile has many rows, so both clamp-free requests use the per-weight fp16 FMA route here
     case kGroupLinear:
     case kGroupFused: return launch_ring<kGroupFused>(p, st);
+    // conversion routes this kernel does not carry
+    case kGroupReal:
+    case kGroupBias:
+    case kGroupCvt: return launch_gemm_prefill_dma(p, mode, 0, st);
   }
   return set_error(QQQ_ERR_SHAPE, "unknown mode %d", mode);
 }

@@ -127,3 +127,15 @@ def test_automatic_k_split_on_a_long_k_narrow_n_layer(variant):
     o_acc, o_y = orc.gemm_samples(a_q, s_a, w, s_g, s_w.view(np.uint16), im, jn)
     assert np.array_equal(acc[im, jn].astype(np.int64), o_acc)
     assert ulp_distance(y[im, jn], o_y).max() <= 1
+
+
+@pytest.mark.parametrize("variant,hi,sg_max", [("pc", 0, 0), ("pg", 16, 16), ("pg", 127, 0), ("real", 0, 0)])
+def test_forced_persistent_kernel(variant, hi, sg_max):
+    """The persistent kernel (one workgroup per CU walking its tiles) on shapes with fewer tiles than
+    CUs, ragged edges, K at its minimum of three k-steps; every element against the oracle.  The
+    real-valued route is not carried by it and must fall back to the per-tile kernel."""
+    for (M, K, N) in ((300, 512, 1040), (130, 384, 528), (257, 1152, 2064)):
+        a_q, s_a, w, s_w = inputs(M, K, N, M + K + N + 3)
+        s_g, o_acc, o_y = reference(variant, a_q, s_a, w, s_w, K, N, 17, hi or 16)
+        qqq.set_prefill_tuning(13)
+        check(*run(variant, a_q, s_a, w, s_w, K, s_g=s_g, sg_max=sg_max), o_acc, o_y)
