@@ -93,16 +93,19 @@ int qqq_pack_w4(const uint32_t* w_nat, int64_t N, int64_t K, void* w_packed, voi
 int qqq_unpack_w4(const void* w_packed, int64_t N, int64_t K, uint32_t* w_nat, void* stream);
 
 /*
- * Scratch of the GEMM calls.  Its first part (arrival counters and split-K partial sums of the
- * decode kernel; the whole workspace for M <= 64) must be zero on entry: the caller zero-fills the
- * workspace ONCE after allocation and every call leaves that part zero again.  For M > 64 it is
- * followed by scratch of the per-group variant's pre-pass (per-group row sums of the activations
- * and a transposed copy of the group scales) and, for M <= 512, by slabs for K-split partial tiles
- * (4 * 1024 * N bytes), which a call overwrites and no call relies on.  The
- * decode kernel (M <= 64) requires the workspace; for M > 64 it is optional (without it, or with a
- * smaller one, the per-group variant uses its costlier per-weight conversion).  One workspace must
- * not be shared by GEMM calls that may run concurrently (different streams).
+ * Scratch of the GEMM calls.  Its first part, qqq_gemm_workspace_zero_bytes() long (arrival
+ * counters and split-K partial sums of the decode kernel), must be zero on entry: the caller
+ * zero-fills the workspace ONCE after allocation and every call leaves that part zero again.  For
+ * M > 16 (where the prefill kernels can be the automatic choice: the decode kernel handles M <= 64,
+ * is always chosen up to 16 rows and by a cost model from 17 to 64) it is followed by plain scratch, which a call overwrites and no call
+ * relies on: the per-group variant's pre-pass buffers (per-group row sums of the activations, a
+ * transposed copy of the group scales) and, for M <= 512, slabs for K-split partial tiles
+ * (4 * 1024 * N bytes).  The decode kernel requires the workspace; the prefill kernels take it as
+ * optional (without it, or with a smaller one, the per-group variant uses its costlier per-weight
+ * conversion and K is never split).  One workspace must not be shared by GEMM calls that may run
+ * concurrently (different streams).
  */
+size_t qqq_gemm_workspace_zero_bytes(int64_t M, int64_t N, int64_t K);
 size_t qqq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 
 /*
@@ -180,7 +183,9 @@ int qqq_set_fused_quant(int enable);
 
 /*
  * Tuning/diagnostic knob (host state, not thread-safe): force a kernel family.
- *   0 = automatic, 1 = skinny split-K kernel, 2 = LDS-tiled prefill kernel.
+ *   0 = automatic (decode kernel up to 16 rows, prefill kernels above 64, a cost model in between),
+ *   1 = decode split-K kernel
+ *   (M <= 64), 2 = LDS-tiled prefill kernels.
  * Returns the previous value.  Forcing a family outside its M range gives QQQ_ERR_SHAPE.
  */
 int qqq_set_kernel_override(int family);
@@ -191,7 +196,7 @@ int qqq_set_kernel_override(int family);
  * partial sum (valid for s_g <= 16), 2 = per-weight saturating conversion (any s_g),
  * 3 = per-weight fp16 FMA conversion without saturation (valid for s_g <= 16).  Values 1-3 act on
  * qqq_gemm_w4a8_pergroup / qqq_linear_w4a8_pergroup (3 also keeps the prefill kernels off their
- * default integer route).  4 acts on qqq_gemm_w4a8_pergroup_f16scale for M > 64 only and exists
+ * default integer route).  4 acts on qqq_gemm_w4a8_pergroup_f16scale on the prefill path only and exists
  * to be timed (the ablation of Sec. 4.5.2, Fig. 9): fp16 multiply, conventional round and
  * fp16->int16 conversion instructions, byte packing; two roundings, so it equals the default route
  * only where code*s is exact in fp16.  Returns the previous value.
@@ -217,7 +222,7 @@ int qqq_set_prefill_tuning(int tune);
 
 /*
  * Tuning/diagnostic knob (host state, not thread-safe): number of K splits of the per-tile prefill
- * kernel for 64 < M <= 512 (each tile's K range is divided over that many workgroups, their raw
+ * kernel for 16 < M <= 512 (each tile's K range is divided over that many workgroups, their raw
  * int32 tiles meet in the workspace and a second kernel sums and dequantises them); 0 = automatic,
  * 1 = never split.  Capped at 1024 / M and at K / 128; ignored without a workspace of the queried
  * size.  Negative values only query.  Returns the previous value.

@@ -22,6 +22,7 @@ SYMBOLS = [
     "qqq_linear_w4a8_pergroup", "qqq_set_fused_quant", "qqq_set_kernel_override",
     "qqq_set_group_mode_override", "qqq_set_skinny_tuning", "qqq_set_prefill_tuning",
     "qqq_quantize_w4_perchannel", "qqq_quantize_w4_pergroup", "qqq_set_prefill_ksplit",
+    "qqq_gemm_workspace_zero_bytes",
 ]
 
 _lib = None
@@ -52,6 +53,8 @@ def lib():
         L.qqq_unpack_w4.argtypes = [vp, i64, i64, vp, vp]
         L.qqq_gemm_workspace_bytes.argtypes = [i64, i64, i64]
         L.qqq_gemm_workspace_bytes.restype = sz
+        L.qqq_gemm_workspace_zero_bytes.argtypes = [i64, i64, i64]
+        L.qqq_gemm_workspace_zero_bytes.restype = sz
         L.qqq_gemm_w4a8_perchannel.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, sz, vp]
         L.qqq_gemm_w4a8_pergroup.argtypes = [vp, vp, vp, vp, vp, ci, ci, vp, vp, i64, i64, i64,
                                              vp, sz, vp]
@@ -183,8 +186,8 @@ def qqq_gemm_workspace_bytes(M: int, N: int, K: int) -> int:
 
 def split_k_part(workspace: torch.Tensor, M: int, N: int, K: int) -> torch.Tensor:
     """The part of a GEMM workspace that every call leaves zero (arrival counters and split-K partial
-    sums); what follows it for M > 64 is scratch of the per-group pre-pass and holds no invariant."""
-    return workspace[:qqq_gemm_workspace_bytes(min(M, 64), N, K)]
+    sums of the decode kernel); what follows it is scratch of the prefill kernels with no invariant."""
+    return workspace[:int(lib().qqq_gemm_workspace_zero_bytes(M, N, K))]
 
 
 def new_workspace(M: int, N: int, K: int, device="cuda") -> torch.Tensor:

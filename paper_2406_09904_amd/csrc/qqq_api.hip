@@ -46,28 +46,98 @@ static bool gemm_shape_ok(int64_t M, int64_t N, int64_t K) {
          K % 128 == 0 && K <= 131072;
 }
 
+static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// split-K slabs of the per-tile prefill kernel: up to kSplitRows rows of int32 partial sums in all
+// (k_splits * M <= kSplitRows), for the row counts where a K split can pay
+constexpr int64_t kSplitRows = 1024, kSplitMaxM = 512;
+static size_t split_bytes(int64_t M, int64_t N) {
+  return (M > kDecodeAlwaysMaxM && M <= kSplitMaxM) ? align256((size_t)kSplitRows * (size_t)N * 4) : 0;
+}
+
+// Tile shape and K split of the per-tile prefill kernel from a cost model measured on MI355X
+// (microseconds per k-step of one workgroup, alone on its CU / with the chip saturated): few rows
+// want many small tiles, many rows the large tile with the most reuse; when even the small tiles
+// leave CUs idle and K is long, splitting K over several workgroups per tile pays for the second
+// kernel that sums the raw tiles (a launch plus writing and reading k_splits * M * N int32 at
+// ~3 TB/s).  Shape 0 with one split means "the large tile": the caller then picks between the
+// persistent kernel and the per-tile one.
+struct PrefillPlan {
+  int shape, k_splits;
+  double us;  // modelled time of the per-channel GEMM
+};
+static PrefillPlan plan_prefill(int64_t M, int64_t N, int64_t K, bool can_split, int forced_split) {
+  const int cus = num_cus();
+  const int T = (int)(K / 128);
+  struct Cand { int shape, bm, bn; bool one_per_cu; double alone, saturated; };
+  const Cand cands[4] = {{0, 128, 512, true, 1.34, 1.50}, {3, 128, 256, true, 0.88, 0.90},
+                         {4, 128, 128, false, 0.63, 0.52}, {5, 64, 128, false, 0.45, 0.275}};
+  const int splits[8] = {1, 2, 3, 4, 6, 8, 12, 16};
+  PrefillPlan best = {0, 1, 0.0};
+  for (int i = 0; i < 4; ++i) {
+    const Cand& c = cands[i];
+    const int64_t tiles_c = ((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
+    for (int j = 0; j < 8; ++j) {
+      const int ks = forced_split > 0 ? forced_split : splits[j];
+      if (ks > 1 && (!can_split || ks * M > kSplitRows || T / ks < 4)) continue;
+      const int64_t wgs = tiles_c * ks;
+      double per_step = c.alone;
+      if (wgs > cus)  // whole rounds where only one workgroup fits a CU, a smooth load otherwise
+        per_step = c.saturated * (c.one_per_cu ? (double)((wgs + cus - 1) / cus) : (double)wgs / cus);
+      // each workgroup pays about four k-steps' worth of ring fill and epilogue; the weights
+      // cannot arrive faster than ~5 TB/s however many workgroups pull
+      double cost = per_step * ((double)T / ks + 4.0);
+      const double stream_us = (double)N * (double)K * 0.5 / 5e6;
+      if (cost < stream_us) cost = stream_us;
+      if (ks > 1) cost += 2.4 + 8e-6 * (double)ks * (double)M * (double)N / 3.0;
+      // leaving the large tile has to pay, and so has a split (its model is the coarser one)
+      const bool first = (i == 0 && j == 0);
+      const double margin =
+          ks > 1 && best.k_splits == 1 ? 0.88 : (best.shape == 0 && best.k_splits == 1 ? 0.95 : 1.0);
+      if (first || cost < best.us * margin) best = {c.shape, ks, cost};
+      if (forced_split > 0) break;
+    }
+  }
+  return best;
+}
+
+// Kernel family of a call: 1 = decode (split-K) kernel, 2 = prefill kernels.  Up to 16 rows the
+// decode kernel streams the weights at memory speed; beyond 64 it does not apply.  In between it
+// re-reads the activations once per 32 channels and its time grows with M (fitted on MI355X:
+// 5 us + c(M) * N*K / 1e6, c = 0.04 + 0.0031 M for two row tiles, 0.12 + 0.0023 M for four, a quarter
+// more when there are fewer 32-channel groups than CUs), while
+// the prefill path's 64-row tiles do not care about M: the models decide.  The per-group prefill
+// conversion costs ~1.3x per k-step and its pre-pass another launch.
+static int kernel_family(int64_t M, int64_t N, int64_t K, bool pergroup) {
+  if (g_override != 0) return g_override;
+  if (M <= kDecodeAlwaysMaxM) return 1;
+  if (M > kSkinnyMaxM) return 2;
+  const double nk = (double)N * (double)K * 1e-6;
+  double c = M <= 32 ? 0.04 + 0.0031 * (double)M : 0.12 + 0.0023 * (double)M;
+  if (N / 32 < num_cus()) c *= 1.25;  // fewer channel groups than CUs
+  const double decode_us = 5.0 + c * nk;
+  const PrefillPlan plan = plan_prefill(M, N, K, true, g_prefill_ksplit);
+  const double reduce_us = plan.k_splits > 1 ? 2.4 + 8e-6 * plan.k_splits * (double)M * (double)N / 3.0 : 0.0;
+  const double prefill_us =
+      pergroup ? (plan.us - reduce_us) * 1.3 + reduce_us + 7.5 : plan.us + 2.5;
+  return prefill_us < 0.92 * decode_us ? 2 : 1;
+}
+
 // per-group conversion route from the caller's bound on the group scales
-static int group_mode(int sg_max, int64_t M) {
+static int group_mode(int sg_max, int64_t M, int64_t N, int64_t K) {
   int mode = kGroupClamp;
-  if (sg_max >= 1 && sg_max <= 16) mode = (M <= kSkinnyMaxM) ? kGroupLinear : kGroupFused;
+  if (sg_max >= 1 && sg_max <= 16) mode = (kernel_family(M, N, K, true) == 1) ? kGroupLinear : kGroupFused;
   if (g_group_mode >= 1 && g_group_mode <= 3) mode = g_group_mode;
   return mode;
 }
 
 static size_t ws_rows(int64_t M) { return (size_t)(M < kSkinnyMaxM ? M : kSkinnyMaxM); }
-static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 // pre-pass buffers of the biased per-group route (prefill only): Rl, Rh [M][Gp], Bc [N][Gp]
 static size_t bias_rows_bytes(int64_t M, int64_t K) {
-  return M > kSkinnyMaxM ? align256((size_t)M * (size_t)(((K / 128) + 31) & ~31)) : 0;
+  return M > kDecodeAlwaysMaxM ? align256((size_t)M * (size_t)(((K / 128) + 31) & ~31)) : 0;
 }
 static size_t bias_cols_bytes(int64_t M, int64_t N, int64_t K) {
-  return M > kSkinnyMaxM ? align256((size_t)N * (size_t)(((K / 128) + 31) & ~31)) : 0;
-}
-// split-K slabs of the per-tile prefill kernel: up to kSplitRows rows of int32 partial sums in all
-// (k_splits * M <= kSplitRows), for the row counts where a K split can pay
-constexpr int64_t kSplitRows = 1024, kSplitMaxM = 512;
-static size_t split_bytes(int64_t M, int64_t N) {
-  return (M > kSkinnyMaxM && M <= kSplitMaxM) ? align256((size_t)kSplitRows * (size_t)N * 4) : 0;
+  return M > kDecodeAlwaysMaxM ? align256((size_t)N * (size_t)(((K / 128) + 31) & ~31)) : 0;
 }
 static size_t ws_counter_bytes(int64_t N);
 static size_t ws_rows(int64_t M);
@@ -84,7 +154,7 @@ static void bias_buffers(void* workspace, int64_t M, int64_t N, int64_t K, int8_
 }
 
 // does gemm_common take the biased per-group route for this call? (same conditions as in there)
-static bool takes_bias_route(int mode, int64_t M, int tune);
+static bool takes_bias_route(int mode, int64_t M, int64_t N, int64_t K, int tune);
 
 static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed, const int8_t* s_g,
                        const void* s_w, void* y, int32_t* acc_out, int64_t M, int64_t N, int64_t K,
@@ -102,8 +172,7 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
       (reinterpret_cast<uintptr_t>(s_g) & 3u))
     return set_error(QQQ_ERR_SHAPE, "gemm: a_q, w_packed, y and workspace must be 16-byte aligned, "
                      "s_a, s_w and s_g 4-byte aligned");
-  int family = g_override;
-  if (family == 0) family = (M <= kSkinnyMaxM) ? 1 : 2;
+  const int family = kernel_family(M, N, K, mode != kPerChannel);
   if (family == 1 && M > kSkinnyMaxM)
     return set_error(QQQ_ERR_SHAPE, "gemm: skinny kernel forced but M=%lld > %d", (long long)M,
                      kSkinnyMaxM);
@@ -142,7 +211,7 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
   if (mode == kGroupCvt) return launch_gemm_prefill_dma(p, mode, 0, (hipStream_t)stream);
   // Clamp-free per-group request with a workspace of the queried size: the biased integer
   // conversion (a pre-pass computes the per-group row sums it needs) instead of the fp16 FMA one
-  if (takes_bias_route(mode, M, tune) && workspace && workspace_bytes >= qqq_gemm_workspace_bytes(M, N, K)) {
+  if (takes_bias_route(mode, M, N, K, tune) && workspace && workspace_bytes >= qqq_gemm_workspace_bytes(M, N, K)) {
     int8_t *r_lo, *r_hi, *bc;
     bias_buffers(workspace, M, N, K, r_lo, r_hi, bc);
     const int rc = launch_group_bias_prepass(a_q, s_g, M, N, K, r_lo, r_hi, bc, !row_sums_ready,
@@ -173,41 +242,8 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
     return per_tile(tune >= 15 ? tune - 12 : 0, forced_split > 0 ? forced_split : 1);
   if (tune == 13) return launch_gemm_prefill_ring(p, mode, (hipStream_t)stream);
   {
-    // Tile shape and K split from a cost model measured on MI355X (microseconds per k-step of one
-    // workgroup, alone on its CU / with the chip saturated): few rows want many small tiles, many
-    // rows the large tile with the most reuse; when even the small tiles leave CUs idle and K is
-    // long, splitting K over several workgroups per tile pays for the second kernel that sums
-    // the raw tiles (a launch plus writing and reading k_splits * M * N int32 at ~3 TB/s).
-    const int cus = num_cus();
-    struct Cand { int shape, bm, bn; bool one_per_cu; double alone, saturated; };
-    const Cand cands[4] = {{0, 128, 512, true, 1.34, 1.50}, {3, 128, 256, true, 0.88, 0.90},
-                           {4, 128, 128, false, 0.63, 0.52}, {5, 64, 128, false, 0.45, 0.275}};
-    const int splits[6] = {1, 2, 3, 4, 6, 8};
-    int best = 0, best_split = 1;
-    double best_cost = 0.0;
-    for (int i = 0; i < 4; ++i) {
-      const Cand& c = cands[i];
-      const int64_t tiles_c = ((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
-      for (int j = 0; j < 6; ++j) {
-        const int ks = forced_split > 0 ? forced_split : splits[j];
-        if (ks > 1 && (!can_split || ks * M > kSplitRows || p.T / ks < 4)) continue;
-        const int64_t wgs = tiles_c * ks;
-        double per_step = c.alone;
-        if (wgs > cus)  // whole rounds where only one workgroup fits a CU, a smooth load otherwise
-          per_step = c.saturated * (c.one_per_cu ? (double)((wgs + cus - 1) / cus) : (double)wgs / cus);
-        double cost = per_step * (double)p.T / ks;
-        if (ks > 1) cost += 2.4 + 8e-6 * (double)ks * (double)M * (double)N / 3.0;
-        // leaving the large tile has to pay, and so has a split (its model is the coarser one)
-        const double margin = ks > 1 && best_split == 1 ? 0.88 : (best == 0 && best_split == 1 ? 0.95 : 1.0);
-        if ((i == 0 && j == 0) || cost < best_cost * margin) {
-          best = c.shape;
-          best_split = ks;
-          best_cost = cost;
-        }
-        if (forced_split > 0) break;
-      }
-    }
-    if (best != 0 || best_split > 1) return per_tile(best, best_split);
+    const PrefillPlan plan = plan_prefill(M, N, K, can_split, forced_split);
+    if (plan.shape != 0 || plan.k_splits > 1) return per_tile(plan.shape, plan.k_splits);
     if (mode == kGroupReal || mode == kGroupBias)
       return launch_gemm_prefill_dma(p, mode, 0, (hipStream_t)stream);
     // Measured on MI355X: the persistent kernel wins for the per-channel variant at every K and
@@ -220,8 +256,10 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
   }
 }
 
-static bool takes_bias_route(int mode, int64_t M, int tune) {
-  return mode == kGroupFused && M > kSkinnyMaxM && g_group_mode == 0 && g_override != 1 &&
+static bool takes_bias_route(int mode, int64_t M, int64_t N, int64_t K, int tune) {
+  // (the workspace holds the pre-pass buffers only above the rows that always take the decode kernel)
+  return mode == kGroupFused && M > kDecodeAlwaysMaxM && g_group_mode == 0 &&
+         kernel_family(M, N, K, true) == 2 &&
          tune != 13;  // every route but the forced persistent kernel carries the biased mode
 }
 
@@ -254,7 +292,7 @@ static int linear_common(const void* a_fp16, int64_t lda, const void* w_packed, 
   // the per-group prefill GEMM's biased route wants per-group row sums of the codes: the quantiser
   // has them in registers, so it writes them on the way
   int8_t *r_lo = nullptr, *r_hi = nullptr, *bc = nullptr;
-  const bool sums = takes_bias_route(mode, M, get_prefill_tuning());
+  const bool sums = takes_bias_route(mode, M, N, K, get_prefill_tuning());
   if (sums) bias_buffers(workspace, M, N, K, r_lo, r_hi, bc);
   const int rc = launch_quant_act(a_fp16, M, K, lda, a_q, s_a, (hipStream_t)stream, r_lo, r_hi);
   if (rc != QQQ_OK) return rc;
@@ -368,6 +406,11 @@ int qqq_unpack_w4(const void* w_packed, int64_t N, int64_t K, uint32_t* w_nat, v
   return pack_common(w_packed, N, K, w_nat, true, stream);
 }
 
+size_t qqq_gemm_workspace_zero_bytes(int64_t M, int64_t N, int64_t K) {
+  if (!gemm_shape_ok(M, N, K)) return 0;
+  return ws_counter_bytes(N) + align256(ws_rows(M) * (size_t)N * 4);
+}
+
 size_t qqq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
   if (!gemm_shape_ok(M, N, K)) return 0;
   return ws_counter_bytes(N) + align256(ws_rows(M) * (size_t)N * 4) + 2 * bias_rows_bytes(M, K) +
@@ -390,7 +433,7 @@ int qqq_gemm_w4a8_pergroup(const int8_t* a_q, const float* s_a, const void* w_pa
   if (sg_max < 0 || sg_max > 127)
     return set_error(QQQ_ERR_SHAPE, "pergroup: sg_max must be in 0..127, got %d", sg_max);
   return gemm_common(a_q, s_a, w_packed, s_g, s_w_fp16, y_fp16, acc_out, M, N, K, workspace,
-                     workspace_bytes, stream, group_mode(sg_max, M));
+                     workspace_bytes, stream, group_mode(sg_max, M, N, K));
 }
 
 int qqq_gemm_w4a8_pergroup_f16scale(const int8_t* a_q, const float* s_a, const void* w_packed,
@@ -399,7 +442,7 @@ int qqq_gemm_w4a8_pergroup_f16scale(const int8_t* a_q, const float* s_a, const v
                                     void* workspace, size_t workspace_bytes, void* stream) {
   if (group != QQQ_GROUP) return set_error(QQQ_ERR_SHAPE, "pergroup: group must be 128, got %d", group);
   // knob 4: the conventional-conversion ablation of Fig. 9 (prefill kernel only)
-  const int mode = (g_group_mode == 4 && M > kSkinnyMaxM) ? kGroupCvt : kGroupReal;
+  const int mode = (g_group_mode == 4 && kernel_family(M, N, K, true) == 2) ? kGroupCvt : kGroupReal;
   return gemm_common(a_q, s_a, w_packed, (const int8_t*)s_g_fp16, s_w_fp16, y_fp16, acc_out, M, N, K,
                      workspace, workspace_bytes, stream, mode);
 }
@@ -431,7 +474,7 @@ int qqq_linear_w4a8_pergroup(const void* a_fp16, int64_t lda, const void* w_pack
   if (sg_max < 0 || sg_max > 127)
     return set_error(QQQ_ERR_SHAPE, "pergroup: sg_max must be in 0..127, got %d", sg_max);
   return linear_common(a_fp16, lda, w_packed, s_g, s_w_fp16, y_fp16, acc_out, M, N, K, workspace,
-                       workspace_bytes, stream, group_mode(sg_max, M));
+                       workspace_bytes, stream, group_mode(sg_max, M, N, K));
 }
 
 }  // extern "C"

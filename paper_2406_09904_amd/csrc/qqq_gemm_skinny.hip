@@ -473,11 +473,12 @@ static int launch_mode(const GemmParams& p, hipStream_t st) {
     if (nt == 2) return deep ? launch_w<MODE, 2, 1, 4>(p, w, S, st) : launch_w<MODE, 2, 1, 2>(p, w, S, st);
     return deep ? launch_w<MODE, 1, 1, 8>(p, w, S, st) : launch_w<MODE, 1, 1, 4>(p, w, S, st);
   }
+  const bool deep2 = g_tune_u > 1;
   if (mt == 2) {
-    if (nt >= 2) return launch_w<MODE, 2, 2, 1>(p, w, S, st);
+    if (nt >= 2) return deep2 ? launch_w<MODE, 2, 2, 2>(p, w, S, st) : launch_w<MODE, 2, 2, 1>(p, w, S, st);
     return launch_w<MODE, 1, 2, 2>(p, w, S, st);
   }
-  if (nt >= 2) return launch_w<MODE, 2, 4, 1>(p, w, S, st);
+  if (nt >= 2) return deep2 ? launch_w<MODE, 2, 4, 2>(p, w, S, st) : launch_w<MODE, 2, 4, 1>(p, w, S, st);
   return launch_w<MODE, 1, 4, 1>(p, w, S, st);
 }
 

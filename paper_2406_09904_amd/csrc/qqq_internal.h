@@ -78,6 +78,10 @@ int get_prefill_ksplit();
 constexpr int kFusedMaxM = 4;          // rows the decode kernel quantises itself (fused path)
 constexpr int kFusedLdsBytes = 8192;   // most activations the fused path quantises: M*K int8 in LDS
 constexpr int kSkinnyMaxM = 64;  // rows the split-K kernel handles (4 MFMA row tiles)
+// rows up to which the decode kernel is always the automatic choice; from there to kSkinnyMaxM a
+// cost model decides between it and the prefill path's 64-row tiles (which read every activation
+// row once per 128 channels instead of once per 32), and the workspace carries the prefill scratch
+constexpr int kDecodeAlwaysMaxM = 16;
 
 // ---------------------------------------------------------------------------------------------
 // Packed layout.  Chunk (nt, t) = output channels [16nt,16nt+16) x k in [128t,128t+128), 1 KiB at
