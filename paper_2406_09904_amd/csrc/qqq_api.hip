@@ -104,8 +104,7 @@ static PrefillPlan plan_prefill(int64_t M, int64_t N, int64_t K, bool can_split,
 // Kernel family of a call: 1 = decode (split-K) kernel, 2 = prefill kernels.  Up to 16 rows the
 // decode kernel streams the weights at memory speed; beyond 64 it does not apply.  In between it
 // re-reads the activations once per 32 channels and its time grows with M (fitted on MI355X:
-// 5 us + c(M) * N*K / 1e6, c = 0.04 + 0.0031 M for two row tiles, 0.12 + 0.0023 M for four, a quarter
-// more when there are fewer 32-channel groups than CUs), while
+// 5 us + c(M) * N*K / 1e6, with c from the number of row tiles and the channel-group width), while
 // the prefill path's 64-row tiles do not care about M: the models decide.  The per-group prefill
 // conversion costs ~1.3x per k-step and its pre-pass another launch.
 static int kernel_family(int64_t M, int64_t N, int64_t K, bool pergroup) {
@@ -113,8 +112,13 @@ static int kernel_family(int64_t M, int64_t N, int64_t K, bool pergroup) {
   if (M <= kDecodeAlwaysMaxM) return 1;
   if (M > kSkinnyMaxM) return 2;
   const double nk = (double)N * (double)K * 1e-6;
-  double c = M <= 32 ? 0.04 + 0.0031 * (double)M : 0.12 + 0.0023 * (double)M;
-  if (N / 32 < num_cus()) c *= 1.25;  // fewer channel groups than CUs
+  double c;
+  if (N % 64 == 0 && (N / 64) * 3 >= 2 * num_cus()) {  // 64-channel groups (the launcher's own rule)
+    c = M <= 32 ? 0.038 + 0.0015 * (double)M : 0.045 + 0.0017 * (double)M;
+  } else {                                               // 32-channel groups
+    c = M <= 32 ? 0.04 + 0.0031 * (double)M : 0.12 + 0.0023 * (double)M;
+    if (N / 32 < num_cus()) c *= 1.25;                   // fewer channel groups than CUs
+  }
   const double decode_us = 5.0 + c * nk;
   const PrefillPlan plan = plan_prefill(M, N, K, true, g_prefill_ksplit);
   const double reduce_us = plan.k_splits > 1 ? 2.4 + 8e-6 * plan.k_splits * (double)M * (double)N / 3.0 : 0.0;

@@ -432,7 +432,9 @@ static int launch_w(const GemmParams& p, int W, int S, hipStream_t st) {
 static void choose_split(const GemmParams& p, int mt, int& nt, int& w, int& s) {
   nt = 1;
   if (mt == 1) nt = (p.N % 64 == 0) ? 4 : (p.N % 32 == 0) ? 2 : 1;
-  if (mt >= 2) nt = (p.N % 32 == 0) ? 2 : 1;  // wider groups also halve the re-reads of the activations
+  // several row tiles: every workgroup re-reads all activations from L2, so the widest channel
+  // group that keeps the CUs busy (rule below) also cuts those re-reads the most
+  if (mt >= 2) nt = (p.N % 64 == 0) ? 4 : (p.N % 32 == 0) ? 2 : 1;
   const int cus = num_cus();
   // Measured on MI355X: the widest channel group that still leaves about two workgroups for
   // every three CUs streams best, with 8 waves per workgroup and no K split (no atomics).
@@ -453,7 +455,7 @@ static int launch_mode(const GemmParams& p, hipStream_t st) {
   const int mt = (p.M + 15) / 16;
   int nt, w, S;
   choose_split(p, mt, nt, w, S);
-  if (g_tune_nt > 0 && (mt * g_tune_nt <= 4 || g_tune_nt <= 2) && p.N % (16 * g_tune_nt) == 0) nt = g_tune_nt;
+  if (g_tune_nt > 0 && p.N % (16 * g_tune_nt) == 0) nt = g_tune_nt;
   if (g_tune_s > 0 && g_tune_s <= p.T) S = g_tune_s;
   if (g_tune_w > 0) w = g_tune_w;
   if (p.a_fp16 != nullptr) {
@@ -473,12 +475,13 @@ static int launch_mode(const GemmParams& p, hipStream_t st) {
     if (nt == 2) return deep ? launch_w<MODE, 2, 1, 4>(p, w, S, st) : launch_w<MODE, 2, 1, 2>(p, w, S, st);
     return deep ? launch_w<MODE, 1, 1, 8>(p, w, S, st) : launch_w<MODE, 1, 1, 4>(p, w, S, st);
   }
-  const bool deep2 = g_tune_u > 1;
   if (mt == 2) {
-    if (nt >= 2) return deep2 ? launch_w<MODE, 2, 2, 2>(p, w, S, st) : launch_w<MODE, 2, 2, 1>(p, w, S, st);
+    if (nt >= 4) return launch_w<MODE, 4, 2, 1>(p, w, S, st);
+    if (nt >= 2) return launch_w<MODE, 2, 2, 1>(p, w, S, st);
     return launch_w<MODE, 1, 2, 2>(p, w, S, st);
   }
-  if (nt >= 2) return deep2 ? launch_w<MODE, 2, 4, 2>(p, w, S, st) : launch_w<MODE, 2, 4, 1>(p, w, S, st);
+  if (nt >= 4) return launch_w<MODE, 4, 4, 1>(p, 4, S, st);  // 16 tiles of accumulators: 4 waves fit LDS and registers
+  if (nt >= 2) return launch_w<MODE, 2, 4, 1>(p, w, S, st);
   return launch_w<MODE, 1, 4, 1>(p, w, S, st);
 }
 
