@@ -21,37 +21,46 @@ template <int NT, int MT, int U>
 struct Batch {
   uint4 w[U][NT];
   v4i a[U][MT][2];
-  int sgv[U];  // word (lane mod 4*NT) of the k-step's 16*NT group-scale bytes
+  int sgv[U];  // the word of the k-step's group scales that holds this lane's scale of tile (lane/16) mod NT
 };
 
-// The 16*NT group scales of one k-step of a wave's channel group are 4*NT contiguous words: lane
-// l requests word l mod 4*NT (one vector-memory instruction for the wave instead of one per
-// tile); when the batch is consumed the words are broadcast from lanes 0..4*NT-1 through scalar
-// registers and each lane picks its byte.
+// The 16*NT group scales of one k-step of a wave's channel group are 4*NT contiguous words.  Lane
+// (row kc = lane/16, channel nl = lane%16) requests the word that holds the scale of channel nl in
+// tile kc mod NT: one vector-memory instruction for the wave, and every lane already holds one of
+// the NT scales of its own channel.  When the batch is consumed each lane extracts its byte and the
+// 16-lane rows are exchanged with the row-swap instructions (v_permlane32_swap swaps the upper
+// half of one operand with the lower half of the other, v_permlane16_swap the odd rows of one with
+// the even rows of the other), after which every lane holds all NT scales of its channel: three
+// instructions for four tiles, no scalar broadcasts, no LDS crossbar.
 // (The real-valued variant's scales are fp16: 8*NT words, two scales each.)
 template <int NT, int MODE>
 __device__ __forceinline__ int load_group_scales(const int8_t* gp, uint32_t lane) {
-  constexpr uint32_t kWords = (MODE == kGroupReal ? 8u : 4u) * NT;
-  return reinterpret_cast<const int*>(gp)[lane & (kWords - 1u)];
+  const uint32_t tile = (lane >> 4) & (uint32_t)(NT - 1), nl = lane & 15u;
+  const uint32_t word = MODE == kGroupReal ? 8u * tile + (nl >> 1) : 4u * tile + (nl >> 2);
+  return reinterpret_cast<const int*>(gp)[word];
 }
 
-// fp16 bit pattern of the lane's scale for tile i: half n%2 of word 8*i + n%16/2, fetched from
-// the lane that holds that word
-__device__ __forceinline__ uint32_t pick_group_scale_f16(int sgv, int i, int nl) {
-  const int d = __builtin_amdgcn_ds_bpermute(4 * (8 * i + (nl >> 1)), sgv);
-  return ((uint32_t)d >> ((nl & 1) * 16)) & 0xFFFFu;
-}
-
-// lane's scale for tile i: byte 16*i + n%16 of the wave's scale words
-template <int NT>
-__device__ __forceinline__ int pick_group_scale(int sgv, int i, int nl) {
-  const int sgs[4] = {__builtin_amdgcn_readlane(sgv, 4 * i), __builtin_amdgcn_readlane(sgv, 4 * i + 1),
-                      __builtin_amdgcn_readlane(sgv, 4 * i + 2), __builtin_amdgcn_readlane(sgv, 4 * i + 3)};
-  // word nl/4 through lane masks (and/or on scalar operands), then byte nl%4
-  const int q = nl >> 2;
-  const int m0 = -(int)(q == 0), m1 = -(int)(q == 1), m2 = -(int)(q == 2), m3 = -(int)(q == 3);
-  const int d = (sgs[0] & m0) | (sgs[1] & m1) | (sgs[2] & m2) | (sgs[3] & m3);
-  return (d >> ((nl & 3) * 8)) & 0xFF;
+// sg[i] = scale of the lane's channel in tile i (int8 scale, or fp16 bit pattern)
+template <int NT, int MODE>
+__device__ __forceinline__ void spread_group_scales(int sgv, int nl, int (&sg)[NT]) {
+  const uint32_t own = MODE == kGroupReal ? ((uint32_t)sgv >> ((nl & 1) * 16)) & 0xFFFFu
+                                          : ((uint32_t)sgv >> ((nl & 3) * 8)) & 0xFFu;
+  if constexpr (NT == 1) {
+    sg[0] = (int)own;
+  } else if constexpr (NT == 2) {  // rows hold tiles 0,1,0,1
+    const auto t = __builtin_amdgcn_permlane16_swap(own, own, false, false);
+    sg[0] = (int)t[0];
+    sg[1] = (int)t[1];
+  } else {                         // rows hold tiles 0,1,2,3
+    static_assert(NT == 4, "channel tiles per workgroup");
+    const auto h = __builtin_amdgcn_permlane32_swap(own, own, false, false);  // rows 0,1,0,1 | 2,3,2,3
+    const auto lo = __builtin_amdgcn_permlane16_swap(h[0], h[0], false, false);
+    const auto hi = __builtin_amdgcn_permlane16_swap(h[1], h[1], false, false);
+    sg[0] = (int)lo[0];
+    sg[1] = (int)lo[1];
+    sg[2] = (int)hi[0];
+    sg[3] = (int)hi[1];
+  }
 }
 
 // Issues the loads of one batch.  Every call issues the same instructions whatever the position:
@@ -119,15 +128,13 @@ __device__ __forceinline__ void consume_batch(const Batch<NT, MT, U>& b, v4i (&a
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     if (tb + tstride * u >= t1) break;
+    int sgs[NT] = {};
+    if constexpr (MODE != kPerChannel) spread_group_scales<NT, MODE>(b.sgv[u], nl, sgs);
 #pragma unroll
     for (int i = 0; i < NT; ++i) {
       const uint32_t d[4] = {b.w[u][i].x, b.w[u][i].y, b.w[u][i].z, b.w[u][i].w};
       int o[8];
-      int sg = 0;
-      if constexpr (MODE == kGroupReal)
-        sg = (int)pick_group_scale_f16(b.sgv[u], i, nl);
-      else if constexpr (MODE != kPerChannel)
-        sg = pick_group_scale<NT>(b.sgv[u], i, nl);
+      const int sg = sgs[i];
       if constexpr (MODE == kPerChannel || MODE == kGroupLinear) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) unpack_x16(d[j], o[2 * j], o[2 * j + 1]);
