@@ -24,6 +24,10 @@
  *               [Sec. 3.3, second consideration]
  *   Y           Dequant: acc * s_A[m] * s_W[n] (per-group: s_Wc[n]) -> fp16
  *               [Sec. 3.3.1 last sentences, Sec. 3.3.2 last sentence]
+ *   quantize_w4 offline front-end: symmetric round-to-nearest int4 codes from fp16 weights with
+ *               the per-channel scale s_W [Sec. 3.3.1] or the per-group scales s_Wg, s_Wc and
+ *               the fused s*_Wg = s_Wg / s_Wc [Sec. 3.3.2, Fig. 4-5]; its readings are listed
+ *               above its functions at the end of this file
  *
  * Readings taken where the paper is silent (each is listed in the design notes of
  * the repository): divisor 127, fp32 correctly rounded division, round half to even,
@@ -34,7 +38,10 @@
  *
  * Pins (tests, CPU only): pure-Python brute force on tiny shapes, numpy's float16
  * conversions, closed forms for constant / one-hot / extreme inputs, the x16 identity
- * of Sec. 3.3.1, exhaustive code x scale table for the per-group W8.
+ * of Sec. 3.3.1, exhaustive code x scale table for the per-group W8; for the front-end: weights
+ * on an exact grid, exact rational arithmetic for every code of small matrices, the round-to-
+ * nearest error bound, the step^2/12 noise law, the no-wrap property through the pinned
+ * code x scale conversion, an end-to-end layer against float64.
  *
  * Return codes: 0 ok, 1 null pointer, 2 bad shape, 5 accumulator does not fit int32.
  */
