@@ -476,6 +476,7 @@ def main():
             st = max(5, min(args.steps, 20 if big else 100))
             s_ms, g_ms, q_ms, _ = measure(c2, torch, st, min(args.warmup, 5), use_graph)
             r2 = roofline_for(c2, s_ms, g_ms)
+            r2["traffic"] = load_traffic(name)
             sweep.append({"workload": name, "steps": st, "ms_per_step": round(s_ms, 6),
                           "gemm_us": round(g_ms * 1e3, 3), "quant_act_us": round(q_ms * 1e3, 3),
                           "quant_act_gbs": round(quant_bytes(w2.M, w2.K) / (q_ms * 1e-3) / 1e9, 1),
