@@ -78,8 +78,15 @@ static PrefillPlan plan_prefill(int64_t M, int64_t N, int64_t K, bool can_split,
     const Cand& c = cands[i];
     const int64_t tiles_c = ((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
     for (int j = 0; j < 8; ++j) {
-      const int ks = forced_split > 0 ? forced_split : splits[j];
-      if (ks > 1 && (!can_split || ks * M > kSplitRows || T / ks < 4)) continue;
+      int ks = splits[j];
+      if (forced_split > 0) {  // the knob: capped like the forced-shape route caps it
+        ks = forced_split;
+        if (ks > kSplitRows / M) ks = (int)(kSplitRows / M);
+        if (ks > T) ks = T;
+        if (ks < 1 || !can_split) ks = 1;
+      } else if (ks > 1 && (!can_split || ks * M > kSplitRows || T / ks < 4)) {
+        continue;
+      }
       const int64_t wgs = tiles_c * ks;
       double per_step = c.alone;
       if (wgs > cus)  // whole rounds where only one workgroup fits a CU, a smooth load otherwise
