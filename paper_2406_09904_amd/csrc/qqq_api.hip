@@ -255,23 +255,22 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
   {
     const PrefillPlan plan = plan_prefill(M, N, K, can_split, forced_split);
     if (plan.shape != 0 || plan.k_splits > 1) return per_tile(plan.shape, plan.k_splits);
-    if (mode == kGroupReal || mode == kGroupBias)
-      return launch_gemm_prefill_dma(p, mode, 0, (hipStream_t)stream);
+    if (mode == kGroupReal) return launch_gemm_prefill_dma(p, mode, 0, (hipStream_t)stream);
     // Measured on MI355X: the persistent kernel wins for the per-channel variant at every K and
     // for the per-group variant when tiles are short (its per-k-step cost is a little higher
-    // there, its per-tile cost much lower).
+    // there, its per-tile cost much lower): up to K = 4096 with the biased conversion (7 % at
+    // K = 1024, level at 8192), up to 3072 with the others.
     const bool tiles_repeat = tiles > num_cus();
-    if (mode == kPerChannel || (tiles_repeat && K <= 3072))
+    if (mode == kPerChannel || (tiles_repeat && K <= (mode == kGroupBias ? 4096 : 3072)))
       return launch_gemm_prefill_ring(p, mode, (hipStream_t)stream);
     return launch_gemm_prefill_dma(p, mode, 0, (hipStream_t)stream);
   }
 }
 
-static bool takes_bias_route(int mode, int64_t M, int64_t N, int64_t K, int tune) {
+static bool takes_bias_route(int mode, int64_t M, int64_t N, int64_t K, int /*tune*/) {
   // (the workspace holds the pre-pass buffers only above the rows that always take the decode kernel)
   return mode == kGroupFused && M > kDecodeAlwaysMaxM && g_group_mode == 0 &&
-         kernel_family(M, N, K, true) == 2 &&
-         tune != 13;  // every route but the forced persistent kernel carries the biased mode
+         kernel_family(M, N, K, true) == 2;
 }
 
 static bool fused_ok(int64_t M, int64_t K) {

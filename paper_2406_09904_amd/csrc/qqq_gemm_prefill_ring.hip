@@ -214,6 +214,34 @@ __global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmPar
       for (int c = 0; c < 2; ++c)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[mt][c][v] = 0;
+    // Biased per-group route: the conversion adds (8*s_g - 128) to every weight, which sums to
+    // sum_g Bc[n][g] * R[m][g] over a row; the pre-pass stored -R = 128*Rh + Rl, so the tile starts
+    // at 128 x (Bc x Rh) + Bc x Rl (see gemm_prefill_dma_kernel).  Ordinary loads: the compiler
+    // waits for them before the MFMAs below, so none is outstanding at the k-loop's counted waits.
+    if constexpr (MODE == kGroupBias) {
+      const int Gp = (T + 31) & ~31;
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        int col = n_wave + c * 32 + n32;
+        if (col > N - 1) col = N - 1;
+        const int8_t* bp = p.bias_w + (int64_t)col * Gp + 16 * h;
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+          int mrow = m0 + 32 * mt + n32;
+          if (mrow > M - 1) mrow = M - 1;
+          const int8_t* lp = p.r_lo + (int64_t)mrow * Gp + 16 * h;
+          const int8_t* hp = p.r_hi + (int64_t)mrow * Gp + 16 * h;
+          for (int j = 0; j < Gp; j += 32)
+            acc[mt][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(*(const v4i*)(hp + j), *(const v4i*)(bp + j),
+                                                               acc[mt][c], 0, 0, 0);
+#pragma unroll
+          for (int v = 0; v < 16; ++v) acc[mt][c][v] *= 128;
+          for (int j = 0; j < Gp; j += 32)
+            acc[mt][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(*(const v4i*)(lp + j), *(const v4i*)(bp + j),
+                                                               acc[mt][c], 0, 0, 0);
+        }
+      }
+    }
 
     for (int t = 0; t < T; ++t) {
       // the cursor's k-step (two ahead, possibly already in the next tile) goes into the stage
@@ -336,9 +364,9 @@ int launch_gemm_prefill_ring(const GemmParams& p, int mode, hipStream_t st) {
     // the tile has many rows, so both clamp-free requests use the per-weight fp16 FMA route here
     case kGroupLinear:
     case kGroupFused: return launch_ring<kGroupFused>(p, st);
+    case kGroupBias: return launch_ring<kGroupBias>(p, st);
     // conversion routes this kernel does not carry
     case kGroupReal:
-    case kGroupBias:
     case kGroupCvt: return launch_gemm_prefill_dma(p, mode, 0, st);
   }
   return set_error(QQQ_ERR_SHAPE, "unknown mode %d", mode);

@@ -139,3 +139,12 @@ def test_forced_persistent_kernel(variant, hi, sg_max):
         s_g, o_acc, o_y = reference(variant, a_q, s_a, w, s_w, K, N, 17, hi or 16)
         qqq.set_prefill_tuning(13)
         check(*run(variant, a_q, s_a, w, s_w, K, s_g=s_g, sg_max=sg_max), o_acc, o_y)
+
+
+def test_automatic_choice_of_the_persistent_kernel_with_the_biased_route():
+    """More 128x512 tiles than CUs (9 x 32 = 288) and a short K: per-group with s_g <= 16 and a
+    workspace takes the persistent kernel with the biased conversion; every element against the oracle."""
+    M, K, N = 1100, 512, 16384
+    a_q, s_a, w, s_w = inputs(M, K, N, 21)
+    s_g, o_acc, o_y = reference("pg", a_q, s_a, w, s_w, K, N, 19, 16)
+    check(*run("pg", a_q, s_a, w, s_w, K, s_g=s_g, sg_max=16), o_acc, o_y)
