@@ -150,10 +150,6 @@ static size_t bias_rows_bytes(int64_t M, int64_t K) {
 static size_t bias_cols_bytes(int64_t M, int64_t N, int64_t K) {
   return M > kDecodeAlwaysMaxM ? align256((size_t)N * (size_t)(((K / 128) + 31) & ~31)) : 0;
 }
-static size_t ws_counter_bytes(int64_t N);
-static size_t ws_rows(int64_t M);
-static void bias_buffers(void* workspace, int64_t M, int64_t N, int64_t K, int8_t*& r_lo, int8_t*& r_hi,
-                         int8_t*& bc);
 static size_t ws_counter_bytes(int64_t N) { return ((size_t)(N / 16) * 4 + 255) & ~(size_t)255; }
 
 static void bias_buffers(void* workspace, int64_t M, int64_t N, int64_t K, int8_t*& r_lo, int8_t*& r_hi,
@@ -165,7 +161,7 @@ static void bias_buffers(void* workspace, int64_t M, int64_t N, int64_t K, int8_
 }
 
 // does gemm_common take the biased per-group route for this call? (same conditions as in there)
-static bool takes_bias_route(int mode, int64_t M, int64_t N, int64_t K, int tune);
+static bool takes_bias_route(int mode, int64_t M, int64_t N, int64_t K);
 
 static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed, const int8_t* s_g,
                        const void* s_w, void* y, int32_t* acc_out, int64_t M, int64_t N, int64_t K,
@@ -222,7 +218,7 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
   if (mode == kGroupCvt) return launch_gemm_prefill_dma(p, mode, 0, (hipStream_t)stream);
   // Clamp-free per-group request with a workspace of the queried size: the biased integer
   // conversion (a pre-pass computes the per-group row sums it needs) instead of the fp16 FMA one
-  if (takes_bias_route(mode, M, N, K, tune) && workspace && workspace_bytes >= qqq_gemm_workspace_bytes(M, N, K)) {
+  if (takes_bias_route(mode, M, N, K) && workspace && workspace_bytes >= qqq_gemm_workspace_bytes(M, N, K)) {
     int8_t *r_lo, *r_hi, *bc;
     bias_buffers(workspace, M, N, K, r_lo, r_hi, bc);
     const int rc = launch_group_bias_prepass(a_q, s_g, M, N, K, r_lo, r_hi, bc, !row_sums_ready,
@@ -267,7 +263,7 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
   }
 }
 
-static bool takes_bias_route(int mode, int64_t M, int64_t N, int64_t K, int /*tune*/) {
+static bool takes_bias_route(int mode, int64_t M, int64_t N, int64_t K) {
   // (the workspace holds the pre-pass buffers only above the rows that always take the decode kernel)
   return mode == kGroupFused && M > kDecodeAlwaysMaxM && g_group_mode == 0 &&
          kernel_family(M, N, K, true) == 2;
@@ -302,7 +298,7 @@ static int linear_common(const void* a_fp16, int64_t lda, const void* w_packed, 
   // the per-group prefill GEMM's biased route wants per-group row sums of the codes: the quantiser
   // has them in registers, so it writes them on the way
   int8_t *r_lo = nullptr, *r_hi = nullptr, *bc = nullptr;
-  const bool sums = takes_bias_route(mode, M, N, K, get_prefill_tuning());
+  const bool sums = takes_bias_route(mode, M, N, K);
   if (sums) bias_buffers(workspace, M, N, K, r_lo, r_hi, bc);
   const int rc = launch_quant_act(a_fp16, M, K, lda, a_q, s_a, (hipStream_t)stream, r_lo, r_hi);
   if (rc != QQQ_OK) return rc;
