@@ -3,8 +3,10 @@
  *
  * The path:  fp16 activations --qqq_quant_act--> int8 codes + per-token scale
  *            int4 weight codes --qqq_pack_w4 (offline)--> device tile layout
- *            qqq_gemm_w4a8_{perchannel,pergroup}:  Y[m,n] = fp16( acc[m,n] * s_a[m] * s_w[n] ),
- *            acc[m,n] = sum_k A_q[m,k] * W8[n,k]  (int32, exact)
+ *            qqq_gemm_w4a8_{perchannel,pergroup,pergroup_f16scale}:
+ *                Y[m,n] = fp16( acc[m,n] * s_a[m] * s_w[n] ),  acc[m,n] = sum_k A_q[m,k] * W8[n,k]  (int32, exact)
+ *            qqq_linear_w4a8_{perchannel,pergroup}: the first and the third step in one call
+ *            fp16 weights --qqq_quantize_w4_{perchannel,pergroup} (offline)--> int4 codes + scales
  *
  * Conventions common to every entry point
  *   - Every pointer is a DEVICE pointer owned by the caller, 16-byte aligned, unless a
