@@ -177,6 +177,24 @@ int qqq_linear_w4a8_pergroup(const void* a_fp16, int64_t lda, const void* w_pack
                              size_t workspace_bytes, void* stream);
 
 /*
+ * For callers that cannot allocate or bring a workspace (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): qqq_linear_w4a8_perchannel with the library's own
+ * scratch, a static device array of QQQ_STATIC_SCRATCH_BYTES per GPU that lives in the code
+ * object until the process ends.  The call allocates nothing and takes no workspace; inputs and
+ * outputs are the caller's, as above, and the result is bit-identical to qqq_linear_w4a8_perchannel.
+ * Shapes whose qqq_linear_workspace_bytes(M,N,K) exceeds QQQ_STATIC_SCRATCH_BYTES return
+ * QQQ_ERR_WORKSPACE (nothing enqueued): use the workspace-taking call for those.
+ * Every call on a GPU shares that GPU's array, which keeps the previous call's contents: the call
+ * itself clears (with a small fill kernel on `stream`) the part its kernels need zero, so one more
+ * launch than the workspace-taking call for M <= 64.  Calls that may overlap on one GPU (different
+ * streams, different threads) race on the array: serialise them.
+ */
+#define QQQ_STATIC_SCRATCH_BYTES (16u << 20)
+int qqq_linear_w4a8_perchannel_static(const void* a_fp16, int64_t lda, const void* w_packed,
+                                      const void* s_w_fp16, void* y_fp16, int32_t* acc_out, int64_t M,
+                                      int64_t N, int64_t K, void* stream);
+
+/*
  * Tuning/diagnostic knob (host state, not thread-safe): 0 makes the qqq_linear_* calls always
  * run the two kernels, 1 (default) lets them use the fused decode kernel.  Returns the previous
  * value.

@@ -22,7 +22,7 @@ SYMBOLS = [
     "qqq_linear_w4a8_pergroup", "qqq_set_fused_quant", "qqq_set_kernel_override",
     "qqq_set_group_mode_override", "qqq_set_skinny_tuning", "qqq_set_prefill_tuning",
     "qqq_quantize_w4_perchannel", "qqq_quantize_w4_pergroup", "qqq_set_prefill_ksplit",
-    "qqq_gemm_workspace_zero_bytes",
+    "qqq_gemm_workspace_zero_bytes", "qqq_linear_w4a8_perchannel_static",
 ]
 
 _lib = None
@@ -65,6 +65,7 @@ def lib():
         L.qqq_linear_w4a8_perchannel.argtypes = [vp, i64, vp, vp, vp, vp, i64, i64, i64, vp, sz, vp]
         L.qqq_linear_w4a8_pergroup.argtypes = [vp, i64, vp, vp, vp, ci, ci, vp, vp, i64, i64, i64,
                                                vp, sz, vp]
+        L.qqq_linear_w4a8_perchannel_static.argtypes = [vp, i64, vp, vp, vp, vp, i64, i64, i64, vp]
         L.qqq_quantize_w4_perchannel.argtypes = [vp, i64, i64, i64, vp, vp, vp]
         L.qqq_quantize_w4_pergroup.argtypes = [vp, i64, i64, i64, ci, vp, vp, vp, vp, vp, vp]
         L.qqq_set_fused_quant.argtypes = [ci]
@@ -264,6 +265,17 @@ def qqq_linear_w4a8_perchannel(a_fp16, w_packed, s_w, workspace, y=None, acc_out
         ctypes.c_void_p(a_fp16.data_ptr()), lda, _ptr(w_packed, torch.uint8), _ptr(s_w, torch.float16),
         _ptr(y, torch.float16), _ptr(acc_out, torch.int32), M, N, K, _ptr(workspace, torch.uint8),
         workspace.numel(), _stream()))
+    return y
+
+
+def qqq_linear_w4a8_perchannel_static(a_fp16, w_packed, s_w, y, acc_out=None):
+    """qqq_linear_w4a8_perchannel on the library's static device scratch: no workspace, and the
+    caller passes the output tensor too, so nothing is allocated on the way."""
+    M, K, lda = _fp16_rows(a_fp16)
+    N = s_w.shape[0]
+    _check(lib().qqq_linear_w4a8_perchannel_static(
+        ctypes.c_void_p(a_fp16.data_ptr()), lda, _ptr(w_packed, torch.uint8), _ptr(s_w, torch.float16),
+        _ptr(y, torch.float16), _ptr(acc_out, torch.int32), M, N, K, _stream()))
     return y
 
 

@@ -2,6 +2,8 @@
 #include <stdarg.h>
 #include <stdio.h>
 
+#include <mutex>
+
 #include "qqq_internal.h"
 
 namespace qqq {
@@ -306,6 +308,36 @@ static int linear_common(const void* a_fp16, int64_t lda, const void* w_packed, 
                      nullptr, 0, sums);
 }
 
+// ---- scratch of the entry point that allocates nothing: a device array that lives in the code
+// object (one copy per GPU, held until the process ends).  Host code never uses the array's name as
+// an address: the per-device address comes from hipGetSymbolAddress, once per device.
+static __device__ __align__(256) unsigned char scratch[QQQ_STATIC_SCRATCH_BYTES];
+static void* g_scratch_ptr[64] = {nullptr};
+static std::mutex g_scratch_mu;
+
+static int static_scratch(void** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+    return set_error(QQQ_ERR_HIP, "static scratch: no current device");
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || ptr == nullptr)
+      return set_error(QQQ_ERR_HIP, "static scratch: hipGetSymbolAddress: %s", hipGetErrorString(e));
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return QQQ_OK;
+}
+
+// zero fill by a kernel (a memset node recorded into a captured graph is avoided on purpose)
+__global__ __launch_bounds__(256) void zero_fill_kernel(uint4* p, size_t n16) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride)
+    p[i] = make_uint4(0, 0, 0, 0);
+}
+
 }  // namespace qqq
 
 using namespace qqq;
@@ -481,6 +513,44 @@ int qqq_linear_w4a8_pergroup(const void* a_fp16, int64_t lda, const void* w_pack
     return set_error(QQQ_ERR_SHAPE, "pergroup: sg_max must be in 0..127, got %d", sg_max);
   return linear_common(a_fp16, lda, w_packed, s_g, s_w_fp16, y_fp16, acc_out, M, N, K, workspace,
                        workspace_bytes, stream, group_mode(sg_max, M, N, K));
+}
+
+int qqq_linear_w4a8_perchannel_static(const void* a_fp16, int64_t lda, const void* w_packed,
+                                      const void* s_w_fp16, void* y_fp16, int32_t* acc_out, int64_t M,
+                                      int64_t N, int64_t K, void* stream) {
+  if (!gemm_shape_ok(M, N, K))
+    return set_error(QQQ_ERR_SHAPE, "linear_static: unsupported shape M=%lld N=%lld K=%lld (need N%%16==0, "
+                     "K%%128==0, 128<=K<=131072)", (long long)M, (long long)N, (long long)K);
+  const size_t need = qqq_linear_workspace_bytes(M, N, K);
+  if (need > (size_t)QQQ_STATIC_SCRATCH_BYTES)
+    return set_error(QQQ_ERR_WORKSPACE, "linear_static: M=%lld N=%lld K=%lld needs %zu bytes of scratch, the "
+                     "static scratch holds %zu; use qqq_linear_w4a8_perchannel with a workspace",
+                     (long long)M, (long long)N, (long long)K, need, (size_t)QQQ_STATIC_SCRATCH_BYTES);
+  if (M == 0) return QQQ_OK;
+  // everything linear_common checks before its first launch, checked here before the fill below
+  if (lda < K || lda % 8 != 0)
+    return set_error(QQQ_ERR_SHAPE, "linear_static: lda=%lld must be >= K and a multiple of 8", (long long)lda);
+  if (!a_fp16 || !w_packed || !s_w_fp16 || !y_fp16)
+    return set_error(QQQ_ERR_NULL, "linear_static: null pointer argument");
+  if (!aligned16(a_fp16) || !aligned16(w_packed) || !aligned16(y_fp16) ||
+      (reinterpret_cast<uintptr_t>(s_w_fp16) & 3u))
+    return set_error(QQQ_ERR_SHAPE, "linear_static: a_fp16, w_packed and y must be 16-byte aligned, s_w 4-byte");
+  void* ws = nullptr;
+  const int rc = static_scratch(&ws);
+  if (rc != QQQ_OK) return rc;
+  // The array keeps the previous call's contents.  The decode kernel (M <= 64) wants its arrival
+  // counters and split-K sums zero, and a previous call of another shape may have left other
+  // scratch there: clear that part.  (Every call leaves its own such part zero, so the fill is
+  // what protects against the OTHER parts of an earlier layout.)
+  if (M <= kSkinnyMaxM) {
+    const size_t n16 = (qqq_gemm_workspace_zero_bytes(M, N, K) + 15) / 16;
+    const unsigned blocks = (unsigned)((n16 + 255) / 256 < 1024 ? (n16 + 255) / 256 : 1024);
+    hipLaunchKernelGGL(zero_fill_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, (uint4*)ws, n16);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return set_error(QQQ_ERR_HIP, "linear_static: fill launch: %s", hipGetErrorString(e));
+  }
+  return linear_common(a_fp16, lda, w_packed, nullptr, s_w_fp16, y_fp16, acc_out, M, N, K, ws, need, stream,
+                       kPerChannel);
 }
 
 }  // extern "C"

@@ -92,6 +92,16 @@ def test_host_side_argument_errors(L):
                                       1 << 20, None) == 2                                      # group
     assert L.qqq_linear_w4a8_pergroup(bad, 128, bad, bad, bad, 128, 128, bad, None, 4, 128, 128, bad,
                                       1 << 20, None) == 2                                      # sg_max
+    # the entry point on the library's static scratch: same order, plus its size limit; nothing
+    # below gets as far as asking the runtime for the scratch address
+    st = (bad, bad, bad, None)
+    assert L.qqq_linear_w4a8_perchannel_static(bad, 128, *st, 4, 100, 128, None) == 2
+    assert L.qqq_linear_w4a8_perchannel_static(bad, 8192, *st, 4096, 28672, 8192, None) == 3
+    assert b"static scratch" in L.qqq_last_error()
+    assert L.qqq_linear_w4a8_perchannel_static(bad, 64, *st, 4, 128, 128, None) == 2            # lda < K
+    assert L.qqq_linear_w4a8_perchannel_static(None, 128, *st, 4, 128, 128, None) == 1
+    assert L.qqq_linear_w4a8_perchannel_static(ctypes.c_void_p(0x1008), 128, *st, 4, 128, 128, None) == 2
+    assert L.qqq_linear_w4a8_perchannel_static(bad, 128, *st, 0, 128, 128, None) == 0           # M == 0
 
 
 def test_binding_refuses_cpu_tensors():
