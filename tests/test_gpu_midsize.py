@@ -148,3 +148,18 @@ def test_automatic_choice_of_the_persistent_kernel_with_the_biased_route():
     a_q, s_a, w, s_w = inputs(M, K, N, 21)
     s_g, o_acc, o_y = reference("pg", a_q, s_a, w, s_w, K, N, 19, 16)
     check(*run("pg", a_q, s_a, w, s_w, K, s_g=s_g, sg_max=16), o_acc, o_y)
+
+
+@pytest.mark.parametrize("M,K,N", [(1100, 512, 16400), (1100, 384, 44048), (2065, 640, 13824)])
+@pytest.mark.parametrize("variant,hi,sg_max", [("pc", 0, 0), ("pg", 16, 16), ("pg", 127, 0)])
+def test_persistent_kernel_with_more_tiles_than_cus(M, K, N, variant, hi, sg_max):
+    """More 128x512 tiles than CUs, so every workgroup of the persistent kernel walks several tiles
+    and its DMA cursor crosses tile borders (297, 783 = three per CU, and 459 tiles), ragged in M
+    and N, K down to the kernel's minimum of three k-steps: automatic selection (the per-channel
+    variant and the short-K per-group routes take the persistent kernel here) and the kernel forced;
+    every element against the oracle."""
+    a_q, s_a, w, s_w = inputs(M, K, N, M + K + N + 5)
+    s_g, o_acc, o_y = reference(variant, a_q, s_a, w, s_w, K, N, 23, hi or 16)
+    check(*run(variant, a_q, s_a, w, s_w, K, s_g=s_g, sg_max=sg_max), o_acc, o_y)
+    qqq.set_prefill_tuning(13)
+    check(*run(variant, a_q, s_a, w, s_w, K, s_g=s_g, sg_max=sg_max), o_acc, o_y)
