@@ -1,0 +1,93 @@
+/*
+ * qqq_tuning.h — tuning and diagnostic controls of libqqq (MI355X W4A8 GEMM hot path).
+ *
+ * NOT part of the product interface (that is qqq.h): these functions exist for the tests, the
+ * benchmark's ablations and kernel tuning.  The setters change process-global host state and are
+ * not thread-safe; leave everything at 0 / default in production use.
+ */
+#ifndef QQQ_TUNING_H_
+#define QQQ_TUNING_H_
+
+#include "qqq.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * Which kernels the most recent GEMM or linear call of the calling thread enqueued, as a short
+ * host string (never NULL), e.g. "decode nt=4 mt=1 waves=8 depth=1 kslices=1 fused=1 mode=0" or
+ * "prefill persistent mode=0 tiles=7168 grid=256" or "prefill per-tile shape=5 ksplit=4 mode=5 +
+ * reduce"; a preceding "quant_act + " or "group-bias pre-pass + " names the other launches of the
+ * call.  For benchmarks and tests that must know which route they measured or compared.
+ */
+const char* qqq_last_route(void);
+
+/*
+ * Diagnostic check of the sg_max promise of qqq_gemm_w4a8_pergroup (Sec. 3.3.2's fused group scale
+ * in its integer form): counts the entries of s_g [K/128, N] outside 0..sg_max into *violations
+ * (device int32, overwritten).  A caller that cannot vouch for its scales runs this once per
+ * weight, offline, before promising sg_max.  Enqueues one kernel on `stream`.
+ */
+int qqq_debug_count_sg_violations(const int8_t* s_g, int64_t N, int64_t K, int sg_max,
+                                  int32_t* violations, void* stream);
+
+/*
+ * Tuning/diagnostic knob (host state, not thread-safe): 0 makes the qqq_linear_* calls always
+ * run the two kernels, 1 (default) lets them use the fused decode kernel.  Returns the previous
+ * value.
+ */
+int qqq_set_fused_quant(int enable);
+
+/*
+ * Tuning/diagnostic knob (host state, not thread-safe): force a kernel family.
+ *   0 = automatic (decode kernel up to 16 rows, prefill kernels above 64, a cost model in between),
+ *   1 = decode split-K kernel
+ *   (M <= 64), 2 = LDS-tiled prefill kernels.
+ * Returns the previous value.  Forcing a family outside its M range gives QQQ_ERR_SHAPE.
+ */
+int qqq_set_kernel_override(int family);
+
+/*
+ * Tuning/diagnostic knob (host state, not thread-safe): force how the per-group variant turns
+ * code x s_g into int8.  0 = automatic (from sg_max and M), 1 = scale applied to each group's
+ * partial sum (valid for s_g <= 16), 2 = per-weight saturating conversion (any s_g),
+ * 3 = per-weight fp16 FMA conversion without saturation (valid for s_g <= 16).  Values 1-3 act on
+ * qqq_gemm_w4a8_pergroup / qqq_linear_w4a8_pergroup (3 also keeps the prefill kernels off their
+ * default integer route).  4 acts on qqq_gemm_w4a8_pergroup_f16scale on the prefill path only and exists
+ * to be timed (the ablation of Sec. 4.5.2, Fig. 9): fp16 multiply, conventional round and
+ * fp16->int16 conversion instructions, byte packing; two roundings, so it equals the default route
+ * only where code*s is exact in fp16.  Returns the previous value.
+ */
+int qqq_set_group_mode_override(int mode);
+
+/*
+ * Tuning/diagnostic knob (host state, not thread-safe) for the skinny kernel: channel tiles per
+ * workgroup (1, 2 or 4), number of K slices, waves per workgroup (4, 8 or 16), load depth (1 =
+ * shallow, 2 = deep batches of in-flight loads); 0 = automatic for each.  Values that do not fit
+ * the shape are ignored.  Returns 0.
+ */
+int qqq_set_skinny_tuning(int channel_tiles, int k_slices, int waves, int depth);
+
+/*
+ * Tuning/diagnostic knob (host state, not thread-safe) for the prefill path: 0 = automatic;
+ * 10 = the DMA-ring kernel, one workgroup per tile, 128x512 tile on 8 waves; 15, 16, 17 = the same
+ * kernel with the narrow tiles meant for mid-size M: 128x256 on 8 waves, 128x128 on 4 waves,
+ * 64x128 on 4 waves; 13 = the persistent DMA-ring kernel (128x512 tiles, one workgroup per CU).
+ * Other values act like 0.  Returns 0.
+ */
+int qqq_set_prefill_tuning(int tune);
+
+/*
+ * Tuning/diagnostic knob (host state, not thread-safe): number of K splits of the per-tile prefill
+ * kernel for 16 < M <= 512 (each tile's K range is divided over that many workgroups, their raw
+ * int32 tiles meet in the workspace and a second kernel sums and dequantises them); 0 = automatic,
+ * 1 = never split.  Capped at 1024 / M and at K / 128; ignored without a workspace of the queried
+ * size.  Negative values only query.  Returns the previous value.
+ */
+int qqq_set_prefill_ksplit(int k_splits);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QQQ_TUNING_H_ */

@@ -16,7 +16,11 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "qqq_oracle.c")
-_LIB = os.path.join(_HERE, "libqqq_oracle.so")
+# QQQ_ORACLE_SANITIZE=<directory>: a separate build under gcc's address and undefined-behaviour
+# sanitizers, written to that directory (the process must then run with libasan preloaded;
+# tests/test_sanitizers.py does that in a child process)
+_SANITIZE = os.environ.get("QQQ_ORACLE_SANITIZE", "")
+_LIB = os.path.join(_SANITIZE, "libqqq_oracle_san.so") if _SANITIZE else os.path.join(_HERE, "libqqq_oracle.so")
 _lock = threading.Lock()
 _lib = None
 
@@ -27,8 +31,9 @@ def build(force: bool = False) -> str:
     """Compile the oracle with gcc (-O2 -fopenmp); returns the path of the shared object."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + ".tmp.%d" % os.getpid()
+        opt = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all"] if _SANITIZE else ["-O2"]
         subprocess.check_call(
-            ["gcc", "-O2", "-fopenmp", "-std=c11", "-fPIC", "-shared", "-Wall", "-Wextra",
+            ["gcc", *opt, "-fopenmp", "-std=c11", "-fPIC", "-shared", "-Wall", "-Wextra",
              "-o", tmp, _SRC, "-lm"]
         )
         os.replace(tmp, _LIB)

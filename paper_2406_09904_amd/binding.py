@@ -1,4 +1,5 @@
-"""Thin ctypes binding over libqqq.so (the C ABI declared in include/qqq.h).
+"""Thin ctypes binding over libqqq.so (the C ABI declared in include/qqq.h; tuning and
+diagnostic controls in include/qqq_tuning.h).
 
 Argument marshalling only: every step of the path runs in the library's HIP kernels.  PyTorch
 supplies device memory and the stream.  There is no CPU fallback: if the library is missing or a
@@ -12,7 +13,8 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libqqq.so")
+# QQQ_LIB_PATH: load another build of the same library (the host-sanitizer build of the CPU tests)
+LIB_PATH = os.environ.get("QQQ_LIB_PATH") or os.path.join(_HERE, "libqqq.so")
 GROUP = 128
 
 SYMBOLS = [
@@ -22,7 +24,8 @@ SYMBOLS = [
     "qqq_linear_w4a8_pergroup", "qqq_set_fused_quant", "qqq_set_kernel_override",
     "qqq_set_group_mode_override", "qqq_set_skinny_tuning", "qqq_set_prefill_tuning",
     "qqq_quantize_w4_perchannel", "qqq_quantize_w4_pergroup", "qqq_set_prefill_ksplit",
-    "qqq_gemm_workspace_zero_bytes", "qqq_linear_w4a8_perchannel_static",
+    "qqq_gemm_workspace_zero_bytes", "qqq_linear_w4a8_perchannel_static", "qqq_last_route",
+    "qqq_debug_count_sg_violations",
 ]
 
 _lib = None
@@ -46,6 +49,8 @@ def lib():
         vp, i64, sz, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t, ctypes.c_int
         L.qqq_version.restype = ci
         L.qqq_last_error.restype = ctypes.c_char_p
+        L.qqq_last_route.restype = ctypes.c_char_p
+        L.qqq_debug_count_sg_violations.argtypes = [vp, i64, i64, ci, vp, vp]
         L.qqq_quant_act.argtypes = [vp, i64, i64, i64, vp, vp, vp]
         L.qqq_packed_w4_bytes.argtypes = [i64, i64]
         L.qqq_packed_w4_bytes.restype = sz
@@ -290,6 +295,20 @@ def qqq_linear_w4a8_pergroup(a_fp16, w_packed, s_g, s_w, workspace, sg_max=0, y=
         _ptr(s_w, torch.float16), group, sg_max, _ptr(y, torch.float16), _ptr(acc_out, torch.int32),
         M, N, K, _ptr(workspace, torch.uint8), workspace.numel(), _stream()))
     return y
+
+
+def last_route() -> str:
+    """The kernels the most recent GEMM / linear call of this thread enqueued (include/qqq_tuning.h)."""
+    return lib().qqq_last_route().decode()
+
+
+def count_sg_violations(s_g: torch.Tensor, sg_max: int) -> int:
+    """Entries of the integer group-scale table [K/128, N] outside 0..sg_max (diagnostic; synchronises)."""
+    G, N = s_g.shape
+    out = torch.empty((1,), dtype=torch.int32, device=s_g.device)
+    _check(lib().qqq_debug_count_sg_violations(_ptr(s_g, torch.int8), N, G * GROUP, sg_max,
+                                               _ptr(out, torch.int32), _stream()))
+    return int(out.item())
 
 
 def set_fused_quant(enable: int) -> int:

@@ -24,9 +24,11 @@ def hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build(verbose: bool = False, extra_flags=()) -> str:
-    """Compile every HIP source for gfx950 and link the shared library; returns its path."""
-    objdir = os.path.join(HERE, "_build")
+def build(verbose: bool = False, extra_flags=(), out_dir: str = None) -> str:
+    """Compile every HIP source for gfx950 and link the shared library; returns its path.
+    out_dir: build somewhere else (objects and library), e.g. a host-sanitizer build for the tests."""
+    objdir = os.path.join(out_dir or HERE, "_build")
+    lib_path = os.path.join(out_dir, "libqqq.so") if out_dir else LIB
     os.makedirs(objdir, exist_ok=True)
     cc = hipcc()
 
@@ -44,13 +46,13 @@ def build(verbose: bool = False, extra_flags=()) -> str:
 
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         objs = list(ex.map(one, SOURCES))
-    tmp = LIB + ".tmp.%d" % os.getpid()
+    tmp = lib_path + ".tmp.%d" % os.getpid()
     r = subprocess.run([cc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs],
                        capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stdout + r.stderr)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, lib_path)
+    return lib_path
 
 
 if __name__ == "__main__":

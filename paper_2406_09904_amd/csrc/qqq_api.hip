@@ -1,6 +1,7 @@
 // C-ABI entry points of libqqq: argument validation and kernel-family dispatch (host code only).
 #include <stdarg.h>
 #include <stdio.h>
+#include <string.h>
 
 #include <mutex>
 
@@ -9,6 +10,7 @@
 namespace qqq {
 
 static thread_local char g_err[256] = "no error";
+static thread_local char g_route[256] = "";
 static int g_override = 0;
 static int g_group_mode = 0;
 static int g_fuse_quant = 1;
@@ -19,6 +21,19 @@ int set_error(int code, const char* fmt, ...) {
   vsnprintf(g_err, sizeof(g_err), fmt, ap);
   va_end(ap);
   return code;
+}
+
+// the kernels a call enqueued, for qqq_last_route(): launchers append, entry points reset
+void route_reset() { g_route[0] = 0; }
+void route_note(const char* fmt, ...) {
+  const size_t used = strlen(g_route);
+  if (used + 4 >= sizeof(g_route)) return;
+  size_t at = used;
+  if (used > 0) at += (size_t)snprintf(g_route + used, sizeof(g_route) - used, " + ");
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_route + at, sizeof(g_route) - at, fmt, ap);
+  va_end(ap);
 }
 
 int num_cus() {
@@ -165,15 +180,16 @@ static void bias_buffers(void* workspace, int64_t M, int64_t N, int64_t K, int8_
 // does gemm_common take the biased per-group route for this call? (same conditions as in there)
 static bool takes_bias_route(int mode, int64_t M, int64_t N, int64_t K);
 
-static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed, const int8_t* s_g,
-                       const void* s_w, void* y, int32_t* acc_out, int64_t M, int64_t N, int64_t K,
-                       void* workspace, size_t workspace_bytes, void* stream, int mode,
-                       const void* a_fp16 = nullptr, int64_t lda = 0, bool row_sums_ready = false) {
+// Everything a GEMM call checks on the host; runs before the first launch of a call, so that an
+// error means nothing was enqueued.  `fused`: the decode kernel quantises fp16 rows itself and takes
+// no a_q / s_a.  `ws_needed`: out, the bytes the chosen kernel family requires (0 = optional).
+static int gemm_validate(const int8_t* a_q, const float* s_a, const void* w_packed, const int8_t* s_g,
+                         const void* s_w, void* y, int64_t M, int64_t N, int64_t K, void* workspace,
+                         size_t workspace_bytes, int mode, bool fused) {
   if (!gemm_shape_ok(M, N, K))
     return set_error(QQQ_ERR_SHAPE, "gemm: unsupported shape M=%lld N=%lld K=%lld (need N%%16==0, "
                      "K%%128==0, 128<=K<=131072)", (long long)M, (long long)N, (long long)K);
   if (M == 0) return QQQ_OK;
-  const bool fused = a_fp16 != nullptr;  // the decode kernel quantises the rows itself
   if ((!fused && (!a_q || !s_a)) || !w_packed || !s_w || !y || (mode != kPerChannel && !s_g))
     return set_error(QQQ_ERR_NULL, "gemm: null pointer argument");
   if (!aligned16(a_q) || !aligned16(w_packed) || !aligned16(y) || !aligned16(workspace) ||
@@ -181,10 +197,33 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
       (reinterpret_cast<uintptr_t>(s_g) & 3u))
     return set_error(QQQ_ERR_SHAPE, "gemm: a_q, w_packed, y and workspace must be 16-byte aligned, "
                      "s_a, s_w and s_g 4-byte aligned");
+  if (((M + 63) / 64) * ((N + 127) / 128) > 0x7FFFFFFF)
+    return set_error(QQQ_ERR_SHAPE, "gemm: too many output tiles for one launch");
   const int family = kernel_family(M, N, K, mode != kPerChannel);
   if (family == 1 && M > kSkinnyMaxM)
     return set_error(QQQ_ERR_SHAPE, "gemm: skinny kernel forced but M=%lld > %d", (long long)M,
                      kSkinnyMaxM);
+  if (fused && family != 1) return set_error(QQQ_ERR_SHAPE, "gemm: fused quantisation needs the decode kernel");
+  if (family == 1) {
+    const size_t need = qqq_gemm_workspace_bytes(M, N, K);
+    if (!workspace) return set_error(QQQ_ERR_NULL, "gemm: workspace is NULL");
+    if (workspace_bytes < need)
+      return set_error(QQQ_ERR_WORKSPACE, "gemm: workspace %zu bytes < %zu needed", workspace_bytes,
+                       need);
+  }
+  return QQQ_OK;
+}
+
+static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed, const int8_t* s_g,
+                       const void* s_w, void* y, int32_t* acc_out, int64_t M, int64_t N, int64_t K,
+                       void* workspace, size_t workspace_bytes, void* stream, int mode,
+                       const void* a_fp16 = nullptr, int64_t lda = 0, bool row_sums_ready = false) {
+  const bool fused = a_fp16 != nullptr;  // the decode kernel quantises the rows itself
+  {
+    const int rc = gemm_validate(a_q, s_a, w_packed, s_g, s_w, y, M, N, K, workspace, workspace_bytes, mode, fused);
+    if (rc != QQQ_OK || M == 0) return rc;
+  }
+  const int family = kernel_family(M, N, K, mode != kPerChannel);
   GemmParams p;
   p.a_q = a_q;
   p.s_a = s_a;
@@ -204,13 +243,7 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
   p.part = nullptr;
   p.a_fp16 = (const uint4*)a_fp16;
   p.lda_vec = lda / 8;
-  if (fused && family != 1) return set_error(QQQ_ERR_SHAPE, "gemm: fused quantisation needs the decode kernel");
   if (family == 1) {
-    const size_t need = qqq_gemm_workspace_bytes(M, N, K);
-    if (!workspace) return set_error(QQQ_ERR_NULL, "gemm: workspace is NULL");
-    if (workspace_bytes < need)
-      return set_error(QQQ_ERR_WORKSPACE, "gemm: workspace %zu bytes < %zu needed", workspace_bytes,
-                       need);
     p.ws_cnt = (int32_t*)workspace;
     p.ws_acc = (int32_t*)((char*)workspace + ws_counter_bytes(N));
     return launch_gemm_skinny(p, mode, (hipStream_t)stream);
@@ -297,6 +330,10 @@ static int linear_common(const void* a_fp16, int64_t lda, const void* w_packed, 
                        stream, mode, a_fp16, lda);
   float* s_a = (float*)((char*)workspace + gemm_ws);
   int8_t* a_q = (int8_t*)((char*)workspace + gemm_ws + align256((size_t)M * 4));
+  {  // the GEMM's own checks, before the quantiser is enqueued: an error leaves nothing behind
+    const int rc = gemm_validate(a_q, s_a, w_packed, s_g, s_w, y, M, N, K, workspace, gemm_ws, mode, false);
+    if (rc != QQQ_OK) return rc;
+  }
   // the per-group prefill GEMM's biased route wants per-group row sums of the codes: the quantiser
   // has them in registers, so it writes them on the way
   int8_t *r_lo = nullptr, *r_hi = nullptr, *bc = nullptr;
@@ -331,6 +368,27 @@ static int static_scratch(void** out) {
   return QQQ_OK;
 }
 
+// entries of an int8 group-scale table outside 0..sg_max, counted by one workgroup (a diagnostic:
+// speed is beside the point, a single plain store of the total is)
+__global__ __launch_bounds__(1024) void sg_violation_kernel(const uint32_t* s_g, int64_t words, int sg_max,
+                                                            int32_t* out) {
+  __shared__ int total;
+  if (threadIdx.x == 0) total = 0;
+  __syncthreads();
+  int bad = 0;
+  for (int64_t i = threadIdx.x; i < words; i += 1024) {
+    const uint32_t w = s_g[i];
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      const int v = (int)(int8_t)((w >> (8 * b)) & 0xFFu);
+      bad += (v < 0 || v > sg_max) ? 1 : 0;
+    }
+  }
+  if (bad) atomicAdd(&total, bad);
+  __syncthreads();
+  if (threadIdx.x == 0) *out = total;
+}
+
 // zero fill by a kernel (a memset node recorded into a captured graph is avoided on purpose)
 __global__ __launch_bounds__(256) void zero_fill_kernel(uint4* p, size_t n16) {
   const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -348,6 +406,24 @@ int qqq_version(void) { return 100; }
 
 const char* qqq_last_error(void) { return g_err; }
 
+const char* qqq_last_route(void) { return g_route; }
+
+int qqq_debug_count_sg_violations(const int8_t* s_g, int64_t N, int64_t K, int sg_max, int32_t* violations,
+                                  void* stream) {
+  if (N < 4 || N % 4 != 0 || K < 128 || K % 128 != 0 || sg_max < 0 || sg_max > 127 || (K / 128) * N > 0x7FFFFFFFLL * 4)
+    return set_error(QQQ_ERR_SHAPE, "count_sg_violations: unsupported N=%lld K=%lld sg_max=%d", (long long)N,
+                     (long long)K, sg_max);
+  if (!s_g || !violations) return set_error(QQQ_ERR_NULL, "count_sg_violations: null pointer argument");
+  if ((reinterpret_cast<uintptr_t>(s_g) & 3u) || (reinterpret_cast<uintptr_t>(violations) & 3u))
+    return set_error(QQQ_ERR_SHAPE, "count_sg_violations: pointers must be 4-byte aligned");
+  const int64_t words = (K / 128) * N / 4;
+  hipLaunchKernelGGL(sg_violation_kernel, dim3(1), dim3(1024), 0, (hipStream_t)stream, (const uint32_t*)s_g, words,
+                     sg_max, violations);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return set_error(QQQ_ERR_HIP, "count_sg_violations launch: %s", hipGetErrorString(e));
+  return QQQ_OK;
+}
+
 int qqq_set_kernel_override(int family) {
   const int old = g_override;
   if (family >= 0 && family <= 2) g_override = family;
@@ -356,6 +432,7 @@ int qqq_set_kernel_override(int family) {
 
 int qqq_quant_act(const void* a_fp16, int64_t M, int64_t K, int64_t lda, int8_t* a_q, float* s_a,
                   void* stream) {
+  route_reset();
   if (M < 0 || M > 0x7FFFFFFF || K < 8 || K % 8 != 0 || K > (1 << 24) || lda < K || lda % 8 != 0)
     return set_error(QQQ_ERR_SHAPE, "quant_act: unsupported M=%lld K=%lld lda=%lld (need K%%8==0, "
                      "lda%%8==0, lda>=K)", (long long)M, (long long)K, (long long)lda);
@@ -459,6 +536,7 @@ int qqq_gemm_w4a8_perchannel(const int8_t* a_q, const float* s_a, const void* w_
                              const void* s_w_fp16, void* y_fp16, int32_t* acc_out, int64_t M,
                              int64_t N, int64_t K, void* workspace, size_t workspace_bytes,
                              void* stream) {
+  route_reset();
   return gemm_common(a_q, s_a, w_packed, nullptr, s_w_fp16, y_fp16, acc_out, M, N, K, workspace,
                      workspace_bytes, stream, kPerChannel);
 }
@@ -467,6 +545,7 @@ int qqq_gemm_w4a8_pergroup(const int8_t* a_q, const float* s_a, const void* w_pa
                            const int8_t* s_g, const void* s_w_fp16, int group, int sg_max,
                            void* y_fp16, int32_t* acc_out, int64_t M, int64_t N, int64_t K,
                            void* workspace, size_t workspace_bytes, void* stream) {
+  route_reset();
   if (group != QQQ_GROUP) return set_error(QQQ_ERR_SHAPE, "pergroup: group must be 128, got %d", group);
   if (sg_max < 0 || sg_max > 127)
     return set_error(QQQ_ERR_SHAPE, "pergroup: sg_max must be in 0..127, got %d", sg_max);
@@ -478,6 +557,7 @@ int qqq_gemm_w4a8_pergroup_f16scale(const int8_t* a_q, const float* s_a, const v
                                     const void* s_g_fp16, const void* s_w_fp16, int group,
                                     void* y_fp16, int32_t* acc_out, int64_t M, int64_t N, int64_t K,
                                     void* workspace, size_t workspace_bytes, void* stream) {
+  route_reset();
   if (group != QQQ_GROUP) return set_error(QQQ_ERR_SHAPE, "pergroup: group must be 128, got %d", group);
   // knob 4: the conventional-conversion ablation of Fig. 9 (prefill kernel only)
   const int mode = (g_group_mode == 4 && kernel_family(M, N, K, true) == 2) ? kGroupCvt : kGroupReal;
@@ -500,6 +580,7 @@ int qqq_linear_w4a8_perchannel(const void* a_fp16, int64_t lda, const void* w_pa
                                const void* s_w_fp16, void* y_fp16, int32_t* acc_out, int64_t M,
                                int64_t N, int64_t K, void* workspace, size_t workspace_bytes,
                                void* stream) {
+  route_reset();
   return linear_common(a_fp16, lda, w_packed, nullptr, s_w_fp16, y_fp16, acc_out, M, N, K, workspace,
                        workspace_bytes, stream, kPerChannel);
 }
@@ -508,6 +589,7 @@ int qqq_linear_w4a8_pergroup(const void* a_fp16, int64_t lda, const void* w_pack
                              const void* s_w_fp16, int group, int sg_max, void* y_fp16,
                              int32_t* acc_out, int64_t M, int64_t N, int64_t K, void* workspace,
                              size_t workspace_bytes, void* stream) {
+  route_reset();
   if (group != QQQ_GROUP) return set_error(QQQ_ERR_SHAPE, "pergroup: group must be 128, got %d", group);
   if (sg_max < 0 || sg_max > 127)
     return set_error(QQQ_ERR_SHAPE, "pergroup: sg_max must be in 0..127, got %d", sg_max);
@@ -518,6 +600,7 @@ int qqq_linear_w4a8_pergroup(const void* a_fp16, int64_t lda, const void* w_pack
 int qqq_linear_w4a8_perchannel_static(const void* a_fp16, int64_t lda, const void* w_packed,
                                       const void* s_w_fp16, void* y_fp16, int32_t* acc_out, int64_t M,
                                       int64_t N, int64_t K, void* stream) {
+  route_reset();
   if (!gemm_shape_ok(M, N, K))
     return set_error(QQQ_ERR_SHAPE, "linear_static: unsupported shape M=%lld N=%lld K=%lld (need N%%16==0, "
                      "K%%128==0, 128<=K<=131072)", (long long)M, (long long)N, (long long)K);

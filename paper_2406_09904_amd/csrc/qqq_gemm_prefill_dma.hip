@@ -22,6 +22,10 @@
 // 3.3.2 of the QQQ paper) and feeds MT MFMAs per converted fragment.
 #include "qqq_prefill_common.h"
 
+// The DMA helpers below name M0 as clobbered (they rewrite it before every use).  M0 is a
+// reserved register, which the compiler remarks on for any clobber list that names one.
+#pragma clang diagnostic ignored "-Winline-asm"
+
 namespace qqq {
 
 template <int MODE, int MT, int CT, int NW>
@@ -101,11 +105,11 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
   const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_ptr_t)lds;
   auto dma16 = [&](const int8_t* src, uint32_t dst) {
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src)
-                 : "memory");
+                 : "memory", "m0");
   };
   auto dma4 = [&](const int8_t* src, uint32_t dst) {
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(dst), "v"(src)
-                 : "memory");
+                 : "memory", "m0");
   };
   const uint32_t wave_u = (uint32_t)__builtin_amdgcn_readfirstlane(wave);
   auto issue_dma = [&](int t, int stage) {
@@ -177,7 +181,8 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
           acc[mt][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(*(const v4i*)(hp + j), *(const v4i*)(bp + j),
                                                              acc[mt][c], 0, 0, 0);
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[mt][c][v] *= 128;
+        for (int v = 0; v < 16; ++v)  // modular by design near the int32 limit: unsigned
+          acc[mt][c][v] = (int)((uint32_t)acc[mt][c][v] << 7);
         for (int j = 0; j < Gp; j += 32)
           acc[mt][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(*(const v4i*)(lp + j), *(const v4i*)(bp + j),
                                                              acc[mt][c], 0, 0, 0);
@@ -352,6 +357,8 @@ static int launch_dma(const GemmParams& p, hipStream_t st) {
                      dim3(NW * 64), 0, st, p, tiles_m, tiles_n);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return set_error(QQQ_ERR_HIP, "prefill gemm launch: %s", hipGetErrorString(e));
+  route_note("prefill per-tile tile=%dx%d waves=%d ksplit=%d mode=%d grid=%lld", S::kBM, S::kBN, NW, p.k_splits,
+             MODE, (long long)grid);
   return QQQ_OK;
 }
 
@@ -392,6 +399,7 @@ int launch_splitk_reduce(const GemmParams& p, int mode, hipStream_t st) {
     hipLaunchKernelGGL((splitk_reduce_kernel<false>), grid, block, 0, st, p);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return set_error(QQQ_ERR_HIP, "split-K reduce launch: %s", hipGetErrorString(e));
+  route_note("k-split reduce");
   return QQQ_OK;
 }
 

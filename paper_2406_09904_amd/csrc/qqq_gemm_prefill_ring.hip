@@ -19,6 +19,10 @@
 // 32 rows at a time into its own fp16 patch there and streams them out as 128-byte row segments.
 #include "qqq_prefill_common.h"
 
+// The DMA helpers below name M0 as clobbered (they rewrite it before every use).  M0 is a
+// reserved register, which the compiler remarks on for any clobber list that names one.
+#pragma clang diagnostic ignored "-Winline-asm"
+
 namespace qqq {
 
 template <int MODE>
@@ -85,11 +89,11 @@ __global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmPar
   const uint32_t wave_u = (uint32_t)__builtin_amdgcn_readfirstlane(wave);
   auto dma16 = [&](const int8_t* src, uint32_t dst) {
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src)
-                 : "memory");
+                 : "memory", "m0");
   };
   auto dma4 = [&](const int8_t* src, uint32_t dst) {
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(dst), "v"(src)
-                 : "memory");
+                 : "memory", "m0");
   };
   // enters tile `iter`: rebuilds the pointers and fetches the tile's scales (two more DMA loads)
   auto enter_dma_tile = [&](int iter) {
@@ -235,7 +239,8 @@ __global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmPar
             acc[mt][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(*(const v4i*)(hp + j), *(const v4i*)(bp + j),
                                                                acc[mt][c], 0, 0, 0);
 #pragma unroll
-          for (int v = 0; v < 16; ++v) acc[mt][c][v] *= 128;
+          for (int v = 0; v < 16; ++v)  // modular by design near the int32 limit: unsigned
+            acc[mt][c][v] = (int)((uint32_t)acc[mt][c][v] << 7);
           for (int j = 0; j < Gp; j += 32)
             acc[mt][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(*(const v4i*)(lp + j), *(const v4i*)(bp + j),
                                                                acc[mt][c], 0, 0, 0);
@@ -350,6 +355,8 @@ static int launch_ring(const GemmParams& p, hipStream_t st) {
                      tiles_m, tiles_n);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return set_error(QQQ_ERR_HIP, "prefill gemm launch: %s", hipGetErrorString(e));
+  route_note("prefill persistent tile=128x512 mode=%d tiles=%lld grid=%lld", MODE, (long long)tiles,
+             (long long)grid);
   return QQQ_OK;
 }
 

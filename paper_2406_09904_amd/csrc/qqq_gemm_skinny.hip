@@ -423,6 +423,8 @@ static int launch_one(const GemmParams& p, int S, hipStream_t st) {
                      dim3(W * 64), 0, st, p, NG, S);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return set_error(QQQ_ERR_HIP, "skinny gemm launch: %s", hipGetErrorString(e));
+  route_note("decode nt=%d mt=%d waves=%d depth=%d kslices=%d fused=%d mode=%d grid=%lld", NT, MT, W, U, S,
+             (int)FUSED, MODE, (long long)grid);
   return QQQ_OK;
 }
 

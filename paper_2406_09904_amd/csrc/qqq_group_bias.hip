@@ -98,6 +98,7 @@ int launch_group_bias_prepass(const int8_t* a_q, const int8_t* s_g, int64_t M, i
                      (int)N, (int)K, G, Gp, r_lo, r_hi, bc);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return set_error(QQQ_ERR_HIP, "group bias pre-pass launch: %s", hipGetErrorString(e));
+  route_note(with_row_sums ? "group-bias pre-pass" : "group-bias pre-pass (scales only)");
   return QQQ_OK;
 }
 

@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include "qqq.h"
+#include "qqq_tuning.h"
 
 namespace qqq {
 
@@ -55,6 +56,8 @@ struct GemmParams {
 // host-side helpers (qqq_api.hip)
 int set_error(int code, const char* fmt, ...);
 int num_cus();
+void route_reset();                      // qqq_last_route(): entry points reset,
+void route_note(const char* fmt, ...);   // launchers append what they enqueued
 
 // launchers; each returns QQQ_OK or QQQ_ERR_HIP/QQQ_ERR_SHAPE
 int launch_quant_act(const void* a, int64_t M, int64_t K, int64_t lda, int8_t* a_q, float* s_a,

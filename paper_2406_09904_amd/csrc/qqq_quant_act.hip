@@ -133,6 +133,7 @@ int launch_quant_act(const void* a, int64_t M, int64_t K, int64_t lda, int8_t* a
     launch_vpt<false>((const uint4*)a, lda / 8, nvec, (uint2*)a_q, s_a, rs, M, st);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return set_error(QQQ_ERR_HIP, "quant_act launch: %s", hipGetErrorString(e));
+  route_note(r_lo ? "quant_act (+ group row sums)" : "quant_act");
   return QQQ_OK;
 }
 

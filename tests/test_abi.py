@@ -1,5 +1,5 @@
 """CPU-only checks of the C-ABI boundary: the library loads, exports every function that
-include/qqq.h declares, and rejects bad arguments on the host before touching a GPU."""
+include/qqq.h and include/qqq_tuning.h declare, and rejects bad arguments on the host before touching a GPU."""
 import ctypes
 import os
 import re
@@ -7,7 +7,7 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "qqq.h")
+HEADERS = [os.path.join(ROOT, "include", "qqq.h"), os.path.join(ROOT, "include", "qqq_tuning.h")]
 
 
 @pytest.fixture(scope="module")
@@ -20,9 +20,16 @@ def L():
 
 
 def declared_functions():
-    src = open(HEADER).read()
-    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    return sorted(set(re.findall(r"\b(qqq_[a-z0-9_]+)\s*\(", src)))
+    names = set()
+    for h in HEADERS:
+        src = re.sub(r"/\*.*?\*/", "", open(h).read(), flags=re.S)
+        names |= set(re.findall(r"\b(qqq_[a-z0-9_]+)\s*\(", src))
+    return sorted(names)
+
+
+def test_product_header_carries_no_knobs():
+    src = re.sub(r"/\*.*?\*/", "", open(HEADERS[0]).read(), flags=re.S)
+    assert "qqq_set_" not in src and "qqq_debug_" not in src and "qqq_last_route" not in src
 
 
 def test_header_functions_are_exported(L):
@@ -92,6 +99,17 @@ def test_host_side_argument_errors(L):
                                       1 << 20, None) == 2                                      # group
     assert L.qqq_linear_w4a8_pergroup(bad, 128, bad, bad, bad, 128, 128, bad, None, 4, 128, 128, bad,
                                       1 << 20, None) == 2                                      # sg_max
+    # errors of the GEMM half are found before the quantiser is enqueued (two-kernel route, M*K > 8192):
+    # without a GPU a launch attempt would come back as error 4, the validation says 1 / 2
+    assert L.qqq_linear_w4a8_perchannel(bad, 256, None, bad, bad, None, 64, 128, 256, bad, 1 << 24, None) == 1
+    assert L.qqq_linear_w4a8_perchannel(bad, 256, bad, bad, ctypes.c_void_p(0x1004), None, 64, 128, 256, bad,
+                                        1 << 24, None) == 2
+    assert L.qqq_linear_w4a8_pergroup(bad, 256, bad, None, bad, 128, 15, bad, None, 64, 128, 256, bad,
+                                      1 << 24, None) == 1
+    # diagnostics
+    assert L.qqq_debug_count_sg_violations(None, 128, 128, 15, bad, None) == 1
+    assert L.qqq_debug_count_sg_violations(bad, 130, 128, 15, bad, None) == 2
+    assert isinstance(L.qqq_last_route(), bytes)
     # the entry point on the library's static scratch: same order, plus its size limit; nothing
     # below gets as far as asking the runtime for the scratch address
     st = (bad, bad, bad, None)

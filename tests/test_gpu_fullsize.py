@@ -72,6 +72,10 @@ def test_full_size_workload(name):
                                        sg_max=wl.sg_hi, acc_out=acc)
     else:
         y = qqq.qqq_gemm_w4a8_perchannel(d_q, d_sa, d_w, d_sw, ws, acc_out=acc)
+    route = qqq.last_route()
+    print("%s: %s" % (name, route), flush=True)
+    if not pg and M >= 2048:     # the launch bench.py times there: several tiles per CU, one cursor
+        assert "prefill persistent" in route, route
     torch.cuda.synchronize()
 
     o_q, o_sa = orc.quant_act(a.view(np.uint16))

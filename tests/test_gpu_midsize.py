@@ -155,11 +155,13 @@ def test_automatic_choice_of_the_persistent_kernel_with_the_biased_route():
 def test_persistent_kernel_with_more_tiles_than_cus(M, K, N, variant, hi, sg_max):
     """More 128x512 tiles than CUs, so every workgroup of the persistent kernel walks several tiles
     and its DMA cursor crosses tile borders (297, 783 = three per CU, and 459 tiles), ragged in M
-    and N, K down to the kernel's minimum of three k-steps: automatic selection (the per-channel
-    variant and the short-K per-group routes take the persistent kernel here) and the kernel forced;
-    every element against the oracle."""
+    and N, K down to the kernel's minimum of three k-steps: automatic selection (whatever the cost
+    model picks for the shape) and the persistent kernel forced; every element against the oracle.
+    The automatic choice of the persistent kernel itself is checked at the benchmark's full sizes."""
     a_q, s_a, w, s_w = inputs(M, K, N, M + K + N + 5)
     s_g, o_acc, o_y = reference(variant, a_q, s_a, w, s_w, K, N, 23, hi or 16)
     check(*run(variant, a_q, s_a, w, s_w, K, s_g=s_g, sg_max=sg_max), o_acc, o_y)
+    print("automatic route for %s M=%d K=%d N=%d: %s" % (variant, M, K, N, qqq.last_route()), flush=True)
     qqq.set_prefill_tuning(13)
     check(*run(variant, a_q, s_a, w, s_w, K, s_g=s_g, sg_max=sg_max), o_acc, o_y)
+    assert "prefill persistent" in qqq.last_route(), qqq.last_route()

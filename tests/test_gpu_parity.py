@@ -309,3 +309,27 @@ def test_whole_path_quant_then_gemm(variant, M, K, N):
     assert np.array_equal(d_q.cpu().numpy(), o_q)
     assert np.array_equal(d_sa.cpu().numpy(), o_sa)
     check(acc.cpu().numpy(), f16_bits(y), ws.cpu().numpy(), o_acc, o_y)
+
+
+def test_route_report_and_sg_max_check():
+    """The library says which kernels a call enqueued, and the diagnostic scan counts the group
+    scales that break an sg_max promise."""
+    M, K, N = 2, 1024, 512
+    wl = synth.Workload("route", "pergroup", M, K, N, seed=77)
+    a = torch.from_numpy(wl.activations()).cuda()
+    d_w = qqq.qqq_pack_w4(torch.from_numpy(wl.w_nat().view(np.int32)).cuda(), K)
+    s_g = wl.s_g()
+    d_sg, d_sw = torch.from_numpy(s_g).cuda(), torch.from_numpy(wl.s_w()).cuda()
+    qqq.qqq_linear_w4a8_pergroup(a, d_w, d_sg, d_sw, qqq.new_linear_workspace(M, N, K), sg_max=15)
+    assert "decode" in qqq.last_route() and "fused=1" in qqq.last_route(), qqq.last_route()
+    a_q, s_a = qqq.qqq_quant_act(a)
+    assert qqq.last_route() == "quant_act"
+    qqq.qqq_gemm_w4a8_pergroup(a_q, s_a, d_w, d_sg, d_sw, qqq.new_workspace(M, N, K), sg_max=15)
+    assert "decode" in qqq.last_route() and "fused=0" in qqq.last_route(), qqq.last_route()
+    assert qqq.count_sg_violations(d_sg, 15) == 0
+    assert qqq.count_sg_violations(d_sg, 7) == int((s_g > 7).sum())
+    bad = s_g.copy()
+    bad[3, 17] = -1
+    bad[0, 0] = 127
+    assert qqq.count_sg_violations(torch.from_numpy(bad).cuda(), 16) == 2
+    torch.cuda.synchronize()
