@@ -2,18 +2,24 @@
 """Benchmark of the W4A8 hot path (quantise activations -> W4A8 GEMM) on one MI355X.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-sweep]
-                  [--no-cpu-baseline] [--eager]
+                  [--no-cpu-baseline] [--no-clock] [--eager]
+                  [--ceilings | --token-sweep | --conversion-ablation | --front-end]
 
 A step is one pass of the whole hot path over one batch of seeded synthetic input that is
 already resident in HBM: per-token int8 quantisation of the fp16 activations, then the W4A8 GEMM
 of the workload's variant, through the library's one-call entry point qqq_linear_w4a8_* (for a
 few decode rows that is one fused kernel, otherwise qqq_quant_act's kernel followed by the GEMM
-kernel; weights were repacked once, offline, outside the timed region).  Packed
-weights (and group scales) exist in R copies whose total exceeds four times the 256 MiB
-last-level cache and consecutive steps rotate through them, so every step streams its weights
-from HBM rather than from cache.  The K timed steps are captured once into a HIP graph and
-replayed, which removes Python's launch overhead from microsecond-scale kernels (--eager
-disables that).  Prints ONE JSON line.
+kernel; weights were repacked once, offline, outside the timed region).  The headline workload is
+the largest single-GPU configuration (per-channel, M=4096 on the 28672 x 8192 layer); every other
+configuration point of the benchmark is a line of the `sweep` array.
+
+Cold-HBM protocol: packed weights (and group scales) exist in R copies whose total exceeds 1 GiB
+(four times the 256 MiB last-level cache) and consecutive steps rotate through them; before every
+timed replay a 512 MiB buffer is rewritten, so a replay shorter than one rotation starts cold too.
+The K timed steps are captured once into a HIP graph (removes Python's launch overhead from
+microsecond-scale kernels; --eager disables that) and the graph is replayed REPLAYS times, each
+replay timed with events on the launch stream: ms_per_step is the median replay / K, min and max
+are reported beside it.  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -30,11 +36,18 @@ if ROOT not in sys.path:
 METRIC = "W4A8 GEMM TOPS and % roofline (HBM at M<=16, int8 MFMA at M>=1024)"
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_I8_PEAK_TOPS = 5033.0     # dense int8 MFMA: 256 CU x 4 SIMD x 2048 op/clk x 2.4 GHz
-PRIMARY = "cfg2_pg_m1_k4096_n11008"
-SWEEP = ["cfg1_pc_m16_k4096_n4096", "cfg3_pc_m1_k5120_n13824", "cfg3_pc_m8_k5120_n13824",
-         "cfg3_pc_m2048_k5120_n13824", "cfg4_pg_m4096_k11008_n4096",
-         "cfg5_pc_m1_k8192_n28672", "cfg5_pg_m16_k8192_n28672", "cfg5_pc_m4096_k8192_n28672",
-         "cfg5_pg_m4096_k8192_n28672"]
+PRIMARY = "cfg5_pc_m4096_k8192_n28672"
+# every configuration point of the benchmark (17), in the order of its five configurations
+SWEEP = ["cfg1_pc_m16_k4096_n4096", "cfg2_pg_m1_k4096_n11008",
+         "cfg3_pc_m1_k5120_n13824", "cfg3_pc_m8_k5120_n13824", "cfg3_pc_m32_k5120_n13824",
+         "cfg3_pc_m128_k5120_n13824", "cfg3_pc_m512_k5120_n13824", "cfg3_pc_m2048_k5120_n13824",
+         "cfg4_pg_m4096_k11008_n4096",
+         "cfg5_pc_m1_k8192_n28672", "cfg5_pg_m1_k8192_n28672", "cfg5_pc_m16_k8192_n28672",
+         "cfg5_pg_m16_k8192_n28672", "cfg5_pc_m256_k8192_n28672", "cfg5_pg_m256_k8192_n28672",
+         "cfg5_pc_m4096_k8192_n28672", "cfg5_pg_m4096_k8192_n28672"]
+REPLAYS = 5                    # timed replays of the captured graph (min / median / max reported)
+FLUSH_BYTES = 512 << 20        # rewritten before every timed replay: twice the last-level cache
+ORACLE_FULL_MACS = 2e11        # the oracle runs the whole product up to this size, a row subset beyond
 
 
 def algorithmic_bytes(M, N, K, pergroup):
@@ -52,15 +65,10 @@ def fused_bytes(M, N, K, pergroup):
     return N * K // 2 + (K // 128 * N if pergroup else 0) + 2 * N + 2 * M * K + 2 * M * N
 
 
-def is_fused(M, K):
-    """Shapes for which qqq_linear_* runs the single fused kernel (see include/qqq.h)."""
-    return M <= 4 and M * K <= 8192
-
-
 class Case:
     """Device-resident inputs of one workload plus the launch closures."""
 
-    def __init__(self, wl, torch, qqq, rotate_bytes=1 << 30, max_copies=64):
+    def __init__(self, wl, torch, qqq, rotate_bytes=1 << 30, max_copies=128):
         import numpy as np
         self.wl = wl
         self.pg = wl.variant == "pergroup"
@@ -84,10 +92,15 @@ class Case:
         self.qqq = qqq
         self.ops = 2 * M * N * K
         self.bytes = algorithmic_bytes(M, N, K, self.pg)
-        self.fused = is_fused(M, K)
         # the GEMM-only timing reads a_q/s_a: fill them with the workload's real codes first (MFMA
         # power, hence clock and speed, depends on the operand values)
         self.quant()
+        # which kernels the library runs for this workload: asked, not re-derived
+        self.gemm(0)
+        self.gemm_route = qqq.last_route()
+        self.step(0)
+        self.step_route = qqq.last_route()
+        self.fused = "fused=1" in self.step_route
         torch.cuda.synchronize()
 
     def quant(self):
@@ -111,14 +124,25 @@ class Case:
             self.qqq.qqq_linear_w4a8_perchannel(self.a, self.w[r], self.s_w, self.lws, y=self.y)
 
 
-def timed(torch, fn, steps, warmup, use_graph):
-    """fn(i) enqueues one unit of work on the current stream.  Returns average ms per unit over
-    exactly `steps` units, measured with events on that stream between two synchronisations."""
+_flush = None
+
+
+def flush_cache(torch):
+    """Rewrites a 512 MiB buffer (read + write): whatever the last-level cache held is gone."""
+    global _flush
+    if _flush is None:
+        _flush = torch.zeros((FLUSH_BYTES // 4,), dtype=torch.int32, device="cuda")
+    _flush.add_(1)
+
+
+def timed(torch, fn, steps, warmup, use_graph, replays=REPLAYS):
+    """fn(i) enqueues one unit of work on the current stream.  The `steps` units are captured once
+    into a graph and replayed `replays` times (eager: re-issued), each replay preceded by a cache
+    flush and timed with events on that stream between two synchronisations.  Returns
+    ({"median","min","max"} in ms per unit, graph used?)."""
     for i in range(warmup):
         fn(i)
     torch.cuda.synchronize()
-    e0 = torch.cuda.Event(enable_timing=True)
-    e1 = torch.cuda.Event(enable_timing=True)
     graph = None
     if use_graph:
         try:
@@ -132,27 +156,40 @@ def timed(torch, fn, steps, warmup, use_graph):
             print("bench: graph capture failed (%s); timing eager launches" % ex, file=sys.stderr)
             graph = None
             torch.cuda.synchronize()
-    torch.cuda.synchronize()
-    e0.record()
-    if graph is not None:
-        graph.replay()
-    else:
-        for i in range(steps):
-            fn(warmup + i)
-    e1.record()
-    torch.cuda.synchronize()
-    return e0.elapsed_time(e1) / steps, graph is not None
+    per = []
+    for r in range(max(1, replays)):
+        flush_cache(torch)
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        if graph is not None:
+            graph.replay()
+        else:
+            for i in range(steps):
+                fn(warmup + i)
+        e1.record()
+        torch.cuda.synchronize()
+        per.append(e0.elapsed_time(e1) / steps)
+    per.sort()
+    return {"median": per[len(per) // 2], "min": per[0], "max": per[-1]}, graph is not None
+
+
+def timed_ms(torch, fn, steps, warmup, use_graph):
+    """Median ms per unit over three flushed replays (the secondary tables)."""
+    return timed(torch, fn, steps, warmup, use_graph, replays=3)[0]["median"]
 
 
 def roofline_for(case, step_ms, gemm_ms):
     """Roofline of the step's dominant kernel: the fused kernel (= the whole step) where
-    qqq_linear_* fuses, the GEMM kernel otherwise."""
+    qqq_linear_* fuses, the GEMM kernel (timed back to back alone) otherwise.  Bound: whichever of
+    algorithmic bytes / 8 TB/s and 2MNK / 5.03 POP/s is the longer time."""
     wl = case.wl
     if case.fused:
-        kernel, kernel_ms = "linear_w4a8_%s (fused quant_act + gemm)" % wl.variant, step_ms
+        kernel, kernel_ms = case.step_route, step_ms
         nbytes = fused_bytes(wl.M, wl.N, wl.K, case.pg)
     else:
-        kernel, kernel_ms, nbytes = "gemm_w4a8_%s" % wl.variant, gemm_ms, case.bytes
+        kernel, kernel_ms, nbytes = case.gemm_route, gemm_ms, case.bytes
     t_mem = nbytes / (HBM_PEAK_GBS * 1e9)
     t_mfma = case.ops / (MFMA_I8_PEAK_TOPS * 1e12)
     if t_mem >= t_mfma:
@@ -166,25 +203,117 @@ def roofline_for(case, step_ms, gemm_ms):
     roof["kernel"] = kernel
     roof["kernel_us"] = round(kernel_ms * 1e3, 3)
     roof["algorithmic_bytes"] = nbytes
+    # the benchmark's own targets: 70 % of HBM at M <= 16, 60 % of int8 MFMA peak at M >= 1024
+    if wl.M <= 16:
+        roof["target"] = {"frac": 0.70, "of": "hbm", "met": bool(roof["bound"] == "hbm" and roof["frac"] >= 0.70)}
+    elif wl.M >= 1024:
+        roof["target"] = {"frac": 0.60, "of": "mfma", "met": bool(roof["bound"] == "mfma" and roof["frac"] >= 0.60)}
+    else:
+        roof["target"] = None
     return roof
+
+
+def load_profile_json(fname, name):
+    try:
+        with open(os.path.join(ROOT, "profiles", fname)) as f:
+            return json.load(f).get(name)
+    except (OSError, ValueError, TypeError):
+        return None
 
 
 def load_traffic(name):
     """HBM bytes per GEMM launch from the rocprofv3 --pmc summaries under profiles/, if present."""
-    path = os.path.join(ROOT, "profiles", "traffic.json")
+    rec = load_profile_json("traffic.json", name)
     try:
-        with open(path) as f:
-            rec = json.load(f).get(name)
         return int(rec["fetch_bytes"]) + int(rec["write_bytes"]) if rec else None
-    except (OSError, ValueError, KeyError, TypeError):
+    except (KeyError, TypeError, ValueError):
+        return None
+
+
+def load_mfma_counters(name, kernel_us):
+    """int8 MFMA utilisation of the dominant kernel from the SQ counter summaries under profiles/
+    (SQ_INSTS_VALU_MFMA_MOPS_I8 * 512 operations per launch, SQ_VALU_MFMA_BUSY_CYCLES), where a
+    run for this workload was recorded: counted operations / (this run's kernel time * nominal peak)."""
+    rec = load_profile_json("mfma_counters.json", name)
+    if not rec:
+        return None
+    try:
+        out = {"counted_ops": int(rec["mops_i8"]) * 512,
+               "util_vs_nominal": round(int(rec["mops_i8"]) * 512 / (kernel_us * 1e-6) / (MFMA_I8_PEAK_TOPS * 1e12), 4)}
+        if "mfma_pipe_busy_frac" in rec:
+            out["mfma_pipe_busy_frac_profiled"] = rec["mfma_pipe_busy_frac"]
+        if "avg_clock_ghz" in rec:
+            out["avg_clock_ghz_profiled"] = rec["avg_clock_ghz"]
+        return out
+    except (KeyError, TypeError, ValueError):
         return None
 
 
 def measure(case, torch, steps, warmup, use_graph):
-    step_ms, graphed = timed(torch, case.step, steps, warmup, use_graph)
-    gemm_ms, _ = timed(torch, case.gemm, steps, warmup, use_graph)
-    quant_ms, _ = timed(torch, lambda i: case.quant(), steps, warmup, use_graph)
-    return step_ms, gemm_ms, quant_ms, graphed
+    step, graphed = timed(torch, case.step, steps, warmup, use_graph)
+    gemm, _ = timed(torch, case.gemm, steps, warmup, use_graph)
+    quant, _ = timed(torch, lambda i: case.quant(), steps, warmup, use_graph)
+    return step, gemm, quant, graphed
+
+
+def workload_line(case, torch, steps, warmup, use_graph):
+    """One configuration point: step / GEMM / quantiser times, roofline of the dominant kernel."""
+    wl = case.wl
+    step, gemm, quant, graphed = measure(case, torch, steps, warmup, use_graph)
+    roof = roofline_for(case, step["median"], gemm["median"])
+    roof["traffic"] = load_traffic(wl.name)
+    line = {"workload": wl.name, "variant": wl.variant, "M": wl.M, "K": wl.K, "N": wl.N,
+            "steps": steps, "replays": REPLAYS, "weight_copies_rotated": case.copies, "hip_graph": graphed,
+            "ms_per_step": round(step["median"], 6),
+            "ms_per_step_min": round(step["min"], 6), "ms_per_step_max": round(step["max"], 6),
+            "step_route": case.step_route, "gemm_route": case.gemm_route,
+            "gemm_us": round(gemm["median"] * 1e3, 3), "gemm_us_min": round(gemm["min"] * 1e3, 3),
+            "gemm_us_max": round(gemm["max"] * 1e3, 3),
+            "quant_act_us": round(quant["median"] * 1e3, 3),
+            "quant_act_gbs": round(quant_bytes(wl.M, wl.K) / (quant["median"] * 1e-3) / 1e9, 1),
+            "tops": round(case.ops / (step["median"] * 1e-3) / 1e12, 3),
+            "roofline": roof}
+    if roof["bound"] == "mfma":
+        line["mfma_util"] = load_mfma_counters(wl.name, roof["kernel_us"])
+    return line
+
+
+def sample_clock(torch, case):
+    """Shader clock reported by rocm-smi while the workload's GEMM runs back to back for about two
+    seconds, and once more when idle.  None where the tool is missing or unreadable."""
+    import re
+    import subprocess
+
+    def read():
+        try:
+            r = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=20)
+            m = re.search(r"sclk clock level:\s*\d+:\s*\((\d+)Mhz\)", r.stdout)
+            return int(m.group(1)) if m else None
+        except (OSError, subprocess.SubprocessError):
+            return None
+
+    try:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for i in range(10):
+                case.gemm(i)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        reps = int(max(1, min(100000, 2500.0 / max(e0.elapsed_time(e1), 1e-3))))
+        for _ in range(reps):                       # ~2.5 s of queued work; the host does not wait
+            graph.replay()
+        time.sleep(0.6)
+        busy = read()
+        torch.cuda.synchronize()
+    except Exception as ex:                         # noqa: BLE001 - a diagnostic, never fatal
+        print("bench: clock sampling failed (%s)" % ex, file=sys.stderr)
+        return None
+    time.sleep(0.5)
+    return {"sclk_mhz_during_gemm": busy, "sclk_mhz_idle": read(), "nominal_mhz": 2400,
+            "source": "rocm-smi --showclocks, one reading while %s's GEMM is replayed back to back" % case.wl.name}
 
 
 def real_scale_lines(wls, torch, qqq, args, use_graph):
@@ -205,7 +334,7 @@ def real_scale_lines(wls, torch, qqq, args, use_graph):
             qqq.qqq_gemm_w4a8_pergroup_f16scale(c.a_q, c.s_a, c.w[r], sgs[r], c.s_w, c.ws, y=c.y)
 
         st = max(5, min(args.steps, 20 if big else 100))
-        ms, _ = timed(torch, gemm, st, min(args.warmup, 5), use_graph)
+        ms = timed_ms(torch, gemm, st, min(args.warmup, 5), use_graph)
         nbytes = c.bytes + wl.K // 128 * wl.N       # fp16 scales: one more byte per group scale
         t_mem = nbytes / (HBM_PEAK_GBS * 1e9)
         t_mfma = c.ops / (MFMA_I8_PEAK_TOPS * 1e12)
@@ -236,7 +365,7 @@ def conversion_ablation(torch, qqq, wls, use_graph):
     rows = []
 
     def t(fn):
-        ms, _ = timed(torch, fn, 20, 5, use_graph)
+        ms = timed_ms(torch, fn, 20, 5, use_graph)
         return round(ms * 1e3, 1)
 
     def pg(i):
@@ -294,14 +423,14 @@ def front_end_lines(torch, qqq, synth, use_graph):
                 fn = lambda i, res=res: qqq.qqq_quantize_w4_pergroup(w, out=res)
                 nbytes = N * K * 2.5 + N * 2 + G * N * 5
             torch.cuda.synchronize()
-            ms, _ = timed(torch, fn, 10, 2, use_graph)
+            ms = timed_ms(torch, fn, 10, 2, use_graph)
             rows.append({"layer": name, "N": N, "K": K, "kernel": "quant_weight_kernel (%s)" % variant,
                          "us": round(ms * 1e3, 1), "bound": "hbm",
                          "achieved_gbs": round(nbytes / (ms * 1e-3) / 1e9, 1),
                          "frac": round(nbytes / (ms * 1e-3) / (HBM_PEAK_GBS * 1e9), 3)})
         w_nat, _ = qqq.qqq_quantize_w4_perchannel(w)
         out = qqq.qqq_pack_w4(w_nat, K)
-        ms, _ = timed(torch, lambda i: qqq.qqq_pack_w4(w_nat, K, out=out), 10, 2, use_graph)
+        ms = timed_ms(torch, lambda i: qqq.qqq_pack_w4(w_nat, K, out=out), 10, 2, use_graph)
         rows.append({"layer": name, "N": N, "K": K, "kernel": "pack_w4", "us": round(ms * 1e3, 1), "bound": "hbm",
                      "achieved_gbs": round(N * K / (ms * 1e-3) / 1e9, 1),
                      "frac": round(N * K / (ms * 1e-3) / (HBM_PEAK_GBS * 1e9), 3)})
@@ -343,7 +472,7 @@ def token_sweep(torch, qqq, synth, use_graph):
         }
         row = {"M": M}
         for key, fn in fns.items():
-            ms, _ = timed(torch, fn, st, 3, use_graph)
+            ms = timed_ms(torch, fn, st, 3, use_graph)
             row[key] = round(ms * 1e3, 2)
         row["speedup_perchannel_vs_fp16"] = round(row["fp16_matmul_us"] / row["perchannel_us"], 2)
         row["speedup_pergroup_vs_fp16"] = round(row["fp16_matmul_us"] / row["pergroup_us"], 2)
@@ -354,53 +483,136 @@ def token_sweep(torch, qqq, synth, use_graph):
             "rows": rows}
 
 
-def cpu_baseline(wl, budget_s=12.0):
-    """The oracle, as it stands, on this machine's host cores: whole path on the workload (repeated
-    until the time budget is used when one pass is short, on a row subset when one pass is long)."""
-    import numpy as np
-    from oracle import qqq_oracle as orc
+def host_cores():
     cores = os.cpu_count() or 1
     try:
         cores = len(os.sched_getaffinity(0))
     except AttributeError:
         pass
     env = os.environ.get("OMP_NUM_THREADS")
-    if env and env.isdigit():
-        cores = min(cores, int(env)) if int(env) > 0 else cores
-    a, w_nat, s_w = wl.activations(), wl.w_nat(), wl.s_w().view(np.uint16)
+    if env and env.isdigit() and int(env) > 0:
+        cores = min(cores, int(env))
+    return cores
+
+
+def oracle_rows(wl):
+    """Rows the oracle takes for a workload: all of them up to ORACLE_FULL_MACS multiply-accumulates,
+    else the first, one interior and the last 128-row tile plus 64 seeded random rows (all N columns)."""
+    import numpy as np
+    if float(wl.M) * wl.N * wl.K <= ORACLE_FULL_MACS:
+        return np.arange(wl.M), "all %d rows" % wl.M
+    g = np.random.default_rng(wl.seed + 11)
+    interior = 128 * int(g.integers(1, wl.M // 128 - 1))
+    rows = np.unique(np.concatenate([np.arange(0, 128), np.arange(interior, interior + 128),
+                                     np.arange(wl.M - 128, wl.M), g.integers(0, wl.M, 64)]))
+    return rows, "%d of %d rows (row tiles at 0, %d and %d plus 64 random rows)" % (
+        len(rows), wl.M, interior, wl.M - 128)
+
+
+def oracle_time(wl):
+    """One pass of the oracle as it stands (gcc -O2 -fopenmp, int64 accumulation, no blocking) over
+    the whole path of a workload on this machine's host cores: quant_act + the variant's GEMM + Dequant
+    on the rows of oracle_rows(), all N columns.  Returns seconds and the sample description."""
+    import numpy as np
+    from oracle import qqq_oracle as orc
+    rows, what = oracle_rows(wl)
+    a = np.ascontiguousarray(wl.activations()[rows])
+    w_nat, s_w = wl.w_nat(), wl.s_w().view(np.uint16)
     s_g = wl.s_g() if wl.variant == "pergroup" else None
-    rows = wl.M
-    macs_full = wl.M * wl.N * wl.K
-    if macs_full > 4e9:                       # keep one pass to roughly ten seconds
-        rows = max(1, int(wl.M * 4e9 / macs_full))
-    a = np.ascontiguousarray(a[:rows])
+    orc.lib()
+    t0 = time.perf_counter()
+    a_q, s_a = orc.quant_act(a.view(np.uint16))
+    if s_g is None:
+        orc.gemm_perchannel(a_q, s_a, w_nat, s_w)
+    else:
+        orc.gemm_pergroup(a_q, s_a, w_nat, s_g, s_w)
+    return time.perf_counter() - t0, len(rows), what
 
-    def one_pass():
-        a_q, s_a = orc.quant_act(a.view(np.uint16))
-        if s_g is None:
-            orc.gemm_perchannel(a_q, s_a, w_nat, s_w)
-        else:
-            orc.gemm_pergroup(a_q, s_a, w_nat, s_g, s_w)
 
-    one_pass()                                # builds/loads the library, warms the page cache
-    reps, t0 = 0, time.perf_counter()
-    while True:
-        one_pass()
-        reps += 1
-        el = time.perf_counter() - t0
-        if el >= budget_s or reps >= 200:
-            break
-    tops = 2.0 * rows * wl.N * wl.K * reps / el / 1e12
-    return {"value": round(tops, 6), "unit": "TOPS", "cores": cores, "kind": "oracle",
-            "sample": "%d pass(es) of quant_act + %s GEMM on rows 0..%d of %s (all N=%d columns, "
-                      "K=%d), %.1f s wall" % (reps, wl.variant, rows - 1, wl.name, wl.N, wl.K, el)}
+def cpu_baseline(wls, names, headline):
+    """The oracle timed on this machine's host cores beside the GPU numbers: one pass per configuration
+    point (bounded: the two M=4096 points on the 28672 x 8192 layer run a stated row subset and their
+    time is extrapolated by M / rows).  `value` is the headline workload's rate."""
+    cores = host_cores()
+    per = {}
+    for name in names:
+        wl = wls[name]
+        sec, nrows, what = oracle_time(wl)
+        macs = float(nrows) * wl.N * wl.K
+        rec = {"seconds": round(sec, 3), "rows": nrows, "gmac_per_s": round(macs / sec / 1e9, 2),
+               "extrapolated": nrows != wl.M}
+        if nrows != wl.M:
+            rec["seconds_full_extrapolated"] = round(sec * wl.M / nrows, 1)
+        per[name] = rec
+        print("oracle %s: %.2f s on %s" % (name, sec, what), file=sys.stderr, flush=True)
+    wl = wls[headline]
+    h = per[headline]
+    _, what = oracle_rows(wl)
+    return {"value": round(2.0 * h["rows"] * wl.N * wl.K / h["seconds"] / 1e12, 6), "unit": "TOPS",
+            "cores": cores, "kind": "oracle",
+            "sample": "one pass of quant_act + %s GEMM + Dequant of %s on %s, all N=%d columns, K=%d: %.1f s wall; "
+                      "the whole workload would take about %.0f s (extrapolated by M/rows)" % (
+                          wl.variant, wl.name, what, wl.N, wl.K, h["seconds"],
+                          h.get("seconds_full_extrapolated", h["seconds"])),
+            "per_workload": per}
+
+
+def ceilings(torch, qqq, synth):
+    """What this GPU gives plain kernels of the path's shape (include/qqq_tuning.h probes): a
+    streaming read of the benchmark's weight sizes, an empty launch, and the int8 MFMA pipe with the
+    prefill kernel's register dataflow on operand values of several kinds (the clock under MFMA
+    load depends on them)."""
+    import numpy as np
+    out = {}
+    sink = torch.zeros((4,), dtype=torch.int32, device="cuda")
+    buf = torch.ones((2 << 30,), dtype=torch.uint8, device="cuda")
+    rows = []
+    for mib in (8, 23, 35, 117, 1024):
+        nbytes = mib << 20
+        nrot = buf.numel() // nbytes
+        for wgs in (256, 512, 1024, 2048, 4096):
+            steps = 100 if mib < 1024 else 6
+
+            def fn(i, nbytes=nbytes, nrot=nrot, wgs=wgs):
+                qqq.probe_stream_read(buf, nbytes, wgs, sink, offset=(i % nrot) * nbytes)
+
+            ms = timed_ms(torch, fn, steps, 5, True)
+            rows.append({"mib": mib, "workgroups": wgs, "us": round(ms * 1e3, 2),
+                         "gbs": round(nbytes / (ms * 1e-3) / 1e9, 1)})
+    out["stream_read"] = rows
+    ms = timed_ms(torch, lambda i: qqq.probe_stream_read(buf, 16, 1, sink), 200, 10, True)
+    out["empty_launch_us"] = round(ms * 1e3, 2)
+    del buf
+    torch.cuda.empty_cache()
+    # operand values: the headline workload's quantised activations, weights as the kernels feed them
+    wl = synth.workloads()[PRIMARY]
+    a_q, _ = qqq.qqq_quant_act(torch.from_numpy(wl.activations()[:64]).cuda())
+    aq = a_q.cpu().numpy().reshape(-1)
+    g = np.random.default_rng(1)
+    na, nb = 4 * 4 * 512 * 16, 2 * 2 * 512 * 16
+    codes = g.integers(-8, 8, nb).astype(np.int8)
+    A = {"zero": np.zeros(na, np.int8), "workload activations": aq[:na].copy(),
+         "uniform int8": g.integers(-127, 128, na).astype(np.int8)}
+    B = {"zero": np.zeros(nb, np.int8), "16 x code (FastINT4toINT8)": (codes.astype(np.int16) * 16).astype(np.int8),
+         "code + 8 (offset binary)": (codes + 8).astype(np.int8), "uniform int8": g.integers(-128, 128, nb).astype(np.int8)}
+    rows = []
+    for an, bn in (("zero", "zero"), ("workload activations", "16 x code (FastINT4toINT8)"),
+                   ("workload activations", "code + 8 (offset binary)"), ("uniform int8", "uniform int8")):
+        da, db = torch.from_numpy(A[an]).cuda(), torch.from_numpy(B[bn]).cuda()
+        iters = 3000
+        ms = timed_ms(torch, lambda i: qqq.probe_mfma_i8(da, db, iters, 256, sink), 1, 1, False)
+        ops = 256 * 8 * iters * 4 * 8 * 65536.0
+        rows.append({"activations": an, "weights": bn, "ms": round(ms, 3), "tops": round(ops / ms / 1e9, 1),
+                     "frac_of_nominal": round(ops / ms / 1e9 / MFMA_I8_PEAK_TOPS, 4)})
+    out["mfma_i8_only"] = rows
+    return out
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default=PRIMARY)
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -410,6 +622,10 @@ def main():
                          "per-group prefill GEMM on the cfg4 shape (Sec. 4.5.2, Fig. 9)")
     ap.add_argument("--front-end", action="store_true",
                     help="only the offline weight front-end lines (fp16 weights -> int4 codes + scales, repack)")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="instead of the benchmark line: measured ceilings of this GPU (streaming read per "
+                         "size and launch width, empty launch, int8 MFMA pipe per operand-value kind)")
+    ap.add_argument("--no-clock", action="store_true", help="skip the rocm-smi clock reading")
     ap.add_argument("--token-sweep", action="store_true",
                     help="instead of the benchmark line: the paper's N=8192, K=21760 token sweep")
     args = ap.parse_args()
@@ -442,58 +658,66 @@ def main():
     if args.token_sweep:
         print(json.dumps({"token_sweep": token_sweep(torch, qqq, synth, use_graph)}), flush=True)
         return 0
+    if args.ceilings:
+        print(json.dumps({"ceilings": ceilings(torch, qqq, synth)}), flush=True)
+        return 0
     wl = wls[args.workload]
     case = Case(wl, torch, qqq)
-    step_ms, gemm_ms, quant_ms, graphed = measure(case, torch, args.steps, args.warmup, use_graph)
-    roof = roofline_for(case, step_ms, gemm_ms)
-    roof["traffic"] = load_traffic(wl.name)
+    head = workload_line(case, torch, args.steps, args.warmup, use_graph)
+    clocks = None if args.no_clock else sample_clock(torch, case)
+    roof = head["roofline"]
     out = {
-        "metric": METRIC, "value": round(case.ops / (step_ms * 1e-3) / 1e12, 4), "unit": "TOPS",
+        "metric": METRIC, "value": head["tops"], "unit": "TOPS",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(step_ms, 6), "higher_is_better": True, "scaling": "weak",
+        "ms_per_step": head["ms_per_step"], "ms_per_step_min": head["ms_per_step_min"],
+        "ms_per_step_max": head["ms_per_step_max"], "replays": REPLAYS,
+        "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": wl.name, "variant": wl.variant, "M": wl.M, "K": wl.K, "N": wl.N,
                    "group": 128 if wl.variant == "pergroup" else None,
-                   "step": "qqq_linear_w4a8_%s (%s)" % (
-                       wl.variant, "one fused kernel" if case.fused else
-                       "quant_act kernel + gemm kernel"),
-                   "weight_copies_rotated": case.copies, "hip_graph": graphed,
-                   "separate_quant_act_us": round(quant_ms * 1e3, 3),
-                   "separate_gemm_us": round(gemm_ms * 1e3, 3)},
+                   "step": "qqq_linear_w4a8_%s: %s" % (wl.variant, head["step_route"]),
+                   "weight_copies_rotated": case.copies, "hip_graph": head["hip_graph"],
+                   "cache_flush_before_each_replay_bytes": FLUSH_BYTES,
+                   "separate_quant_act_us": head["quant_act_us"],
+                   "separate_gemm_us": head["gemm_us"]},
         "roofline": roof,
+        "clocks": clocks,
     }
+    if "mfma_util" in head:
+        out["mfma_util"] = head["mfma_util"]
     del case
     torch.cuda.empty_cache()
 
+    names = [wl.name]
     if not args.no_sweep:
         sweep = []
         for name in SWEEP:
             if name == wl.name:
+                sweep.append(dict(head, note="the headline line"))
                 continue
             w2 = wls[name]
-            big = w2.M >= 1024
-            c2 = Case(w2, torch, qqq, rotate_bytes=(1 << 28) if big else (1 << 30))
-            st = max(5, min(args.steps, 20 if big else 100))
-            s_ms, g_ms, q_ms, _ = measure(c2, torch, st, min(args.warmup, 5), use_graph)
-            r2 = roofline_for(c2, s_ms, g_ms)
-            r2["traffic"] = load_traffic(name)
-            sweep.append({"workload": name, "steps": st, "ms_per_step": round(s_ms, 6),
-                          "gemm_us": round(g_ms * 1e3, 3), "quant_act_us": round(q_ms * 1e3, 3),
-                          "quant_act_gbs": round(quant_bytes(w2.M, w2.K) / (q_ms * 1e-3) / 1e9, 1),
-                          "tops": round(c2.ops / (s_ms * 1e-3) / 1e12, 3),
-                          "roofline": r2})
+            c2 = Case(w2, torch, qqq)
+            # graph length: a whole rotation of the weight copies for the short kernels
+            st = max(5, min(args.steps, 20)) if w2.M >= 256 else max(args.steps, min(c2.copies, 128))
+            sweep.append(workload_line(c2, torch, st, min(args.warmup, 5), use_graph))
+            print("bench %s: %.2f us/step, roofline %.3f (%s)" % (
+                name, sweep[-1]["ms_per_step"] * 1e3, sweep[-1]["roofline"]["frac"],
+                sweep[-1]["roofline"]["bound"]), file=sys.stderr, flush=True)
             del c2
             torch.cuda.empty_cache()
+            names.append(name)
         out["sweep"] = sweep
-
-    if not args.no_sweep:
+        met = [l["workload"] for l in sweep if l["roofline"]["target"] and l["roofline"]["target"]["met"]]
+        tgt = [l["workload"] for l in sweep if l["roofline"]["target"]]
+        out["targets"] = {"met": len(met), "of": len(tgt), "met_workloads": met}
         out["real_valued_group_scale"] = real_scale_lines(wls, torch, qqq, args, use_graph)
-
-    if not args.no_sweep:
         out["weight_front_end"] = front_end_lines(torch, qqq, synth, use_graph)
 
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl)
+        out["cpu_baseline"] = cpu_baseline(wls, names, wl.name)
+        if "sweep" in out:
+            for l in out["sweep"]:
+                l["oracle"] = out["cpu_baseline"]["per_workload"].get(l["workload"])
     print(json.dumps(out), flush=True)
     return 0
 

@@ -33,6 +33,23 @@ int qqq_debug_count_sg_violations(const int8_t* s_g, int64_t N, int64_t K, int s
                                   int32_t* violations, void* stream);
 
 /*
+ * Ceiling probes for the benchmark (not part of the path).  Each enqueues ONE kernel on `stream`;
+ * the caller times it.
+ *   qqq_probe_stream_read: `workgroups` x 256 threads read `bytes` (multiple of 16) of `buf` once
+ *     with coalesced 128-bit loads and nothing else: the streaming ceiling of a short launch.
+ *   qqq_probe_mfma_i8: `workgroups` x 8 waves, each wave 4 x 2 tiles of v_mfma_i32_32x32x32_i8 per
+ *     round (the prefill kernel's register dataflow, two waves per SIMD), operands held in
+ *     registers, no memory traffic in the loop: 2 * 32^3 * 32 * 8 * iters * 4 operations per
+ *     workgroup.  a_pool: 4*4*512 16-byte operand values (one per pool slot, row tile and thread),
+ *     b_pool: 2*2*512; every workgroup reads the same pools.  The chip's clock under MFMA load depends
+ *     on the operand values, which is why the caller supplies them.  sink: 4 bytes, never written
+ *     in practice.
+ */
+int qqq_probe_stream_read(const void* buf, size_t bytes, int workgroups, uint32_t* sink, void* stream);
+int qqq_probe_mfma_i8(const void* a_pool, const void* b_pool, int iters, int workgroups, int32_t* sink,
+                      void* stream);
+
+/*
  * Tuning/diagnostic knob (host state, not thread-safe): 0 makes the qqq_linear_* calls always
  * run the two kernels, 1 (default) lets them use the fused decode kernel.  Returns the previous
  * value.

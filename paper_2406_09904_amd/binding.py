@@ -25,7 +25,7 @@ SYMBOLS = [
     "qqq_set_group_mode_override", "qqq_set_skinny_tuning", "qqq_set_prefill_tuning",
     "qqq_quantize_w4_perchannel", "qqq_quantize_w4_pergroup", "qqq_set_prefill_ksplit",
     "qqq_gemm_workspace_zero_bytes", "qqq_linear_w4a8_perchannel_static", "qqq_last_route",
-    "qqq_debug_count_sg_violations",
+    "qqq_debug_count_sg_violations", "qqq_probe_stream_read", "qqq_probe_mfma_i8",
 ]
 
 _lib = None
@@ -51,6 +51,8 @@ def lib():
         L.qqq_last_error.restype = ctypes.c_char_p
         L.qqq_last_route.restype = ctypes.c_char_p
         L.qqq_debug_count_sg_violations.argtypes = [vp, i64, i64, ci, vp, vp]
+        L.qqq_probe_stream_read.argtypes = [vp, sz, ci, vp, vp]
+        L.qqq_probe_mfma_i8.argtypes = [vp, vp, ci, ci, vp, vp]
         L.qqq_quant_act.argtypes = [vp, i64, i64, i64, vp, vp, vp]
         L.qqq_packed_w4_bytes.argtypes = [i64, i64]
         L.qqq_packed_w4_bytes.restype = sz
@@ -309,6 +311,20 @@ def count_sg_violations(s_g: torch.Tensor, sg_max: int) -> int:
     _check(lib().qqq_debug_count_sg_violations(_ptr(s_g, torch.int8), N, G * GROUP, sg_max,
                                                _ptr(out, torch.int32), _stream()))
     return int(out.item())
+
+
+def probe_stream_read(buf: torch.Tensor, nbytes: int, workgroups: int, sink: torch.Tensor, offset: int = 0):
+    """One launch of the streaming-read ceiling probe over buf[offset : offset + nbytes] (uint8 tensor)."""
+    _check(lib().qqq_probe_stream_read(ctypes.c_void_p(buf.data_ptr() + offset), nbytes, workgroups,
+                                       _ptr(sink, torch.int32), _stream()))
+
+
+def probe_mfma_i8(a_pool: torch.Tensor, b_pool: torch.Tensor, iters: int, workgroups: int, sink: torch.Tensor):
+    """One launch of the int8 MFMA ceiling probe (a_pool 128 KiB, b_pool 32 KiB of int8 operand values)."""
+    if a_pool.numel() != 4 * 4 * 512 * 16 or b_pool.numel() != 2 * 2 * 512 * 16:
+        raise ValueError("operand pools must hold 4*4*512 and 2*2*512 16-byte values")
+    _check(lib().qqq_probe_mfma_i8(_ptr(a_pool, torch.int8), _ptr(b_pool, torch.int8), iters, workgroups,
+                                   _ptr(sink, torch.int32), _stream()))
 
 
 def set_fused_quant(enable: int) -> int:
