@@ -15,7 +15,8 @@ configuration point of the benchmark is a line of the `sweep` array.
 
 Cold-HBM protocol: packed weights (and group scales) exist in R copies whose total exceeds 1 GiB
 (four times the 256 MiB last-level cache) and consecutive steps rotate through them; before every
-timed replay a 512 MiB buffer is rewritten, so a replay shorter than one rotation starts cold too.
+timed replay a 512 MiB buffer is streamed through the chip (reads only), so a replay shorter than
+one rotation starts cold too.
 The K timed steps are captured once into a HIP graph (removes Python's launch overhead from
 microsecond-scale kernels; --eager disables that) and the graph is replayed REPLAYS times, each
 replay timed with events on the launch stream: ms_per_step is the median replay / K, min and max
@@ -46,7 +47,7 @@ SWEEP = ["cfg1_pc_m16_k4096_n4096", "cfg2_pg_m1_k4096_n11008",
          "cfg5_pg_m16_k8192_n28672", "cfg5_pc_m256_k8192_n28672", "cfg5_pg_m256_k8192_n28672",
          "cfg5_pc_m4096_k8192_n28672", "cfg5_pg_m4096_k8192_n28672"]
 REPLAYS = 5                    # timed replays of the captured graph (min / median / max reported)
-FLUSH_BYTES = 512 << 20        # rewritten before every timed replay: twice the last-level cache
+FLUSH_BYTES = 512 << 20        # read before every timed replay: twice the last-level cache
 ORACLE_FULL_MACS = 2e11        # the oracle runs the whole product up to this size, a row subset beyond
 
 
@@ -127,12 +128,17 @@ class Case:
 _flush = None
 
 
-def flush_cache(torch):
-    """Rewrites a 512 MiB buffer (read + write): whatever the last-level cache held is gone."""
+def flush_cache(torch, qqq=None):
+    """Streams a 512 MiB buffer through the chip with plain reads (the library's ceiling probe):
+    whatever the 256 MiB last-level cache held is gone, and nothing dirty is left behind whose
+    write-back would compete with the timed kernels (a rewritten buffer would do that)."""
     global _flush
+    from paper_2406_09904_amd import binding
     if _flush is None:
-        _flush = torch.zeros((FLUSH_BYTES // 4,), dtype=torch.int32, device="cuda")
-    _flush.add_(1)
+        _flush = (torch.zeros((FLUSH_BYTES,), dtype=torch.uint8, device="cuda"),
+                  torch.zeros((4,), dtype=torch.int32, device="cuda"))
+        torch.cuda.synchronize()
+    binding.probe_stream_read(_flush[0], FLUSH_BYTES, 2048, _flush[1])
 
 
 def timed(torch, fn, steps, warmup, use_graph, replays=REPLAYS):

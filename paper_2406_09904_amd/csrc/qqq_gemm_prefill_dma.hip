@@ -15,8 +15,11 @@
 // workgroup barrier (s_waitcnt vmcnt(number of DMA loads per wave per k-step)).
 //
 // LDS stage (<= 50 KiB): activations (32*MT) rows x 128 B with the 16-byte slots of row r
-// XOR-swizzled by r%8 (DMA writes lane-linear, so the swizzle is applied on the global side: lane
-// l fetches slot l%8 ^ row%8), then each wave's own 2*CT KiB of packed int4 codes exactly as they
+// XOR-swizzled by (r/2)%8 (DMA writes lane-linear, so the swizzle is applied on the global side:
+// lane l fetches slot l%8 ^ (row/2)%8).  The LDS of gfx950 serves a 128-bit read 16 lanes at a time
+// over 64 banks: the 16 rows such a group reads must land in 16 different 16-byte bank groups, i.e.
+// rows of equal parity need different slots, which (r/2)%8 gives and r%8 does not (rows r and r+8
+// would collide: measured 125 instead of 240 bytes per clock and CU), then each wave's own 2*CT KiB of packed int4 codes exactly as they
 // lie in memory, then (per-group variant) each wave's 32*CT group scales of the k-step.
 // Weights never cross waves: each wave converts its codes to int8 once per k-step (Sec. 3.3.1 /
 // 3.3.2 of the QQQ paper) and feeds MT MFMAs per converted fragment.
@@ -65,7 +68,7 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
   const int n_wave = tn * S::kBN + wave * 32 * CT;  // first channel of this wave
 
   // ---- DMA sources.  Activations: this wave copies rows 8*kAPieces*wave .. (1 KiB pieces of 8
-  // rows); lane l lands in slot l%8 of row l/8, so it fetches chunk (l%8) ^ (row%8).  Rows past M
+  // rows); lane l lands in slot l%8 of row l/8, so it fetches chunk (l%8) ^ ((row/2)%8).  Rows past M
   // re-read row M-1 (never stored).  Weights: this wave's 1 KiB chunks, copied verbatim; chunks
   // past N/16 re-read the last valid chunk (never stored).
   const int8_t* a_src[S::kAPieces];
@@ -74,7 +77,7 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
     const int r = 8 * (S::kAPieces * wave + i) + (lane >> 3);
     int m = m0 + r;
     if (m > M - 1) m = M - 1;
-    a_src[i] = p.a_q + (int64_t)m * K + (int64_t)t_first * S::kBK + (((lane & 7) ^ (r & 7)) << 4);
+    a_src[i] = p.a_q + (int64_t)m * K + (int64_t)t_first * S::kBK + (((lane & 7) ^ ((r >> 1) & 7)) << 4);
   }
   const int8_t* w_src[S::kWChunks];
 #pragma unroll
@@ -132,11 +135,11 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
   };
 
   // ---- per-lane LDS read offsets.  A operand of MFMA step s: row 32*mt + n32, chunk 2s+h, stored
-  // in slot (2s+h) ^ (row%8).  W: tile c is chunks 2c and 2c+1; this lane's pieces are at
+  // in slot (2s+h) ^ ((row/2)%8).  W: tile c is chunks 2c and 2c+1; this lane's pieces are at
   // (n32%16 + 16h)*16 and +512 of chunk 2c + n32/16.
   int a_off[4];
 #pragma unroll
-  for (int s = 0; s < 4; ++s) a_off[s] = n32 * 128 + (((2 * s + h) ^ (n32 & 7)) << 4);
+  for (int s = 0; s < 4; ++s) a_off[s] = n32 * 128 + (((2 * s + h) ^ ((n32 >> 1) & 7)) << 4);
   const int w_off = S::kAStage + wave * S::kWWave + (n32 >> 4) * 1024 + ((n32 & 15) + 16 * h) * 16;
   const int sg_off = S::kAStage + S::kWStage + wave * 256 + n32 * kSgBytes;
 

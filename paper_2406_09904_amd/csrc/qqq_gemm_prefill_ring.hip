@@ -67,7 +67,7 @@ __global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmPar
 
   // ---- DMA side: a cursor (tile iteration d_iter, k-step d_t) that runs two k-steps ahead.
   // Per-lane source pointers of the cursor's position: two activation rows (1 KiB pieces of 8
-  // rows; lane l lands in slot l%8 of row l/8 and fetches chunk (l%8)^(row%8); rows past M re-read
+  // rows; lane l lands in slot l%8 of row l/8 and fetches chunk (l%8)^((row/2)%8); rows past M re-read
   // row M-1), four 1 KiB weight chunks (chunks past N/16 re-read the last one) and a group-scale
   // dword (lanes past the wave's 64 channels, and channels past N, re-read a valid dword).  They
   // advance by constant strides per k-step and are rebuilt when the cursor enters a new tile,
@@ -77,7 +77,9 @@ __global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmPar
   const int8_t* pa[2];
   const int8_t* pw[4];
   const int8_t* psg = nullptr;
-  const int swz = ((lane & 7) ^ ((lane >> 3) & 7)) << 4;
+  // slot swizzle: 16-byte chunk c of tile row r sits in slot c ^ ((r >> 1) & 7) of its 128-byte LDS row
+  // (r = 16*wave + 8*i + lane/8 here, so (r >> 1) & 7 = (4*i + lane/16) & 7)
+  const int swz[2] = {((lane & 7) ^ ((lane >> 4) & 7)) << 4, ((lane & 7) ^ ((4 + (lane >> 4)) & 7)) << 4};
   const int64_t w_step = (int64_t)ntiles * 1024;  // bytes between k-steps of the packed weights
 
   // DMA loads are issued through inline assembly so that the compiler's wait-count pass does not
@@ -103,7 +105,7 @@ __global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmPar
     for (int i = 0; i < 2; ++i) {
       int m = tm * kBM + 16 * wave + 8 * i + (lane >> 3);
       if (m > M - 1) m = M - 1;
-      pa[i] = p.a_q + (int64_t)m * K + swz;
+      pa[i] = p.a_q + (int64_t)m * K + swz[i];
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -125,16 +127,21 @@ __global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmPar
     dma4((const int8_t*)(p.s_a + row), dst);
     dma4((const int8_t*)(p.s_w + col), dst + 256);
   };
-  // issues the cursor's k-step into `stage` and advances the cursor; returns true when the step
-  // was the first of a tile (two more loads are then in flight).  Past the last tile the cursor
-  // keeps re-fetching the last k-step (in bounds, never read), so wait counts never change.
-  auto issue_next_dma = [&](int stage) {
+  // The cursor's k-step goes into `stage` one DMA instruction at a time (piece 0..5, plus the group
+  // scales), so that the k-loop can spread the requests between its MFMAs: eight waves that
+  // issue all their requests at once right after a barrier queue up behind one address unit, and
+  // a wave that waits there issues no MFMA either.
+  auto issue_dma_piece = [&](int stage, int piece) {
     const uint32_t base = lds_base + (uint32_t)stage * kStage;
-#pragma unroll
-    for (int i = 0; i < 2; ++i) dma16(pa[i], base + (2 * wave_u + i) * 1024);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) dma16(pw[j], base + kAStage + wave_u * kWWave + j * 1024);
-    if constexpr (MODE != kPerChannel) dma4(psg, base + kSmall + wave_u * 256);
+    if (piece < 2) dma16(pa[piece], base + (2 * wave_u + piece) * 1024);
+    else if (piece < 6) dma16(pw[piece - 2], base + kAStage + wave_u * kWWave + (piece - 2) * 1024);
+    else if constexpr (MODE != kPerChannel) dma4(psg, base + kSmall + wave_u * 256);
+  };
+  // advances the cursor after a k-step's pieces are out; returns true when the step was the last of
+  // a tile and the next tile was entered (two more loads, the tile's scales, are then in flight).
+  // Past the last tile the cursor keeps re-fetching the last k-step (in bounds, never read), so
+  // wait counts never change.
+  auto advance_cursor = [&]() {
     ++d_t;
     if (d_t < T) {
 #pragma unroll
@@ -153,6 +160,11 @@ __global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmPar
     d_t = T - 1;  // stay on the last k-step
     return false;
   };
+  auto issue_next_dma = [&](int stage) {
+#pragma unroll
+    for (int piece = 0; piece < 7; ++piece) issue_dma_piece(stage, piece);
+    return advance_cursor();
+  };
   constexpr int kDmaPerStep = 6 + (MODE != kPerChannel ? 1 : 0);
   // "everything but my newest k-step of DMA has landed, my LDS reads are done", then the barrier;
   // `extra` = the newest k-step was followed by a tile's two scale loads
@@ -166,7 +178,7 @@ __global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmPar
   // ---- per-lane LDS read offsets (see gemm_prefill_dma_kernel)
   int a_off[4];
 #pragma unroll
-  for (int s = 0; s < 4; ++s) a_off[s] = n32 * 128 + (((2 * s + h) ^ (n32 & 7)) << 4);
+  for (int s = 0; s < 4; ++s) a_off[s] = n32 * 128 + (((2 * s + h) ^ ((n32 >> 1) & 7)) << 4);
   const int w_off = kAStage + wave * kWWave + (n32 >> 4) * 1024 + ((n32 & 15) + 16 * h) * 16;
   const int small_off = kSmall + wave * 256;
 
@@ -251,16 +263,24 @@ __global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmPar
     for (int t = 0; t < T; ++t) {
       // the cursor's k-step (two ahead, possibly already in the next tile) goes into the stage
       // that was read during the previous k-step (everyone is past the barrier inside it)
-      const bool extra = issue_next_dma(stage == 0 ? 2 : stage - 1);
+      const int dstage = stage == 0 ? 2 : stage - 1;
       const int8_t* sb = lds + stage * kStage;
+      issue_dma_piece(dstage, 0);
       read_a(a1, sb, 1);
       mfma_col(a0, make_b(0, 0), 0);
+      issue_dma_piece(dstage, 1);
       mfma_col(a0, make_b(1, 0), 1);
+      issue_dma_piece(dstage, 2);
       read_a(a0, sb, 2);
       mfma_col(a1, make_b(0, 1), 0);
+      issue_dma_piece(dstage, 3);
       mfma_col(a1, make_b(1, 1), 1);
+      issue_dma_piece(dstage, 4);
       read_a(a1, sb, 3);
       mfma_col(a0, make_b(0, 2), 0);
+      issue_dma_piece(dstage, 5);
+      issue_dma_piece(dstage, 6);
+      const bool extra = advance_cursor();
       mfma_col(a0, make_b(1, 2), 1);
       const v4i b30 = make_b(0, 3), b31 = make_b(1, 3);
       // my DMA of the next k-step has landed (only the loads of the one after may still be in

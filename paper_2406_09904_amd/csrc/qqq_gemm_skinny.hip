@@ -162,7 +162,8 @@ __device__ __forceinline__ void consume_batch(const Batch<NT, MT, U>& b, v4i (&a
               __builtin_amdgcn_mfma_i32_16x16x64_i8(b.a[u][mt][0], b0, (v4i){0, 0, 0, 0}, 0, 0, 0);
           part = __builtin_amdgcn_mfma_i32_16x16x64_i8(b.a[u][mt][1], b1, part, 0, 0, 0);
 #pragma unroll
-          for (int r = 0; r < 4; ++r) acc[mt][i][r] += (part[r] >> 4) * sg;
+          for (int r = 0; r < 4; ++r)  // |part >> 4| <= 127*8*128 < 2^23 and 0 <= sg <= 16: the full-rate
+            acc[mt][i][r] = __mul24(part[r] >> 4, sg) + acc[mt][i][r];  // 24-bit multiply(-add)
         } else {
           acc[mt][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(b.a[u][mt][0], b0, acc[mt][i], 0, 0, 0);
           acc[mt][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(b.a[u][mt][1], b1, acc[mt][i], 0, 0, 0);
