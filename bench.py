@@ -445,6 +445,38 @@ def front_end_lines(torch, qqq, synth, use_graph):
     return rows
 
 
+def offline_stage_lines(torch, qqq, synth):
+    """The offline stage on one synthetic layer (include/qqq_calib.h): adaptive smoothing with a 16-point
+    grid (Sec. 3.1) and Hessian-based compensation (Sec. 3.2).  Calibration-time code: wall time per
+    call with events, eager launches (thousands of small kernels; no roofline is claimed for it)."""
+    import numpy as np
+    rows = []
+
+    def wall(fn):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return round(e0.elapsed_time(e1), 3)
+
+    M, K, N = 512, 4096, 4096
+    x = torch.from_numpy(synth.activations_fp16(M, K, 301)).cuda()
+    w = torch.from_numpy(synth.weights_fp16(N, K, 302).view(np.int16)).cuda().view(torch.float16)
+    rows.append({"call": "qqq_adaptive_smoothing", "M": M, "K": K, "N": N, "grid_points": 16,
+                 "ms": wall(lambda: qqq.qqq_adaptive_smoothing(x, w, 16))})
+    rows.append({"call": "qqq_hessian", "M": M, "K": K, "ms": wall(lambda: qqq.qqq_hessian(x))})
+    K2, N2 = 1024, 4096
+    x2 = torch.from_numpy(synth.activations_fp16(M, K2, 303)).cuda()
+    w2 = torch.from_numpy(synth.weights_fp16(N2, K2, 304).view(np.int16)).cuda().view(torch.float16)
+    H = qqq.qqq_hessian(x2)
+    rows.append({"call": "qqq_gptq_quantize_w4_perchannel", "K": K2, "N": N2,
+                 "ms": wall(lambda: qqq.qqq_gptq_quantize_w4_perchannel(w2, H, 0.01))})
+    return rows
+
+
 def token_sweep(torch, qqq, synth, use_graph):
     """The paper's own GEMM-study shape (Sec. 4.4: N=8192, K=21760) over a sweep of token counts:
     GEMM-kernel time of the per-channel, the integer per-group and the real-valued per-group
@@ -718,6 +750,7 @@ def main():
         out["targets"] = {"met": len(met), "of": len(tgt), "met_workloads": met}
         out["real_valued_group_scale"] = real_scale_lines(wls, torch, qqq, args, use_graph)
         out["weight_front_end"] = front_end_lines(torch, qqq, synth, use_graph)
+        out["offline_stage"] = offline_stage_lines(torch, qqq, synth)
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wls, names, wl.name)

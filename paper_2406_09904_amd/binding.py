@@ -26,6 +26,8 @@ SYMBOLS = [
     "qqq_quantize_w4_perchannel", "qqq_quantize_w4_pergroup", "qqq_set_prefill_ksplit",
     "qqq_gemm_workspace_zero_bytes", "qqq_linear_w4a8_perchannel_static", "qqq_last_route",
     "qqq_debug_count_sg_violations", "qqq_probe_stream_read", "qqq_probe_mfma_i8",
+    "qqq_smoothing_workspace_bytes", "qqq_adaptive_smoothing", "qqq_channel_absmax", "qqq_smooth_apply",
+    "qqq_fp16_gemm_nt", "qqq_hessian", "qqq_gptq_workspace_bytes", "qqq_gptq_quantize_w4_perchannel",
 ]
 
 _lib = None
@@ -51,6 +53,16 @@ def lib():
         L.qqq_last_error.restype = ctypes.c_char_p
         L.qqq_last_route.restype = ctypes.c_char_p
         L.qqq_debug_count_sg_violations.argtypes = [vp, i64, i64, ci, vp, vp]
+        L.qqq_smoothing_workspace_bytes.argtypes = [i64, i64, i64]
+        L.qqq_smoothing_workspace_bytes.restype = sz
+        L.qqq_adaptive_smoothing.argtypes = [vp, vp, i64, i64, i64, ci, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.qqq_channel_absmax.argtypes = [vp, i64, i64, vp, vp]
+        L.qqq_smooth_apply.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp, vp, vp]
+        L.qqq_fp16_gemm_nt.argtypes = [vp, vp, i64, i64, i64, vp, vp]
+        L.qqq_hessian.argtypes = [vp, i64, i64, vp, vp]
+        L.qqq_gptq_workspace_bytes.argtypes = [i64, i64]
+        L.qqq_gptq_workspace_bytes.restype = sz
+        L.qqq_gptq_quantize_w4_perchannel.argtypes = [vp, vp, i64, i64, ctypes.c_double, vp, vp, vp, sz, vp]
         L.qqq_probe_stream_read.argtypes = [vp, sz, ci, vp, vp]
         L.qqq_probe_mfma_i8.argtypes = [vp, vp, ci, ci, vp, vp]
         L.qqq_quant_act.argtypes = [vp, i64, i64, i64, vp, vp, vp]
@@ -297,6 +309,79 @@ def qqq_linear_w4a8_pergroup(a_fp16, w_packed, s_g, s_w, workspace, sg_max=0, y=
         _ptr(s_w, torch.float16), group, sg_max, _ptr(y, torch.float16), _ptr(acc_out, torch.int32),
         M, N, K, _ptr(workspace, torch.uint8), workspace.numel(), _stream()))
     return y
+
+
+# ---- offline stage (include/qqq_calib.h): adaptive smoothing and Hessian-based compensation
+
+def _fp16_matrix(t):
+    if t.dtype != torch.float16 or t.dim() != 2 or not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous 2-D fp16 device tensor")
+    return t.shape
+
+
+def qqq_adaptive_smoothing(x_fp16, w_fp16, grid_points=20):
+    """Sec. 3.1 on one layer: X [M,K], W [N,K] fp16 -> dict(xs, ws, s, sigmas, losses, best); best is a
+    device tensor (no synchronisation here)."""
+    (M, K), (N, K2) = _fp16_matrix(x_fp16), _fp16_matrix(w_fp16)
+    if K != K2:
+        raise ValueError("X and W disagree on K")
+    dev = x_fp16.device
+    xs, ws = torch.empty_like(x_fp16), torch.empty_like(w_fp16)
+    s = torch.empty((K,), dtype=torch.float32, device=dev)
+    sigmas = torch.empty((grid_points,), dtype=torch.float32, device=dev)
+    losses = torch.empty((grid_points,), dtype=torch.float64, device=dev)
+    best = torch.empty((1,), dtype=torch.int32, device=dev)
+    nbytes = int(lib().qqq_smoothing_workspace_bytes(M, N, K))
+    work = torch.empty((max(nbytes, 16),), dtype=torch.uint8, device=dev)
+    _check(lib().qqq_adaptive_smoothing(_ptr(x_fp16), _ptr(w_fp16), M, N, K, grid_points, _ptr(xs), _ptr(ws),
+                                        _ptr(s), _ptr(sigmas), _ptr(losses), _ptr(best), _ptr(work),
+                                        work.numel(), _stream()))
+    return {"xs": xs, "ws": ws, "s": s, "sigmas": sigmas, "losses": losses, "best": best}
+
+
+def qqq_channel_absmax(x_fp16):
+    M, K = _fp16_matrix(x_fp16)
+    out = torch.empty((K,), dtype=torch.float32, device=x_fp16.device)
+    _check(lib().qqq_channel_absmax(_ptr(x_fp16), M, K, _ptr(out), _stream()))
+    return out
+
+
+def qqq_smooth_apply(x_fp16, w_fp16, absmax, sigma):
+    """sigma: 1-element fp32 device tensor.  -> (xs, ws, s)."""
+    (M, K), (N, _) = _fp16_matrix(x_fp16), _fp16_matrix(w_fp16)
+    xs, ws = torch.empty_like(x_fp16), torch.empty_like(w_fp16)
+    s = torch.empty((K,), dtype=torch.float32, device=x_fp16.device)
+    _check(lib().qqq_smooth_apply(_ptr(x_fp16), _ptr(w_fp16), _ptr(absmax, torch.float32), _ptr(sigma, torch.float32),
+                                  M, N, K, _ptr(xs), _ptr(ws), _ptr(s), _stream()))
+    return xs, ws, s
+
+
+def qqq_fp16_gemm_nt(x_fp16, w_fp16):
+    (M, K), (N, _) = _fp16_matrix(x_fp16), _fp16_matrix(w_fp16)
+    y = torch.empty((M, N), dtype=torch.float32, device=x_fp16.device)
+    _check(lib().qqq_fp16_gemm_nt(_ptr(x_fp16), _ptr(w_fp16), M, N, K, _ptr(y), _stream()))
+    return y
+
+
+def qqq_hessian(x_fp16):
+    M, K = _fp16_matrix(x_fp16)
+    H = torch.empty((K, K), dtype=torch.float64, device=x_fp16.device)
+    _check(lib().qqq_hessian(_ptr(x_fp16), M, K, _ptr(H), _stream()))
+    return H
+
+
+def qqq_gptq_quantize_w4_perchannel(w_fp16, H, percdamp=0.01):
+    """Sec. 3.2 on one layer: W [N,K] fp16, H [K,K] fp64 -> (w_nat int32 [N,K/8], s_w fp16 [N])."""
+    N, K = _fp16_matrix(w_fp16)
+    dev = w_fp16.device
+    w_nat = torch.empty((N, K // 8), dtype=torch.int32, device=dev)
+    s_w = torch.empty((N,), dtype=torch.float16, device=dev)
+    nbytes = int(lib().qqq_gptq_workspace_bytes(N, K))
+    work = torch.empty((max(nbytes, 16),), dtype=torch.uint8, device=dev)
+    _check(lib().qqq_gptq_quantize_w4_perchannel(_ptr(w_fp16), _ptr(H, torch.float64), N, K, float(percdamp),
+                                                 _ptr(w_nat, torch.int32), _ptr(s_w, torch.float16), _ptr(work),
+                                                 work.numel(), _stream()))
+    return w_nat, s_w
 
 
 def last_route() -> str:

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqqq.so")
 SOURCES = ["qqq_api.hip", "qqq_pack.hip", "qqq_quant_act.hip", "qqq_gemm_skinny.hip",
-           "qqq_gemm_prefill_dma.hip", "qqq_gemm_prefill_ring.hip", "qqq_group_bias.hip", "qqq_quant_weight.hip", "qqq_probes.hip"]
+           "qqq_gemm_prefill_dma.hip", "qqq_gemm_prefill_ring.hip", "qqq_group_bias.hip", "qqq_quant_weight.hip", "qqq_probes.hip", "qqq_calib.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]

@@ -1,5 +1,5 @@
 """CPU-only checks of the C-ABI boundary: the library loads, exports every function that
-include/qqq.h and include/qqq_tuning.h declare, and rejects bad arguments on the host before touching a GPU."""
+the headers under include/ declare, and rejects bad arguments on the host before touching a GPU."""
 import ctypes
 import os
 import re
@@ -7,7 +7,7 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADERS = [os.path.join(ROOT, "include", "qqq.h"), os.path.join(ROOT, "include", "qqq_tuning.h")]
+HEADERS = [os.path.join(ROOT, "include", h) for h in ("qqq.h", "qqq_tuning.h", "qqq_calib.h")]
 
 
 @pytest.fixture(scope="module")
@@ -110,6 +110,21 @@ def test_host_side_argument_errors(L):
     assert L.qqq_debug_count_sg_violations(None, 128, 128, 15, bad, None) == 1
     assert L.qqq_debug_count_sg_violations(bad, 130, 128, 15, bad, None) == 2
     assert isinstance(L.qqq_last_route(), bytes)
+    # offline stage
+    assert L.qqq_smoothing_workspace_bytes(64, 128, 256) > 64 * 128 * 4
+    assert L.qqq_smoothing_workspace_bytes(64, 100, 256) == 0
+    assert L.qqq_adaptive_smoothing(bad, bad, 64, 128, 200, 8, bad, bad, bad, bad, bad, bad, bad, 1 << 30, None) == 2
+    assert L.qqq_adaptive_smoothing(bad, bad, 64, 128, 256, 0, bad, bad, bad, bad, bad, bad, bad, 1 << 30, None) == 2
+    assert L.qqq_adaptive_smoothing(None, bad, 64, 128, 256, 8, bad, bad, bad, bad, bad, bad, bad, 1 << 30, None) == 1
+    assert L.qqq_adaptive_smoothing(bad, bad, 64, 128, 256, 8, bad, bad, bad, bad, bad, bad, bad, 16, None) == 3
+    assert L.qqq_channel_absmax(bad, 4, 100, bad, None) == 2
+    assert L.qqq_smooth_apply(bad, bad, bad, None, 4, 4, 128, bad, bad, bad, None) == 1
+    assert L.qqq_fp16_gemm_nt(bad, bad, 4, 4, 24, bad, None) == 2
+    assert L.qqq_hessian(bad, 4, 20000, bad, None) == 2
+    assert L.qqq_gptq_workspace_bytes(64, 256) >= 256 * 256 * 8 + 64 * 256 * 8
+    assert L.qqq_gptq_quantize_w4_perchannel(bad, bad, 64, 256, ctypes.c_double(-1.0), bad, bad, bad, 1 << 30, None) == 2
+    assert L.qqq_gptq_quantize_w4_perchannel(bad, None, 64, 256, ctypes.c_double(0.01), bad, bad, bad, 1 << 30, None) == 1
+    assert L.qqq_gptq_quantize_w4_perchannel(bad, bad, 64, 256, ctypes.c_double(0.01), bad, bad, bad, 64, None) == 3
     # the entry point on the library's static scratch: same order, plus its size limit; nothing
     # below gets as far as asking the runtime for the scratch address
     st = (bad, bad, bad, None)
