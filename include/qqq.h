@@ -67,8 +67,8 @@ int qqq_quant_act(const void* a_fp16, int64_t M, int64_t K, int64_t lda, int8_t*
  *     s_wc[n]      = fp16_rne( max_k |code * s_Wg| / 127 )        (fp16 -> int8 scale s_Wc)
  *     s_star[g][n] = min( fp16_rne( s_Wg / s_wc ), 18.203125 )    (s*_Wg; 0 where s_wc == 0; the cap,
  *                    the largest fp16 s with rne(7*s) <= 127, binds only where s_wc is subnormal)
- *     s_int[g][n]  = clamp( rne( s_star ), 1, 18 )                (for the integer-scale GEMM; then
- *                    pass sg_max = 0 or 18 there, since 16 < 18)
+ *     s_int[g][n]  = clamp( rne( s_star ), 1, 18 )                (for the integer-scale GEMM; pass
+ *                    sg_max = 18 | QQQ_SG_SYMMETRIC_CODES there: codes in [-7,7], no product saturates)
  *   w_fp16 [N, ldw] fp16 device, 16-byte aligned, ldw >= K, ldw % 8 == 0; K % 8 == 0 (per-group:
  *   K % 128 == 0).  w_nat [N, K/8] uint32 device, the natural format qqq_pack_w4 takes.
  *   s_w / s_wc [N] fp16; s_star, s_wg, s_int [K/128, N] row-major; s_int and s_wg may be NULL.
@@ -132,8 +132,14 @@ int qqq_gemm_w4a8_perchannel(const int8_t* a_q, const float* s_a, const void* w_
  *   s_g [K/128, N] int8 row-major; group must be 128.
  *   sg_max: the caller's promise that every s_g <= sg_max.  With 1 <= sg_max <= 16 the product
  *   cannot leave int8, the clamp is dead and a cheaper conversion is used; 0 = no promise
- *   (general saturating conversion).  A broken promise gives wrong results, not a fault.
+ *   (general saturating conversion).  A broken promise gives wrong results, not a fault
+ *   (qqq_debug_count_sg_violations in qqq_tuning.h checks one).
+ *   QQQ_SG_SYMMETRIC_CODES or-ed into sg_max adds the promise that no weight code is -8, i.e. the
+ *   symmetric code range [-7,7] that qqq_quantize_w4_pergroup emits: then the clamp is dead up to
+ *   sg_max = 18 (7 * 18 = 126), which is the range of that call's integer scales, and the cheaper
+ *   conversions apply to them too: pass sg_max = 18 | QQQ_SG_SYMMETRIC_CODES for its outputs.
  */
+#define QQQ_SG_SYMMETRIC_CODES 0x100
 int qqq_gemm_w4a8_pergroup(const int8_t* a_q, const float* s_a, const void* w_packed,
                            const int8_t* s_g, const void* s_w_fp16, int group, int sg_max,
                            void* y_fp16, int32_t* acc_out, int64_t M, int64_t N, int64_t K,

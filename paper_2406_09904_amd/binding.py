@@ -16,6 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 # QQQ_LIB_PATH: load another build of the same library (the host-sanitizer build of the CPU tests)
 LIB_PATH = os.environ.get("QQQ_LIB_PATH") or os.path.join(_HERE, "libqqq.so")
 GROUP = 128
+SG_SYMMETRIC_CODES = 0x100   # QQQ_SG_SYMMETRIC_CODES of include/qqq.h, or-ed into sg_max
 
 SYMBOLS = [
     "qqq_version", "qqq_last_error", "qqq_quant_act", "qqq_packed_w4_bytes", "qqq_pack_w4",

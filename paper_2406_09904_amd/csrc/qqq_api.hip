@@ -151,12 +151,21 @@ static int kernel_family(int64_t M, int64_t N, int64_t K, bool pergroup) {
   return prefill_us < 0.92 * decode_us ? 2 : 1;
 }
 
-// per-group conversion route from the caller's bound on the group scales
-static int group_mode(int sg_max, int64_t M, int64_t N, int64_t K) {
+// per-group conversion route from the caller's promises about the group scales (and the codes)
+static int group_mode(int sg_arg, int64_t M, int64_t N, int64_t K) {
+  const bool symmetric = (sg_arg & QQQ_SG_SYMMETRIC_CODES) != 0;  // no code is -8
+  const int sg_max = sg_arg & ~QQQ_SG_SYMMETRIC_CODES;
   int mode = kGroupClamp;
-  if (sg_max >= 1 && sg_max <= 16) mode = (kernel_family(M, N, K, true) == 1) ? kGroupLinear : kGroupFused;
+  const bool decode = kernel_family(M, N, K, true) == 1;
+  if (sg_max >= 1 && sg_max <= 16) mode = decode ? kGroupLinear : kGroupFused;
+  else if (symmetric && sg_max >= 17 && sg_max <= 18) mode = decode ? kGroupLinear : kGroupFusedWide;
   if (g_group_mode >= 1 && g_group_mode <= 3) mode = g_group_mode;
   return mode;
+}
+
+static bool sg_arg_ok(int sg_arg) {
+  const int sg_max = sg_arg & ~QQQ_SG_SYMMETRIC_CODES;
+  return sg_arg >= 0 && sg_max <= 127;
 }
 
 static size_t ws_rows(int64_t M) { return (size_t)(M < kSkinnyMaxM ? M : kSkinnyMaxM); }
@@ -287,12 +296,11 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
     const PrefillPlan plan = plan_prefill(M, N, K, can_split, forced_split);
     if (plan.shape != 0 || plan.k_splits > 1) return per_tile(plan.shape, plan.k_splits);
     if (mode == kGroupReal) return launch_gemm_prefill_dma(p, mode, 0, (hipStream_t)stream);
-    // Measured on MI355X: the persistent kernel wins for the per-channel variant at every K and
-    // for the per-group variant when tiles are short (its per-k-step cost is a little higher
-    // there, its per-tile cost much lower): up to K = 4096 with the biased conversion (7 % at
-    // K = 1024, level at 8192), up to 3072 with the others.
+    // Measured on MI355X: the persistent kernel is level with the per-tile one for the per-channel
+    // variant and 1-7 % ahead for the per-group variant whenever a CU walks more than one tile
+    // (the next tile's first k-steps load under the epilogue).
     const bool tiles_repeat = tiles > num_cus();
-    if (mode == kPerChannel || (tiles_repeat && K <= (mode == kGroupBias ? 4096 : 3072)))
+    if (mode == kPerChannel || tiles_repeat)
       return launch_gemm_prefill_ring(p, mode, (hipStream_t)stream);
     return launch_gemm_prefill_dma(p, mode, 0, (hipStream_t)stream);
   }
@@ -547,8 +555,9 @@ int qqq_gemm_w4a8_pergroup(const int8_t* a_q, const float* s_a, const void* w_pa
                            void* workspace, size_t workspace_bytes, void* stream) {
   route_reset();
   if (group != QQQ_GROUP) return set_error(QQQ_ERR_SHAPE, "pergroup: group must be 128, got %d", group);
-  if (sg_max < 0 || sg_max > 127)
-    return set_error(QQQ_ERR_SHAPE, "pergroup: sg_max must be in 0..127, got %d", sg_max);
+  if (!sg_arg_ok(sg_max))
+    return set_error(QQQ_ERR_SHAPE, "pergroup: sg_max must be in 0..127 (optionally or-ed with "
+                     "QQQ_SG_SYMMETRIC_CODES), got %d", sg_max);
   return gemm_common(a_q, s_a, w_packed, s_g, s_w_fp16, y_fp16, acc_out, M, N, K, workspace,
                      workspace_bytes, stream, group_mode(sg_max, M, N, K));
 }
@@ -591,8 +600,9 @@ int qqq_linear_w4a8_pergroup(const void* a_fp16, int64_t lda, const void* w_pack
                              size_t workspace_bytes, void* stream) {
   route_reset();
   if (group != QQQ_GROUP) return set_error(QQQ_ERR_SHAPE, "pergroup: group must be 128, got %d", group);
-  if (sg_max < 0 || sg_max > 127)
-    return set_error(QQQ_ERR_SHAPE, "pergroup: sg_max must be in 0..127, got %d", sg_max);
+  if (!sg_arg_ok(sg_max))
+    return set_error(QQQ_ERR_SHAPE, "pergroup: sg_max must be in 0..127 (optionally or-ed with "
+                     "QQQ_SG_SYMMETRIC_CODES), got %d", sg_max);
   return linear_common(a_fp16, lda, w_packed, s_g, s_w_fp16, y_fp16, acc_out, M, N, K, workspace,
                        workspace_bytes, stream, group_mode(sg_max, M, N, K));
 }

@@ -426,6 +426,7 @@ int launch_gemm_prefill_dma(const GemmParams& p, int mode, int shape, hipStream_
     // applying the group scale to partial sums costs more VALU work than the MFMAs hide once
     // the tile has many rows, so both clamp-free requests use the per-weight fp16 FMA route here
     case kGroupLinear:
+    case kGroupFusedWide:
     case kGroupFused: return launch_shape<kGroupFused>(p, shape, st);
     case kGroupReal: return launch_shape<kGroupReal>(p, shape, st);
     case kGroupCvt: return launch_dma<kGroupCvt, 4, 2, 8>(p, st);  // timing ablation: one shape

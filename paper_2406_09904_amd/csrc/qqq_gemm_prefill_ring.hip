@@ -390,6 +390,7 @@ int launch_gemm_prefill_ring(const GemmParams& p, int mode, hipStream_t st) {
     // applying the group scale to partial sums costs more VALU work than the MFMAs hide once
     // the tile has many rows, so both clamp-free requests use the per-weight fp16 FMA route here
     case kGroupLinear:
+    case kGroupFusedWide:
     case kGroupFused: return launch_ring<kGroupFused>(p, st);
     case kGroupBias: return launch_ring<kGroupBias>(p, st);
     // conversion routes this kernel does not carry

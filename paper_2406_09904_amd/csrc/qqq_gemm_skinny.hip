@@ -501,6 +501,7 @@ int launch_gemm_skinny(const GemmParams& p, int mode, hipStream_t st) {
     case kPerChannel: return launch_mode<kPerChannel>(p, st);
     case kGroupLinear: return launch_mode<kGroupLinear>(p, st);
     case kGroupClamp: return launch_mode<kGroupClamp>(p, st);
+    case kGroupFusedWide:
     case kGroupFused: return launch_mode<kGroupFused>(p, st);
     case kGroupReal: return launch_mode<kGroupReal>(p, st);
   }

@@ -20,6 +20,9 @@ enum Mode : int {
                       // the group's partial int32 sum instead of to each weight (same integers)
   kGroupClamp = 2,    // Sec. 3.3.2, general: code*s_g saturated to int8 per weight (fp16 route)
   kGroupFused = 3,    // Sec. 3.3.2 with s_g <= 16: per-weight fp16 FMA + byte extract, no clamp
+  kGroupFusedWide = 7,  // the same conversion for s_g <= 18 under the promise that no code is -8 (its
+                        // constants stay exact in fp16 and code * s_g stays inside int8); not eligible
+                        // for the biased integer route, whose byte products (code + 8) * s_g need s_g <= 17
   kGroupBias = 5,     // Sec. 3.3.2 with s_g <= 16, prefill: byte-wise integer multiply of code+8, sign by a
                       // top-bit flip; the constant 8*s_g - 128 per weight is taken out again through
                       // per-group row sums of the activations (see qqq_group_bias.hip)

@@ -79,6 +79,8 @@ def test_host_side_argument_errors(L):
     assert L.qqq_gemm_w4a8_pergroup(*g, 128, 200, bad, None, 4, 128, 128, bad, 1 << 20, None) == 2
     assert L.qqq_gemm_w4a8_pergroup(bad, bad, bad, None, bad, 128, 0, bad, None, 4, 128, 128, bad,
                                     1 << 20, None) == 1
+    assert L.qqq_gemm_w4a8_pergroup(*g, 128, 0x200, bad, None, 4, 128, 128, bad, 1 << 20, None) == 2
+    assert L.qqq_gemm_w4a8_pergroup(*g, 128, 0x100 | 128, bad, None, 4, 128, 128, bad, 1 << 20, None) == 2
     assert b"workspace" in L.qqq_last_error() or len(L.qqq_last_error()) > 0
     # real-valued fp16 group scales: same validation
     assert L.qqq_gemm_w4a8_pergroup_f16scale(*g, 64, bad, None, 4, 128, 128, bad, 1 << 20, None) == 2

@@ -145,11 +145,15 @@ def test_linear_layer_from_fp16_weights(M):
     assert np.array_equal(acc.cpu().numpy(), o_acc)
     assert ulp_distance(f16_bits(y), o_y).max() <= 1
 
-    y = qqq.qqq_gemm_w4a8_pergroup(d_aq, d_sa, qqq.qqq_pack_w4(w_nat, K), s_int, s_wc, ws,
-                                   sg_max=18, acc_out=acc)
     o_acc, _, o_y = orc.gemm_pergroup(a_q, s_a, o_nat, o_int, o_wc)
-    assert np.array_equal(acc.cpu().numpy(), o_acc)
-    assert ulp_distance(f16_bits(y), o_y).max() <= 1
+    # the integer scales reach 18 but the codes stay in [-7,7]: with that promise the clamp-free
+    # conversions carry them; without it the saturating one does; both give the oracle's result
+    for sg_arg, clamp_free in ((18 | qqq.SG_SYMMETRIC_CODES, True), (18, False)):
+        y = qqq.qqq_gemm_w4a8_pergroup(d_aq, d_sa, qqq.qqq_pack_w4(w_nat, K), s_int, s_wc, ws,
+                                       sg_max=sg_arg, acc_out=acc)
+        assert ("mode=2" not in qqq.last_route()) == clamp_free, qqq.last_route()
+        assert np.array_equal(acc.cpu().numpy(), o_acc)
+        assert ulp_distance(f16_bits(y), o_y).max() <= 1
 
 
 @pytest.mark.parametrize("variant", ["perchannel", "pergroup"])
@@ -160,3 +164,35 @@ def test_full_size_layer(variant):
         check_perchannel(w16)
     else:
         check_pergroup(w16)
+
+
+@pytest.mark.parametrize("M,K,N", [(1, 1024, 512), (16, 2048, 256), (40, 512, 1024), (200, 640, 528),
+                                   (1100, 384, 16400)])
+def test_symmetric_codes_with_integer_scales_up_to_18(M, K, N):
+    """Codes in [-7,7] and integer group scales over the whole range 1..18 (what the front-end can
+    emit): no product saturates, so the clamp-free routes must equal the oracle, whose clamp is
+    there but never fires; every kernel family the shape can take."""
+    g = synth.rng(500 + M)
+    codes = g.integers(-7, 8, (N, K)).astype(np.int8)
+    w_nat = synth.codes_to_w_nat(codes)
+    s_g = g.integers(1, 19, (K // 128, N)).astype(np.int8)
+    s_g[0, :] = 18
+    a_q = synth.int8_activations(M, K, 501 + M)
+    s_a = synth.token_scales(M, 502 + M)
+    s_w = synth.weight_scales_fp16(N, 503 + M, 0.001, 0.01)
+    o_acc, _, o_y = orc.gemm_pergroup(a_q, s_a, w_nat, s_g, s_w.view(np.uint16))
+    d_w = qqq.qqq_pack_w4(torch.from_numpy(w_nat.view(np.int32)).cuda(), K)
+    d_sg, d_sw = torch.from_numpy(s_g).cuda(), torch.from_numpy(s_w).cuda()
+    d_aq, d_sa = torch.from_numpy(a_q).cuda(), torch.from_numpy(s_a).cuda()
+    families = [0] + ([1] if M <= 64 else []) + ([2] if M > 16 else [])
+    try:
+        for fam in families:
+            qqq.set_kernel_override(fam)
+            acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
+            y = qqq.qqq_gemm_w4a8_pergroup(d_aq, d_sa, d_w, d_sg, d_sw, qqq.new_workspace(M, N, K),
+                                           sg_max=18 | qqq.SG_SYMMETRIC_CODES, acc_out=acc)
+            assert "mode=2" not in qqq.last_route(), qqq.last_route()
+            assert np.array_equal(acc.cpu().numpy(), o_acc), (fam, qqq.last_route())
+            assert ulp_distance(f16_bits(y), o_y).max() <= 1
+    finally:
+        qqq.set_kernel_override(0)
