@@ -18,9 +18,9 @@ Cold-HBM protocol: packed weights (and group scales) exist in R copies whose tot
 timed replay a 512 MiB buffer is streamed through the chip (reads only), so a replay shorter than
 one rotation starts cold too.
 The K timed steps are captured once into a HIP graph (removes Python's launch overhead from
-microsecond-scale kernels; --eager disables that) and the graph is replayed REPLAYS times, each
-replay timed with events on the launch stream: ms_per_step is the median replay / K, min and max
-are reported beside it.  Prints ONE JSON line.
+microsecond-scale kernels; --eager disables that), replayed untimed for about 30 ms so that the
+clocks have left their idle state, and then replayed REPLAYS times, each replay timed with events on
+the launch stream: ms_per_step is the median replay / K, min and max are reported beside it.  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -48,6 +48,7 @@ SWEEP = ["cfg1_pc_m16_k4096_n4096", "cfg2_pg_m1_k4096_n11008",
          "cfg5_pc_m4096_k8192_n28672", "cfg5_pg_m4096_k8192_n28672"]
 REPLAYS = 5                    # timed replays of the captured graph (min / median / max reported)
 FLUSH_BYTES = 512 << 20        # read before every timed replay: twice the last-level cache
+WARM_MS = 30.0                 # untimed graph replays before the timed ones (clock ramp-up)
 ORACLE_FULL_MACS = 2e11        # the oracle runs the whole product up to this size, a row subset beyond
 
 
@@ -156,7 +157,17 @@ def timed(torch, fn, steps, warmup, use_graph, replays=REPLAYS):
             with torch.cuda.graph(graph):
                 for i in range(steps):
                     fn(warmup + i)
-            graph.replay()           # one untimed replay: graph upload
+            w0 = torch.cuda.Event(enable_timing=True)
+            w1 = torch.cuda.Event(enable_timing=True)
+            w0.record()
+            graph.replay()           # untimed replay: graph upload
+            w1.record()
+            torch.cuda.synchronize()
+            # more untimed replays until the chip has been busy for ~WARM_MS: after the host-side
+            # set-up of a workload the clocks sit at idle, and the first milliseconds of work run slower
+            more = int(min(200, WARM_MS / max(w0.elapsed_time(w1), 1e-3)))
+            for _ in range(more):
+                graph.replay()
             torch.cuda.synchronize()
         except Exception as ex:      # capture unsupported: fall back to eager launches
             print("bench: graph capture failed (%s); timing eager launches" % ex, file=sys.stderr)

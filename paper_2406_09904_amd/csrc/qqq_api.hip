@@ -72,27 +72,64 @@ static size_t split_bytes(int64_t M, int64_t N) {
   return (M > kDecodeAlwaysMaxM && M <= kSplitMaxM) ? align256((size_t)kSplitRows * (size_t)N * 4) : 0;
 }
 
-// Tile shape and K split of the per-tile prefill kernel from a cost model measured on MI355X
-// (microseconds per k-step of one workgroup, alone on its CU / with the chip saturated): few rows
-// want many small tiles, many rows the large tile with the most reuse; when even the small tiles
-// leave CUs idle and K is long, splitting K over several workgroups per tile pays for the second
-// kernel that sums the raw tiles (a launch plus writing and reading k_splits * M * N int32 at
-// ~3 TB/s).  Shape 0 with one split means "the large tile": the caller then picks between the
+// ---------------------------------------------------------------------------------------------
+// Dispatch model: every fitted constant the automatic kernel choice uses, in one place.  All were
+// measured on one MI355X with the kernels of this library on the benchmark's layer shapes
+// (K x N = 4096 x 4096, 4096 x 11008, 5120 x 13824, 11008 x 4096, 8192 x 28672, 21760 x 8192),
+// timing GEMM launches back to back from a HIP graph with the weights rotated through > 1 GiB:
+//   tile[]        K swept at fixed M, N for each forced tile shape; the slope is the cost of one
+//                 k-step (128 k) of one workgroup in microseconds, measured once with at most one
+//                 workgroup per CU ("alone") and once with several times more tiles than CUs,
+//                 divided by the tiles per CU ("saturated"); the intercept (~4 k-steps) is the
+//                 ring fill plus the epilogue of a tile.
+//   stream_tbs    what the weight stream of a launch reaches at best (plain-read probe, 35-117 MiB).
+//   launch_us     one more kernel in the stream (empty-kernel spacing).
+//   reduce_tbs    the K-split reduce kernel's traffic rate (splits * M * N int32 written and read).
+//   margins       how much cheaper (modelled) an alternative must be before the large tile or the
+//                 unsplit launch is given up: set so that on a 72-case grid no pick lost more than
+//                 13 % against the best forced choice.
+//   decode_*      time of the decode kernel for 17..64 rows: decode_base_us + c(M) * N*K/1e6 with
+//                 c linear in M per channel-group width (fit over M = 17..64 on the six layers).
+//   pergroup_*    the per-group prefill conversion relative to per-channel (per k-step factor)
+//                 and its pre-pass launch.
+// A test times the automatic pick against every forced pick on a small grid (15 % bar).
+struct TileCost { int shape, bm, bn; bool one_per_cu; double alone_us, saturated_us; };
+static const struct DispatchModel {
+  TileCost tile[4] = {{0, 128, 512, true, 1.34, 1.50}, {3, 128, 256, true, 0.88, 0.90},
+                      {4, 128, 128, false, 0.63, 0.52}, {5, 64, 128, false, 0.45, 0.275}};
+  double tile_fixed_ksteps = 4.0;
+  double stream_tbs = 5.0;
+  double launch_us = 2.4;
+  double reduce_tbs = 3.0;
+  double margin_split = 0.88, margin_leave_large_tile = 0.95;
+  int min_ksteps_per_split = 4;
+  double decode_base_us = 5.0;
+  double decode_c64_lo[2] = {0.038, 0.0015}, decode_c64_hi[2] = {0.045, 0.0017};  // 64-channel groups: M <= 32, M > 32
+  double decode_c32_lo[2] = {0.04, 0.0031}, decode_c32_hi[2] = {0.12, 0.0023};    // 32-channel groups
+  double decode_few_groups = 1.25;           // fewer channel groups than CUs
+  double prefill_wins_by = 0.92;             // the prefill path must be this much cheaper at 17..64 rows
+  double pergroup_kstep_factor = 1.3, pergroup_prepass_us = 7.5, perchannel_extra_us = 2.5;
+} kModel;
+
+// Tile shape and K split of the per-tile prefill kernel from the model: few rows want many small
+// tiles, many rows the large tile with the most reuse; when even the small tiles leave CUs idle and
+// K is long, splitting K over several workgroups per tile pays for the second kernel that sums the
+// raw tiles.  Shape 0 with one split means "the large tile": the caller then picks between the
 // persistent kernel and the per-tile one.
 struct PrefillPlan {
   int shape, k_splits;
   double us;  // modelled time of the per-channel GEMM
 };
+static double reduce_cost_us(int k_splits, int64_t M, int64_t N) {
+  return kModel.launch_us + 8e-6 * (double)k_splits * (double)M * (double)N / kModel.reduce_tbs;
+}
 static PrefillPlan plan_prefill(int64_t M, int64_t N, int64_t K, bool can_split, int forced_split) {
   const int cus = num_cus();
   const int T = (int)(K / 128);
-  struct Cand { int shape, bm, bn; bool one_per_cu; double alone, saturated; };
-  const Cand cands[4] = {{0, 128, 512, true, 1.34, 1.50}, {3, 128, 256, true, 0.88, 0.90},
-                         {4, 128, 128, false, 0.63, 0.52}, {5, 64, 128, false, 0.45, 0.275}};
   const int splits[8] = {1, 2, 3, 4, 6, 8, 12, 16};
   PrefillPlan best = {0, 1, 0.0};
   for (int i = 0; i < 4; ++i) {
-    const Cand& c = cands[i];
+    const TileCost& c = kModel.tile[i];
     const int64_t tiles_c = ((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
     for (int j = 0; j < 8; ++j) {
       int ks = splits[j];
@@ -101,23 +138,22 @@ static PrefillPlan plan_prefill(int64_t M, int64_t N, int64_t K, bool can_split,
         if (ks > kSplitRows / M) ks = (int)(kSplitRows / M);
         if (ks > T) ks = T;
         if (ks < 1 || !can_split) ks = 1;
-      } else if (ks > 1 && (!can_split || ks * M > kSplitRows || T / ks < 4)) {
+      } else if (ks > 1 && (!can_split || ks * M > kSplitRows || T / ks < kModel.min_ksteps_per_split)) {
         continue;
       }
       const int64_t wgs = tiles_c * ks;
-      double per_step = c.alone;
+      double per_step = c.alone_us;
       if (wgs > cus)  // whole rounds where only one workgroup fits a CU, a smooth load otherwise
-        per_step = c.saturated * (c.one_per_cu ? (double)((wgs + cus - 1) / cus) : (double)wgs / cus);
-      // each workgroup pays about four k-steps' worth of ring fill and epilogue; the weights
-      // cannot arrive faster than ~5 TB/s however many workgroups pull
-      double cost = per_step * ((double)T / ks + 4.0);
-      const double stream_us = (double)N * (double)K * 0.5 / 5e6;
+        per_step = c.saturated_us * (c.one_per_cu ? (double)((wgs + cus - 1) / cus) : (double)wgs / cus);
+      double cost = per_step * ((double)T / ks + kModel.tile_fixed_ksteps);
+      const double stream_us = (double)N * (double)K * 0.5 / (kModel.stream_tbs * 1e6);
       if (cost < stream_us) cost = stream_us;
-      if (ks > 1) cost += 2.4 + 8e-6 * (double)ks * (double)M * (double)N / 3.0;
+      if (ks > 1) cost += reduce_cost_us(ks, M, N);
       // leaving the large tile has to pay, and so has a split (its model is the coarser one)
       const bool first = (i == 0 && j == 0);
-      const double margin =
-          ks > 1 && best.k_splits == 1 ? 0.88 : (best.shape == 0 && best.k_splits == 1 ? 0.95 : 1.0);
+      const double margin = ks > 1 && best.k_splits == 1
+                                ? kModel.margin_split
+                                : (best.shape == 0 && best.k_splits == 1 ? kModel.margin_leave_large_tile : 1.0);
       if (first || cost < best.us * margin) best = {c.shape, ks, cost};
       if (forced_split > 0) break;
     }
@@ -127,10 +163,8 @@ static PrefillPlan plan_prefill(int64_t M, int64_t N, int64_t K, bool can_split,
 
 // Kernel family of a call: 1 = decode (split-K) kernel, 2 = prefill kernels.  Up to 16 rows the
 // decode kernel streams the weights at memory speed; beyond 64 it does not apply.  In between it
-// re-reads the activations once per 32 channels and its time grows with M (fitted on MI355X:
-// 5 us + c(M) * N*K / 1e6, with c from the number of row tiles and the channel-group width), while
-// the prefill path's 64-row tiles do not care about M: the models decide.  The per-group prefill
-// conversion costs ~1.3x per k-step and its pre-pass another launch.
+// re-reads the activations once per 32 or 64 channels and its time grows with M, while the prefill
+// path's 64-row tiles do not care about M: the models decide.
 static int kernel_family(int64_t M, int64_t N, int64_t K, bool pergroup) {
   if (g_override != 0) return g_override;
   if (M <= kDecodeAlwaysMaxM) return 1;
@@ -138,17 +172,20 @@ static int kernel_family(int64_t M, int64_t N, int64_t K, bool pergroup) {
   const double nk = (double)N * (double)K * 1e-6;
   double c;
   if (N % 64 == 0 && (N / 64) * 3 >= 2 * num_cus()) {  // 64-channel groups (the launcher's own rule)
-    c = M <= 32 ? 0.038 + 0.0015 * (double)M : 0.045 + 0.0017 * (double)M;
+    const double* f = M <= 32 ? kModel.decode_c64_lo : kModel.decode_c64_hi;
+    c = f[0] + f[1] * (double)M;
   } else {                                               // 32-channel groups
-    c = M <= 32 ? 0.04 + 0.0031 * (double)M : 0.12 + 0.0023 * (double)M;
-    if (N / 32 < num_cus()) c *= 1.25;                   // fewer channel groups than CUs
+    const double* f = M <= 32 ? kModel.decode_c32_lo : kModel.decode_c32_hi;
+    c = f[0] + f[1] * (double)M;
+    if (N / 32 < num_cus()) c *= kModel.decode_few_groups;
   }
-  const double decode_us = 5.0 + c * nk;
+  const double decode_us = kModel.decode_base_us + c * nk;
   const PrefillPlan plan = plan_prefill(M, N, K, true, g_prefill_ksplit);
-  const double reduce_us = plan.k_splits > 1 ? 2.4 + 8e-6 * plan.k_splits * (double)M * (double)N / 3.0 : 0.0;
-  const double prefill_us =
-      pergroup ? (plan.us - reduce_us) * 1.3 + reduce_us + 7.5 : plan.us + 2.5;
-  return prefill_us < 0.92 * decode_us ? 2 : 1;
+  const double reduce_us = plan.k_splits > 1 ? reduce_cost_us(plan.k_splits, M, N) : 0.0;
+  const double prefill_us = pergroup ? (plan.us - reduce_us) * kModel.pergroup_kstep_factor + reduce_us +
+                                           kModel.pergroup_prepass_us
+                                     : plan.us + kModel.perchannel_extra_us;
+  return prefill_us < kModel.prefill_wins_by * decode_us ? 2 : 1;
 }
 
 // per-group conversion route from the caller's promises about the group scales (and the codes)
