@@ -753,8 +753,10 @@ def main():
                 continue
             w2 = wls[name]
             c2 = Case(w2, torch, qqq)
-            # graph length: a whole rotation of the weight copies for the short kernels
-            st = max(5, min(args.steps, 20)) if w2.M >= 256 else max(args.steps, min(c2.copies, 128))
+            # graph length: for the short kernels a whole rotation of the weight copies and at least
+            # 100 steps, so that what a replay pays once after the cache flush (address translation,
+            # the first wave of workgroups) is spread over enough steps to read as per-step time
+            st = max(5, min(args.steps, 20)) if w2.M >= 256 else max(args.steps, min(c2.copies, 128), 100)
             sweep.append(workload_line(c2, torch, st, min(args.warmup, 5), use_graph))
             print("bench %s: %.2f us/step, roofline %.3f (%s)" % (
                 name, sweep[-1]["ms_per_step"] * 1e3, sweep[-1]["roofline"]["frac"],
