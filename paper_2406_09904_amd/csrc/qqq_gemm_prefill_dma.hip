@@ -71,24 +71,28 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
   // rows); lane l lands in slot l%8 of row l/8, so it fetches chunk (l%8) ^ ((row/2)%8).  Rows past M
   // re-read row M-1 (never stored).  Weights: this wave's 1 KiB chunks, copied verbatim; chunks
   // past N/16 re-read the last valid chunk (never stored).
-  const int8_t* a_src[S::kAPieces];
+  // Addresses are a wave-uniform 64-bit base in scalar registers plus a 32-bit per-lane offset: the
+  // per-k-step advance is then scalar arithmetic, not 64-bit vector adds on every lane.
+  const uint32_t wave_u = (uint32_t)__builtin_amdgcn_readfirstlane(wave);
+  uint32_t a_voff[S::kAPieces];
 #pragma unroll
   for (int i = 0; i < S::kAPieces; ++i) {
     const int r = 8 * (S::kAPieces * wave + i) + (lane >> 3);
     int m = m0 + r;
     if (m > M - 1) m = M - 1;
-    a_src[i] = p.a_q + (int64_t)m * K + (int64_t)t_first * S::kBK + (((lane & 7) ^ ((r >> 1) & 7)) << 4);
+    a_voff[i] = (uint32_t)(m - m0) * (uint32_t)K + (uint32_t)(((lane & 7) ^ ((r >> 1) & 7)) << 4);
   }
-  const int8_t* w_src[S::kWChunks];
+  const int8_t* a_base = p.a_q + (int64_t)m0 * K + (int64_t)t_first * S::kBK;
+  const int64_t w_step = (int64_t)ntiles * 1024;  // bytes between k-steps of the packed weights
+  const int8_t* w_base[S::kWChunks];
+  const int nt0 = (tn * S::kBN + (int)wave_u * 32 * CT) >> 4;
 #pragma unroll
   for (int j = 0; j < S::kWChunks; ++j) {
-    int nt = (n_wave >> 4) + j;
+    int nt = nt0 + j;
     if (nt > ntiles - 1) nt = ntiles - 1;
-    w_src[j] = (const int8_t*)p.w + (int64_t)nt * 1024 + lane * 16;
+    w_base[j] = (const int8_t*)p.w + (int64_t)nt * 1024 + (int64_t)t_first * w_step;
   }
-  const int64_t w_step = (int64_t)ntiles * 1024;  // bytes between k-steps of the packed weights
-#pragma unroll
-  for (int j = 0; j < S::kWChunks; ++j) w_src[j] += (int64_t)t_first * w_step;
+  const uint32_t w_voff = (uint32_t)lane * 16u;
   // group scales of the wave's 32*CT channels: the first 8*CT lanes fetch 4 bytes each, the other
   // lanes (and channels past N) re-read a valid dword; each lane writes its own LDS dword
   // (fp16 scales of the real-valued variant: the first 16*CT lanes fetch two scales each)
@@ -106,23 +110,22 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
   // read of each k-step); the waits are placed by hand below.  M0 carries the wave-uniform LDS
   // destination; lane l writes its 16 (or 4) bytes at M0 + 16*l (4*l).
   const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_ptr_t)lds;
-  auto dma16 = [&](const int8_t* src, uint32_t dst) {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src)
+  auto dma16s = [&](const int8_t* base, uint32_t voff, uint32_t dst) {  // scalar base + lane offset
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(voff), "s"(base)
                  : "memory", "m0");
   };
   auto dma4 = [&](const int8_t* src, uint32_t dst) {
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(dst), "v"(src)
                  : "memory", "m0");
   };
-  const uint32_t wave_u = (uint32_t)__builtin_amdgcn_readfirstlane(wave);
   auto issue_dma = [&](int t, int stage) {
     const uint32_t base = lds_base + (uint32_t)stage * S::kStage;
+    const int8_t* ab = a_base + (int64_t)t * S::kBK;
 #pragma unroll
-    for (int i = 0; i < S::kAPieces; ++i)
-      dma16(a_src[i] + (int64_t)t * S::kBK, base + (S::kAPieces * wave_u + i) * 1024);
+    for (int i = 0; i < S::kAPieces; ++i) dma16s(ab, a_voff[i], base + (S::kAPieces * wave_u + i) * 1024);
 #pragma unroll
     for (int j = 0; j < S::kWChunks; ++j)
-      dma16(w_src[j] + (int64_t)t * w_step, base + S::kAStage + wave_u * S::kWWave + j * 1024);
+      dma16s(w_base[j] + (int64_t)t * w_step, w_voff, base + S::kAStage + wave_u * S::kWWave + j * 1024);
     if constexpr (MODE != kPerChannel)
       dma4(sg_src + (int64_t)t * N * kSgBytes, base + S::kAStage + S::kWStage + wave_u * 256);
   };

@@ -74,8 +74,12 @@ __global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmPar
   // which is also when the tile's token scales and channel scales are fetched, once, into a small
   // side buffer indexed by the tile's parity.
   int d_iter = 0, d_t = 0;
-  const int8_t* pa[2];
-  const int8_t* pw[4];
+  // (activations and weights: a wave-uniform 64-bit base in scalar registers plus a 32-bit lane
+  // offset, so the per-k-step advance is scalar arithmetic)
+  const int8_t* a_base = nullptr;
+  uint32_t a_voff[2] = {0, 0};
+  const int8_t* w_base[4] = {nullptr, nullptr, nullptr, nullptr};
+  const uint32_t w_voff = (uint32_t)lane * 16u;
   const int8_t* psg = nullptr;
   // slot swizzle: 16-byte chunk c of tile row r sits in slot c ^ ((r >> 1) & 7) of its 128-byte LDS row
   // (r = 16*wave + 8*i + lane/8 here, so (r >> 1) & 7 = (4*i + lane/16) & 7)
@@ -89,29 +93,38 @@ __global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmPar
   const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_ptr_t)lds;
   const uint32_t side_base = (uint32_t)(uintptr_t)(lds_ptr_t)side;
   const uint32_t wave_u = (uint32_t)__builtin_amdgcn_readfirstlane(wave);
-  auto dma16 = [&](const int8_t* src, uint32_t dst) {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src)
+  auto dma16s = [&](const int8_t* base, uint32_t voff, uint32_t dst) {  // scalar base + lane offset
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(voff), "s"(base)
                  : "memory", "m0");
   };
   auto dma4 = [&](const int8_t* src, uint32_t dst) {
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(dst), "v"(src)
                  : "memory", "m0");
   };
+  // (the tile order's integer divisions run on the vector unit; this brings a wave-uniform address
+  // back to scalar registers, where the per-k-step advance then stays)
+  auto to_scalar = [](const int8_t* ptr) {
+    const uint64_t v = (uint64_t)(uintptr_t)ptr;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return (const int8_t*)(uintptr_t)(((uint64_t)hi << 32) | lo);
+  };
   // enters tile `iter`: rebuilds the pointers and fetches the tile's scales (two more DMA loads)
   auto enter_dma_tile = [&](int iter) {
     int tm, tn;
     tile_coords(iter, tm, tn);
+    a_base = to_scalar(p.a_q + (int64_t)tm * kBM * K);
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       int m = tm * kBM + 16 * wave + 8 * i + (lane >> 3);
       if (m > M - 1) m = M - 1;
-      pa[i] = p.a_q + (int64_t)m * K + swz[i];
+      a_voff[i] = (uint32_t)(m - tm * kBM) * (uint32_t)K + (uint32_t)swz[i];
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      int nt = tn * (kBN / 16) + wave * 4 + j;
+      int nt = tn * (kBN / 16) + (int)wave_u * 4 + j;
       if (nt > ntiles - 1) nt = ntiles - 1;
-      pw[j] = (const int8_t*)p.w + (int64_t)nt * 1024 + lane * 16;
+      w_base[j] = to_scalar((const int8_t*)p.w + (int64_t)nt * 1024);
     }
     const int c0 = tn * kBN + wave * 64;
     if constexpr (MODE != kPerChannel) {
@@ -133,8 +146,8 @@ __global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmPar
   // a wave that waits there issues no MFMA either.
   auto issue_dma_piece = [&](int stage, int piece) {
     const uint32_t base = lds_base + (uint32_t)stage * kStage;
-    if (piece < 2) dma16(pa[piece], base + (2 * wave_u + piece) * 1024);
-    else if (piece < 6) dma16(pw[piece - 2], base + kAStage + wave_u * kWWave + (piece - 2) * 1024);
+    if (piece < 2) dma16s(a_base, a_voff[piece], base + (2 * wave_u + piece) * 1024);
+    else if (piece < 6) dma16s(w_base[piece - 2], w_voff, base + kAStage + wave_u * kWWave + (piece - 2) * 1024);
     else if constexpr (MODE != kPerChannel) dma4(psg, base + kSmall + wave_u * 256);
   };
   // advances the cursor after a k-step's pieces are out; returns true when the step was the last of
@@ -144,10 +157,9 @@ __global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmPar
   auto advance_cursor = [&]() {
     ++d_t;
     if (d_t < T) {
+      a_base += kBK;
 #pragma unroll
-      for (int i = 0; i < 2; ++i) pa[i] += kBK;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) pw[j] += w_step;
+      for (int j = 0; j < 4; ++j) w_base[j] += w_step;
       if constexpr (MODE != kPerChannel) psg += N;
       return false;
     }
