@@ -296,18 +296,24 @@ def workload_line(case, torch, steps, warmup, use_graph):
 
 
 def sample_clock(torch, case):
-    """Shader clock reported by rocm-smi while the workload's GEMM runs back to back for about two
-    seconds, and once more when idle.  None where the tool is missing or unreadable."""
+    """Shader clock (rocm-smi) and socket power (amd-smi) while the workload's GEMM runs back to back
+    for a few seconds, and once more when idle, plus the board's power limit.  None where the tools
+    are missing or unreadable.  The int8 MFMA kernels run this GPU at its power limit, which is what
+    sets their clock."""
     import re
     import subprocess
 
-    def read():
+    def tool(args, pattern):
         try:
-            r = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=20)
-            m = re.search(r"sclk clock level:\s*\d+:\s*\((\d+)Mhz\)", r.stdout)
-            return int(m.group(1)) if m else None
+            r = subprocess.run(args, capture_output=True, text=True, timeout=20)
+            m = re.search(pattern, r.stdout)
+            return float(m.group(1)) if m else None
         except (OSError, subprocess.SubprocessError):
             return None
+
+    def read():
+        return (tool(["rocm-smi", "--showclocks"], r"sclk clock level:\s*\d+:\s*\((\d+)Mhz\)"),
+                tool(["amd-smi", "metric", "--power"], r"SOCKET_POWER:\s*([0-9.]+)\s*W"))
 
     try:
         graph = torch.cuda.CUDAGraph()
@@ -319,18 +325,22 @@ def sample_clock(torch, case):
         graph.replay()
         e1.record()
         torch.cuda.synchronize()
-        reps = int(max(1, min(100000, 2500.0 / max(e0.elapsed_time(e1), 1e-3))))
-        for _ in range(reps):                       # ~2.5 s of queued work; the host does not wait
+        reps = int(max(1, min(200000, 5000.0 / max(e0.elapsed_time(e1), 1e-3))))
+        for _ in range(reps):                       # ~5 s of queued work; the host does not wait
             graph.replay()
-        time.sleep(0.6)
+        time.sleep(1.2)
         busy = read()
         torch.cuda.synchronize()
     except Exception as ex:                         # noqa: BLE001 - a diagnostic, never fatal
         print("bench: clock sampling failed (%s)" % ex, file=sys.stderr)
         return None
     time.sleep(0.5)
-    return {"sclk_mhz_during_gemm": busy, "sclk_mhz_idle": read(), "nominal_mhz": 2400,
-            "source": "rocm-smi --showclocks, one reading while %s's GEMM is replayed back to back" % case.wl.name}
+    idle = read()
+    cap = tool(["rocm-smi", "--showmaxpower"], r"Max Graphics Package Power \(W\):\s*([0-9.]+)")
+    return {"sclk_mhz_during_gemm": busy[0], "sclk_mhz_idle": idle[0], "nominal_mhz": 2400,
+            "socket_power_w_during_gemm": busy[1], "socket_power_w_idle": idle[1], "power_limit_w": cap,
+            "source": "rocm-smi --showclocks / amd-smi metric --power, one reading while %s's GEMM is replayed "
+                      "back to back" % case.wl.name}
 
 
 def real_scale_lines(wls, torch, qqq, args, use_graph):
@@ -661,6 +671,38 @@ def ceilings(torch, qqq, synth):
         rows.append({"activations": an, "weights": bn, "ms": round(ms, 3), "tops": round(ops / ms / 1e9, 1),
                      "frac_of_nominal": round(ops / ms / 1e9 / MFMA_I8_PEAK_TOPS, 4)})
     out["mfma_i8_only"] = rows
+    # the prefill kernel's k-loop, part by part, on the headline workload's own bytes: activation
+    # tiles (128 rows x 128 k) cut from its quantised activations, packed codes as they lie in memory
+    w_packed = qqq.qqq_pack_w4(torch.from_numpy(wl.w_nat().view(np.int32)).cuda(), wl.K)
+    a_all, _ = qqq.qqq_quant_act(torch.from_numpy(wl.activations()[:512]).cuda())
+    wgs, stages = 256, 2
+    a_tiles = a_all.view(4, 128, wl.K // 128, 128).permute(0, 2, 1, 3).reshape(-1, 16384)
+    reps = (wgs * stages + a_tiles.shape[0] - 1) // a_tiles.shape[0]
+    a_tiles = a_tiles.repeat(reps, 1)[:wgs * stages].contiguous().view(torch.uint8)
+    w_bytes = w_packed.view(torch.uint8).reshape(-1)[:wgs * stages * 32768].view(wgs * stages, 32768)
+    src = torch.zeros((wgs * stages, qqq.PROBE_LOOP_STAGE), dtype=torch.uint8, device="cuda")
+    src[:, :16384] = a_tiles
+    src[:, 16384:49152] = w_bytes
+    region = stages * qqq.PROBE_LOOP_STAGE
+    A, W, C, D = qqq.PROBE_A_READS, qqq.PROBE_W_READS, qqq.PROBE_CONVERT, qqq.PROBE_DMA
+    rows = []
+    steps = 3000
+    for parts, name in ((0, "MFMAs only: operands stay in registers, conversion hoisted"),
+                        (C, "+ int4 -> int8 conversion every k-step"),
+                        (A, "+ activation fragments from LDS"),
+                        (W | C, "+ packed codes from LDS and their conversion"),
+                        (D, "+ DMA ring refill, wait and barrier"),
+                        (A | W | C, "all LDS reads and the conversion"),
+                        (A | W | C | D, "the whole k-loop")):
+        ms = min(timed_ms(torch, lambda i, parts=parts: qqq.probe_prefill_loop(src, region, steps, parts, wgs, sink),
+                          1, 1, False) for _ in range(3))
+        ops = wgs * 8 * steps * 32 * 65536.0
+        rows.append({"parts": name, "ms": round(ms, 3),
+                     "frac_of_nominal": round(ops / ms / 1e9 / MFMA_I8_PEAK_TOPS, 4)})
+    base = 1.0 / rows[0]["frac_of_nominal"]
+    for r in rows:
+        r["time_per_mfma_vs_first_row"] = round(1.0 / r["frac_of_nominal"] / base, 3)
+    out["prefill_loop_parts"] = rows
     return out
 
 

@@ -26,7 +26,7 @@ SYMBOLS = [
     "qqq_set_group_mode_override", "qqq_set_skinny_tuning", "qqq_set_prefill_tuning",
     "qqq_quantize_w4_perchannel", "qqq_quantize_w4_pergroup", "qqq_set_prefill_ksplit",
     "qqq_gemm_workspace_zero_bytes", "qqq_linear_w4a8_perchannel_static", "qqq_last_route",
-    "qqq_debug_count_sg_violations", "qqq_probe_stream_read", "qqq_probe_mfma_i8",
+    "qqq_debug_count_sg_violations", "qqq_probe_stream_read", "qqq_probe_mfma_i8", "qqq_probe_prefill_loop",
     "qqq_smoothing_workspace_bytes", "qqq_adaptive_smoothing", "qqq_channel_absmax", "qqq_smooth_apply",
     "qqq_fp16_gemm_nt", "qqq_hessian", "qqq_gptq_workspace_bytes", "qqq_gptq_quantize_w4_perchannel",
 ]
@@ -66,6 +66,7 @@ def lib():
         L.qqq_gptq_quantize_w4_perchannel.argtypes = [vp, vp, i64, i64, ctypes.c_double, vp, vp, vp, sz, vp]
         L.qqq_probe_stream_read.argtypes = [vp, sz, ci, vp, vp]
         L.qqq_probe_mfma_i8.argtypes = [vp, vp, ci, ci, vp, vp]
+        L.qqq_probe_prefill_loop.argtypes = [vp, sz, ci, ci, ci, vp, vp]
         L.qqq_quant_act.argtypes = [vp, i64, i64, i64, vp, vp, vp]
         L.qqq_packed_w4_bytes.argtypes = [i64, i64]
         L.qqq_packed_w4_bytes.restype = sz
@@ -411,6 +412,19 @@ def probe_mfma_i8(a_pool: torch.Tensor, b_pool: torch.Tensor, iters: int, workgr
         raise ValueError("operand pools must hold 4*4*512 and 2*2*512 16-byte values")
     _check(lib().qqq_probe_mfma_i8(_ptr(a_pool, torch.int8), _ptr(b_pool, torch.int8), iters, workgroups,
                                    _ptr(sink, torch.int32), _stream()))
+
+
+PROBE_A_READS, PROBE_W_READS, PROBE_CONVERT, PROBE_DMA = 1, 2, 4, 8
+PROBE_LOOP_STAGE = 51200
+
+
+def probe_prefill_loop(src: torch.Tensor, region_bytes: int, steps: int, parts: int, workgroups: int,
+                       sink: torch.Tensor):
+    """One launch of the prefill k-loop probe: src is a uint8 tensor of workgroups * region_bytes bytes."""
+    if src.numel() < workgroups * region_bytes:
+        raise ValueError("src must hold workgroups * region_bytes bytes")
+    _check(lib().qqq_probe_prefill_loop(_ptr(src, torch.uint8), region_bytes, steps, parts, workgroups,
+                                        _ptr(sink, torch.int32), _stream()))
 
 
 def set_fused_quant(enable: int) -> int:
