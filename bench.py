@@ -702,6 +702,14 @@ def ceilings(torch, qqq, synth):
     base = 1.0 / rows[0]["frac_of_nominal"]
     for r in rows:
         r["time_per_mfma_vs_first_row"] = round(1.0 / r["frac_of_nominal"] / base, 3)
+    # the same loop on constant bytes draws little power: the clock stays near nominal and the
+    # fraction is the MFMA pipe's busy share, i.e. what the loop loses as a schedule
+    src.fill_(0x12)
+    for parts, name in ((0, "constant bytes: MFMAs only"), (A | W | C | D, "constant bytes: the whole k-loop")):
+        ms = min(timed_ms(torch, lambda i, parts=parts: qqq.probe_prefill_loop(src, region, steps, parts, wgs, sink),
+                          1, 1, False) for _ in range(3))
+        rows.append({"parts": name, "ms": round(ms, 3),
+                     "frac_of_nominal": round(wgs * 8 * steps * 32 * 65536.0 / ms / 1e9 / MFMA_I8_PEAK_TOPS, 4)})
     out["prefill_loop_parts"] = rows
     return out
 

@@ -42,7 +42,6 @@ __global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmPar
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const int n32 = lane & 31, h = lane >> 5;
   const int T = p.T, N = p.N, M = p.M;
   const int64_t K = p.K;
   const int ntiles = N >> 4;
@@ -187,39 +186,38 @@ __global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmPar
       asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(kDmaPerStep) : "memory");
   };
 
-  // ---- per-lane LDS read offsets (see gemm_prefill_dma_kernel)
-  int a_off[4];
+  // ---- per-lane LDS read offsets.  v_mfma_i32_16x16x64_i8: lane l holds row (or channel) l%16 and
+  // the 16 k-values of k-block l/16, i.e. chunk 4*s + l/16 of the row in the k-sub s (64 k) of the
+  // k-step; register i of a 16x16 result tile is row 4*(l/16) + i, column l%16.  A wave's 128 x 64
+  // patch is 8 x 4 such tiles.  (The 16x16x64 form moves half the accumulator bytes per
+  // multiply-accumulate of the 32x32x32 form; at the board's power limit, where this kernel runs,
+  // that is worth 10-15 % of throughput.)
+  const int r16 = lane & 15, kb = lane >> 4;
+  int a_off[2];  // row r16 of row tile 0 (row tile mt adds 16 rows: the swizzle term does not change)
 #pragma unroll
-  for (int s = 0; s < 4; ++s) a_off[s] = n32 * 128 + (((2 * s + h) ^ ((n32 >> 1) & 7)) << 4);
-  const int w_off = kAStage + wave * kWWave + (n32 >> 4) * 1024 + ((n32 & 15) + 16 * h) * 16;
+  for (int s = 0; s < 2; ++s) a_off[s] = r16 * 128 + (((4 * s + kb) ^ ((r16 >> 1) & 7)) << 4);
+  // packed codes: lane l's 16-byte vector of each of the wave's four 16-channel chunks is exactly
+  // its operand data: dwords 0,1 = the 16 k-values of k-block l/16 in k-sub 0, dwords 2,3 in k-sub 1
+  const int w_off = kAStage + wave * kWWave + lane * 16;
   const int small_off = kSmall + wave * 256;
 
-  v16i acc[4][2];
-  uint4 wq[2][2];  // this lane's packed codes of the current k-step: [tile][piece]
-  int sg[2];       // and its group scales
+  v4i acc[8][4];
+  uint4 wq[4];  // this lane's packed codes of a k-step, one vector per channel tile
+  int sg[4];    // and its group scales
   auto read_w = [&](const int8_t* sb) {
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
-      wq[c][0] = *(const uint4*)(sb + w_off + c * 2048);
-      wq[c][1] = *(const uint4*)(sb + w_off + c * 2048 + 512);
+    for (int c = 0; c < 4; ++c) {
+      wq[c] = *(const uint4*)(sb + w_off + c * 1024);
       sg[c] = 0;
-      if constexpr (MODE != kPerChannel) sg[c] = (int)sb[small_off + c * 32 + n32];
+      if constexpr (MODE != kPerChannel) sg[c] = (int)sb[small_off + c * 16 + r16];
     }
   };
-  auto read_a = [&](v4i (&a)[4], const int8_t* sb, int s) {
-#pragma unroll
-    for (int mt = 0; mt < 4; ++mt) a[mt] = *(const v4i*)(sb + a_off[s] + mt * 4096);
+  // fragment of slot i = (k-sub i/8, row tile i%8): 4 MFMAs use it
+  auto read_a = [&](const int8_t* sb, int slot) {
+    return *(const v4i*)(sb + a_off[slot >> 3] + (slot & 7) * 2048);
   };
-  // MFMA step s uses piece s%2, dword pair s/2 of the lane's packed codes
   auto make_b = [&](int c, int s) {
-    const uint4 pc = wq[c][s & 1];
-    const uint32_t d0 = (s >> 1) ? pc.z : pc.x, d1 = (s >> 1) ? pc.w : pc.y;
-    return convert_b<MODE>(d0, d1, sg[c]);
-  };
-  auto mfma_col = [&](const v4i (&a)[4], const v4i b, int c) {
-#pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
-      acc[mt][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[mt], b, acc[mt][c], 0, 0, 0);
+    return s ? convert_b<MODE>(wq[c].z, wq[c].w, sg[c]) : convert_b<MODE>(wq[c].x, wq[c].y, sg[c]);
   };
 
   // ---- prologue: k-steps 0 and 1 of the first tile in flight, wait for step 0
@@ -227,47 +225,62 @@ __global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmPar
   issue_next_dma(0);
   wait_all_but_newest_step(issue_next_dma(1));
 
+  // The k-step is a fixed sequence of 16 slots (4 MFMAs each).  Fragments are read kAhead slots
+  // before their MFMAs into a rotating set of four registers; the closing wait and barrier of the
+  // k-step sit before the last kAhead slots, whose fragment reads (and the reads of the packed
+  // codes) already go to the next stage, so that LDS latency at the k-step border hides behind MFMAs
+  // whose operands are in registers.  The compiler's scheduler would pull these reads next to their
+  // uses; a scheduling barrier after every slot keeps the order written here.
+  constexpr int kAhead = 3;
   int stage = 0;
-  v4i a0[4], a1[4];
+  v4i abuf[4], b0[4], b1[4];
   read_w(lds);
-  read_a(a0, lds, 0);
+#pragma unroll
+  for (int i = 0; i < kAhead; ++i) abuf[i] = read_a(lds, i);
+#pragma unroll
+  for (int c = 0; c < 4; ++c) b0[c] = make_b(c, 0);
   for (int it = 0; it < my_tiles; ++it) {
     int tm, tn;
     tile_coords(it, tm, tn);
     const int m0 = tm * kBM;
     const int n_wave = tn * kBN + wave * 64;
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
+    for (int mt = 0; mt < 8; ++mt)
 #pragma unroll
-      for (int c = 0; c < 2; ++c)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[mt][c][v] = 0;
+      for (int c = 0; c < 4; ++c) acc[mt][c] = (v4i){0, 0, 0, 0};
     // Biased per-group route: the conversion adds (8*s_g - 128) to every weight, which sums to
     // sum_g Bc[n][g] * R[m][g] over a row; the pre-pass stored -R = 128*Rh + Rl, so the tile starts
     // at 128 x (Bc x Rh) + Bc x Rl (see gemm_prefill_dma_kernel).  Ordinary loads: the compiler
     // waits for them before the MFMAs below, so none is outstanding at the k-loop's counted waits.
+    // Rows of the tables are padded with zeros to a multiple of 32 groups; an MFMA takes 64, so
+    // k-blocks past the padded row feed zeros.
     if constexpr (MODE == kGroupBias) {
       const int Gp = (T + 31) & ~31;
+      const v4i zero = {0, 0, 0, 0};
 #pragma unroll
-      for (int c = 0; c < 2; ++c) {
-        int col = n_wave + c * 32 + n32;
+      for (int c = 0; c < 4; ++c) {
+        int col = n_wave + c * 16 + r16;
         if (col > N - 1) col = N - 1;
-        const int8_t* bp = p.bias_w + (int64_t)col * Gp + 16 * h;
+        const int8_t* bp = p.bias_w + (int64_t)col * Gp + 16 * kb;
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {
-          int mrow = m0 + 32 * mt + n32;
+        for (int mt = 0; mt < 8; ++mt) {
+          int mrow = m0 + 16 * mt + r16;
           if (mrow > M - 1) mrow = M - 1;
-          const int8_t* lp = p.r_lo + (int64_t)mrow * Gp + 16 * h;
-          const int8_t* hp = p.r_hi + (int64_t)mrow * Gp + 16 * h;
-          for (int j = 0; j < Gp; j += 32)
-            acc[mt][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(*(const v4i*)(hp + j), *(const v4i*)(bp + j),
-                                                               acc[mt][c], 0, 0, 0);
+          const int8_t* lp = p.r_lo + (int64_t)mrow * Gp + 16 * kb;
+          const int8_t* hp = p.r_hi + (int64_t)mrow * Gp + 16 * kb;
+          for (int j = 0; j < Gp; j += 64) {
+            const bool in = j + 16 * kb < Gp;
+            acc[mt][c] = __builtin_amdgcn_mfma_i32_16x16x64_i8(in ? *(const v4i*)(hp + j) : zero,
+                                                               in ? *(const v4i*)(bp + j) : zero, acc[mt][c], 0, 0, 0);
+          }
 #pragma unroll
-          for (int v = 0; v < 16; ++v)  // modular by design near the int32 limit: unsigned
+          for (int v = 0; v < 4; ++v)  // modular by design near the int32 limit: unsigned
             acc[mt][c][v] = (int)((uint32_t)acc[mt][c][v] << 7);
-          for (int j = 0; j < Gp; j += 32)
-            acc[mt][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(*(const v4i*)(lp + j), *(const v4i*)(bp + j),
-                                                               acc[mt][c], 0, 0, 0);
+          for (int j = 0; j < Gp; j += 64) {
+            const bool in = j + 16 * kb < Gp;
+            acc[mt][c] = __builtin_amdgcn_mfma_i32_16x16x64_i8(in ? *(const v4i*)(lp + j) : zero,
+                                                               in ? *(const v4i*)(bp + j) : zero, acc[mt][c], 0, 0, 0);
+          }
         }
       }
     }
@@ -276,65 +289,60 @@ __global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmPar
       // the cursor's k-step (two ahead, possibly already in the next tile) goes into the stage
       // that was read during the previous k-step (everyone is past the barrier inside it)
       const int dstage = stage == 0 ? 2 : stage - 1;
+      const int nstage = stage == 2 ? 0 : stage + 1;
       const int8_t* sb = lds + stage * kStage;
-      issue_dma_piece(dstage, 0);
-      read_a(a1, sb, 1);
-      mfma_col(a0, make_b(0, 0), 0);
-      issue_dma_piece(dstage, 1);
-      mfma_col(a0, make_b(1, 0), 1);
-      issue_dma_piece(dstage, 2);
-      read_a(a0, sb, 2);
-      mfma_col(a1, make_b(0, 1), 0);
-      issue_dma_piece(dstage, 3);
-      mfma_col(a1, make_b(1, 1), 1);
-      issue_dma_piece(dstage, 4);
-      read_a(a1, sb, 3);
-      mfma_col(a0, make_b(0, 2), 0);
-      issue_dma_piece(dstage, 5);
-      issue_dma_piece(dstage, 6);
-      const bool extra = advance_cursor();
-      mfma_col(a0, make_b(1, 2), 1);
-      const v4i b30 = make_b(0, 3), b31 = make_b(1, 3);
-      // my DMA of the next k-step has landed (only the loads of the one after may still be in
-      // flight), my LDS reads of this stage are done; then everyone's
-      wait_all_but_newest_step(extra);
-      stage = (stage == 2) ? 0 : stage + 1;
-      // first LDS reads of the next k-step (after a tile's last k-step: the next tile's first;
-      // after the very last: stale data, read but never used) ...
-      const int8_t* nb = lds + stage * kStage;
-      read_a(a0, nb, 0);
-      read_w(nb);
-      // ... in flight behind the last MFMA step of this k-step
-      mfma_col(a1, b30, 0);
-      mfma_col(a1, b31, 1);
+      const int8_t* nb = lds + nstage * kStage;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        if (i == 16 - kAhead) {
+          // my DMA of the next k-step has landed (only the loads of the one after may still be in
+          // flight), my LDS reads of this stage are done; then everyone's.  From here on the reads
+          // go to the next k-step's stage (after a tile's last k-step: the next tile's first;
+          // after the very last: stale data, read but never used).
+          wait_all_but_newest_step(advance_cursor());
+          read_w(nb);
+        }
+        abuf[(i + kAhead) & 3] = (i + kAhead < 16) ? read_a(sb, i + kAhead) : read_a(nb, i + kAhead - 16);
+        if (i < 7) issue_dma_piece(dstage, i);
+        if (i >= 2 && i < 6) b1[i - 2] = make_b(i - 2, 1);  // the second k-sub's operands, one per slot
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+          acc[i & 7][c] = __builtin_amdgcn_mfma_i32_16x16x64_i8(abuf[i & 3], i < 8 ? b0[c] : b1[c], acc[i & 7][c], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      // the next k-step's first operands, from the codes read after the barrier
+#pragma unroll
+      for (int c = 0; c < 4; ++c) b0[c] = make_b(c, 0);
+      stage = nstage;
     }
 
-    // ---- fused Dequant epilogue in the stage of the tile's last k-step.  Lane holds column n32
-    // of each 32-wide tile; register v of a 32x32 tile is row 8*(v/4) + 4*h + v%4.
+    // ---- fused Dequant epilogue in the stage of the tile's last k-step, 32 rows (two row tiles)
+    // per pass: lane holds rows 4*kb .. 4*kb+3 of column r16 of each 16-wide tile.
     {
       const int8_t* fsb = lds + (stage == 0 ? 2 : stage - 1) * kStage;
       int8_t* patch = const_cast<int8_t*>(fsb) + wave * kEpWave;
       const int8_t* sd = side + (it & 1) * kSide;  // this tile's scales: [wave][256 B s_a, 256 B s_w]
-      float swv[2];
+      float swv[4];
 #pragma unroll
-      for (int c = 0; c < 2; ++c)
-        swv[c] = (float)*(const _Float16*)(sd + wave * 512 + 256 + (c * 32 + n32) * 2);
+      for (int c = 0; c < 4; ++c)
+        swv[c] = (float)*(const _Float16*)(sd + wave * 512 + 256 + (c * 16 + r16) * 2);
       const int cc = lane & 7;
       const int ncol = n_wave + cc * 8;
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt) {
+      for (int pass = 0; pass < 4; ++pass) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int r0 = mt * 32 + 8 * q + 4 * h;  // token scales of rows r0..r0+3: wave r0/16's slot
-          const float4 sa4 = *(const float4*)(sd + (r0 >> 4) * 512 + (r0 & 15) * 4);
+        for (int half = 0; half < 2; ++half) {
+          const int mt = 2 * pass + half;
+          // token scales of rows 16*mt + 4*kb .. +3: wave mt's slot of the side buffer
+          const float4 sa4 = *(const float4*)(sd + mt * 512 + kb * 16);
           const float sav[4] = {sa4.x, sa4.y, sa4.z, sa4.w};
 #pragma unroll
-          for (int c = 0; c < 2; ++c) {
+          for (int c = 0; c < 4; ++c) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-              int x = acc[mt][c][4 * q + j];
+              int x = acc[mt][c][j];
               if constexpr (MODE == kPerChannel) x >>= 4;  // exact: the sum is a multiple of 16
-              *(_Float16*)(patch + (8 * q + 4 * h + j) * kEpRow + (c * 32 + n32) * 2) =
+              *(_Float16*)(patch + (16 * half + 4 * kb + j) * kEpRow + (c * 16 + r16) * 2) =
                   dequant(x, sav[j], swv[c]);
             }
           }
@@ -344,20 +352,20 @@ __global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmPar
         for (int i4 = 0; i4 < 4; ++i4) {
           const int row = i4 * 8 + (lane >> 3);
           const v4i d = *(const v4i*)(patch + row * kEpRow + cc * 16);
-          const int m = m0 + mt * 32 + row;
+          const int m = m0 + pass * 32 + row;
           if (m < M && ncol < N) *(v4i*)(p.y + (int64_t)m * N + ncol) = d;
         }
       }
       if (p.acc_out) {  // parity/debug output of the true accumulators: plain stores
 #pragma unroll
-        for (int c = 0; c < 2; ++c) {
-          const int col = n_wave + c * 32 + n32;
+        for (int c = 0; c < 4; ++c) {
+          const int col = n_wave + c * 16 + r16;
           if (col >= N) continue;
 #pragma unroll
-          for (int mt = 0; mt < 4; ++mt) {
+          for (int mt = 0; mt < 8; ++mt) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-              const int m = m0 + mt * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+            for (int v = 0; v < 4; ++v) {
+              const int m = m0 + mt * 16 + 4 * kb + v;
               if (m < M) {
                 int x = acc[mt][c][v];
                 if constexpr (MODE == kPerChannel) x >>= 4;

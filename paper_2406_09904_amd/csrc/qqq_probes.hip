@@ -137,7 +137,7 @@ __global__ __launch_bounds__(512, 1) void probe_prefill_loop_kernel(int steps, c
   auto make_b = [&](int c, int s) {
     uint4 pc = wq[c][s & 1];
     // without this the conversion of loop-invariant codes is hoisted out of the loop
-    if constexpr (kConvert) asm volatile("" : "+v"(pc.x), "+v"(pc.y), "+v"(pc.z), "+v"(pc.w));
+    if constexpr (kConvert && !kWReads) asm volatile("" : "+v"(pc.x), "+v"(pc.y), "+v"(pc.z), "+v"(pc.w));
     const uint32_t d0 = (s >> 1) ? pc.z : pc.x, d1 = (s >> 1) ? pc.w : pc.y;
     return convert_b<kPerChannel>(d0, d1, 0);
   };
