@@ -95,7 +95,7 @@ static size_t split_bytes(int64_t M, int64_t N) {
 // A test times the automatic pick against every forced pick on a small grid (15 % bar).
 struct TileCost { int shape, bm, bn; bool one_per_cu; double alone_us, saturated_us; };
 static const struct DispatchModel {
-  TileCost tile[4] = {{0, 128, 512, true, 1.34, 1.50}, {3, 128, 256, true, 0.88, 0.90},
+  TileCost tile[4] = {{0, 128, 512, true, 1.15, 1.33}, {3, 128, 256, true, 0.71, 0.78},
                       {4, 128, 128, false, 0.63, 0.52}, {5, 64, 128, false, 0.45, 0.275}};
   double tile_fixed_ksteps = 4.0;
   double stream_tbs = 5.0;

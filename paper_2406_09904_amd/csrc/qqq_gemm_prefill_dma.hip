@@ -1,8 +1,9 @@
 // Prefill W4A8 GEMM, main kernel family: three-stage LDS ring fed by global->LDS DMA loads
-// (global_load_lds_dwordx4), v_mfma_i32_32x32x32_i8 main loop, one workgroup per output tile.
+// (global_load_lds_dwordx4), int8 MFMA main loop (v_mfma_i32_16x16x64_i8 in the 8-wave shapes,
+// v_mfma_i32_32x32x32_i8 in the 4-wave ones), one workgroup per output tile.
 //
-// Shape parameters: NW waves split N; each wave owns MT x CT MFMA tiles of 32 x 32, i.e. a
-// (32*MT) x (32*CT) patch of Y, so the workgroup tile is (32*MT) x (NW*32*CT).  Instances:
+// Shape parameters: NW waves split N; each wave owns a (32*MT) x (32*CT) patch of Y, so the
+// workgroup tile is (32*MT) x (NW*32*CT).  Instances:
 //   <4,2,8>  128 x 512, 8 waves, 128 accumulator registers, two waves per SIMD
 //   <4,1,8>  128 x 256, <4,1,4>  128 x 128, <2,1,4>  64 x 128: narrow tiles for mid-size M, where
 //            a few large tiles would leave most CUs idle
@@ -40,7 +41,6 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const int n32 = lane & 31, h = lane >> 5;
   const int N = p.N, M = p.M;
   const int64_t K = p.K;
   const int ntiles = N >> 4;
@@ -118,16 +118,22 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(dst), "v"(src)
                  : "memory", "m0");
   };
-  auto issue_dma = [&](int t, int stage) {
+  // One DMA instruction of k-step t into `stage` (piece 0 .. kDmaPerStep-1): the k-loop spreads a
+  // k-step's requests between its MFMAs (eight waves that issue everything at once right after a
+  // barrier queue up behind one address unit, and a wave that waits there issues no MFMA either).
+  auto issue_dma_piece = [&](int t, int stage, int piece) {
     const uint32_t base = lds_base + (uint32_t)stage * S::kStage;
-    const int8_t* ab = a_base + (int64_t)t * S::kBK;
-#pragma unroll
-    for (int i = 0; i < S::kAPieces; ++i) dma16s(ab, a_voff[i], base + (S::kAPieces * wave_u + i) * 1024);
-#pragma unroll
-    for (int j = 0; j < S::kWChunks; ++j)
-      dma16s(w_base[j] + (int64_t)t * w_step, w_voff, base + S::kAStage + wave_u * S::kWWave + j * 1024);
-    if constexpr (MODE != kPerChannel)
+    if (piece < S::kAPieces)
+      dma16s(a_base + (int64_t)t * S::kBK, a_voff[piece], base + (S::kAPieces * wave_u + piece) * 1024);
+    else if (piece < S::kAPieces + S::kWChunks)
+      dma16s(w_base[piece - S::kAPieces] + (int64_t)t * w_step, w_voff,
+             base + S::kAStage + wave_u * S::kWWave + (piece - S::kAPieces) * 1024);
+    else if constexpr (MODE != kPerChannel)
       dma4(sg_src + (int64_t)t * N * kSgBytes, base + S::kAStage + S::kWStage + wave_u * 256);
+  };
+  auto issue_dma = [&](int t, int stage) {
+#pragma unroll
+    for (int piece = 0; piece < S::kAPieces + S::kWChunks + 1; ++piece) issue_dma_piece(t, stage, piece);
   };
   // DMA loads per wave per k-step
   constexpr int kDmaPerStep = S::kAPieces + S::kWChunks + (MODE != kPerChannel ? 1 : 0);
@@ -137,29 +143,55 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(kDmaPerStep) : "memory");
   };
 
-  // ---- per-lane LDS read offsets.  A operand of MFMA step s: row 32*mt + n32, chunk 2s+h, stored
-  // in slot (2s+h) ^ ((row/2)%8).  W: tile c is chunks 2c and 2c+1; this lane's pieces are at
-  // (n32%16 + 16h)*16 and +512 of chunk 2c + n32/16.
-  int a_off[4];
+  // ---- MFMA form and fragment layout.
+  // 8-wave shapes: v_mfma_i32_16x16x64_i8.  Lane l holds row (or channel) l%16 and the 16 k-values
+  // of k-block l/16, i.e. chunk 4*s + l/16 of the row in the k-sub s (64 k) of the k-step; register
+  // i of a 16x16 result tile is row 4*(l/16) + i, column l%16.  Packed codes: lane l's 16-byte
+  // vector of each of the wave's 16-channel chunks is exactly its operand data (dwords 0,1: k-sub
+  // 0, dwords 2,3: k-sub 1).  This form moves half the accumulator bytes per multiply-accumulate
+  // of the 32x32x32 form, which is worth 10-15 % at the board's power limit, where the large shapes
+  // run; it issues twice the instructions, which two waves per SIMD absorb.
+  // 4-wave shapes: v_mfma_i32_32x32x32_i8.  They serve launches that leave one wave per SIMD, where
+  // the instruction issue of that one wave is the limit.  Lane l holds row (or channel) l%32 and
+  // the 16 k-values of chunk 2*s + l/32 in MFMA step s (32 k); register v of a 32x32 result tile is
+  // row 8*(v/4) + 4*(l/32) + v%4, column l%32.  Codes: tile c is chunks 2c and 2c+1; the lane's two
+  // pieces are at (l%16 + 16*(l/32))*16 and +512 of chunk 2c + (l%32)/16.
+  constexpr bool k32 = NW == 4;
+  constexpr int kTile = k32 ? 32 : 16;                 // edge of a result tile
+  constexpr int TM = S::kBM / kTile, TC = 32 * CT / kTile;  // result tiles per wave: TM x TC
+  constexpr int kRegs = k32 ? 16 : 4;                  // accumulator registers per tile
+  typedef int acc_t __attribute__((ext_vector_type(kRegs)));
+  const int lcol = lane & (kTile - 1);                 // the lane's column (and fragment row) in a tile
+  const int kblk = lane / kTile;                       // its k-block
+  // row of accumulator register v of row tile mt, relative to the workgroup tile
+  auto acc_row = [&](int mt, int v) { return mt * kTile + 8 * (v >> 2) + 4 * kblk + (v & 3); };
+  constexpr int kSubs = k32 ? 4 : 2;                   // MFMA steps along k per k-step
+  int a_off[kSubs];  // fragment of row lcol of row tile 0 (row tile mt adds kTile rows: same swizzle term)
 #pragma unroll
-  for (int s = 0; s < 4; ++s) a_off[s] = n32 * 128 + (((2 * s + h) ^ ((n32 >> 1) & 7)) << 4);
-  const int w_off = S::kAStage + wave * S::kWWave + (n32 >> 4) * 1024 + ((n32 & 15) + 16 * h) * 16;
-  const int sg_off = S::kAStage + S::kWStage + wave * 256 + n32 * kSgBytes;
+  for (int s = 0; s < kSubs; ++s)
+    a_off[s] = lcol * 128 + ((((k32 ? 2 : 4) * s + kblk) ^ ((lcol >> 1) & 7)) << 4);
+  const int w_off = S::kAStage + wave * S::kWWave +
+                    (k32 ? (lcol >> 4) * 1024 + ((lcol & 15) + 16 * kblk) * 16 : lane * 16);
+  const int sg_off = S::kAStage + S::kWStage + wave * 256 + lcol * kSgBytes;
 
-  int col[CT];
-  bool nvalid[CT];
+  int col[TC];
+  bool nvalid[TC];
 #pragma unroll
-  for (int c = 0; c < CT; ++c) {
-    col[c] = n_wave + c * 32 + n32;
+  for (int c = 0; c < TC; ++c) {
+    col[c] = n_wave + c * kTile + lcol;
     nvalid[c] = col[c] < N;
   }
-  v16i acc[MT][CT];
+  acc_t acc[TM][TC];
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
+  for (int mt = 0; mt < TM; ++mt)
 #pragma unroll
-    for (int c = 0; c < CT; ++c)
+    for (int c = 0; c < TC; ++c)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[mt][c][v] = 0;
+      for (int v = 0; v < kRegs; ++v) acc[mt][c][v] = 0;
+  auto mfma = [&](const v4i a, const v4i b, acc_t& d) {
+    if constexpr (k32) d = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, d, 0, 0, 0);
+    else d = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, d, 0, 0, 0);
+  };
 
   // ---- prologue: k-steps 0 and 1 in flight, wait for step 0.  DMA requests past the last k-step
   // re-fetch the last one (in bounds, never read), which keeps every k-step's wait count the same.
@@ -171,100 +203,181 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
   // starting the accumulators at 128 x (Bc x Rh) + Bc x Rl takes it out in advance: a small int8
   // contraction over the groups with the main loop's operand roles (row operand from the
   // activations' side, column operand from the weights' side), every lane reading its 16 group
-  // entries straight from memory while the first two k-steps of DMA are in flight.
+  // entries straight from memory while the first two k-steps of DMA are in flight.  Rows of the
+  // tables are padded with zeros to a multiple of 32 groups; where an MFMA takes 64, k-blocks past
+  // the padded row feed zeros.
   if (MODE == kGroupBias && split == 0) {  // the whole correction goes to the first K split
     const int Gp = (p.T + 31) & ~31;
+    constexpr int kStep = k32 ? 32 : 64;
+    const v4i zero = {0, 0, 0, 0};
 #pragma unroll
-    for (int c = 0; c < CT; ++c) {
-      const int8_t* bp = p.bias_w + (int64_t)(nvalid[c] ? col[c] : N - 1) * Gp + 16 * h;
+    for (int c = 0; c < TC; ++c) {
+      const int8_t* bp = p.bias_w + (int64_t)(nvalid[c] ? col[c] : N - 1) * Gp + 16 * kblk;
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        int mrow = m0 + 32 * mt + n32;
+      for (int mt = 0; mt < TM; ++mt) {
+        int mrow = m0 + kTile * mt + lcol;
         if (mrow > M - 1) mrow = M - 1;
-        const int8_t* lp = p.r_lo + (int64_t)mrow * Gp + 16 * h;
-        const int8_t* hp = p.r_hi + (int64_t)mrow * Gp + 16 * h;
-        for (int j = 0; j < Gp; j += 32)
-          acc[mt][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(*(const v4i*)(hp + j), *(const v4i*)(bp + j),
-                                                             acc[mt][c], 0, 0, 0);
+        const int8_t* lp = p.r_lo + (int64_t)mrow * Gp + 16 * kblk;
+        const int8_t* hp = p.r_hi + (int64_t)mrow * Gp + 16 * kblk;
+        for (int j = 0; j < Gp; j += kStep) {
+          const bool in = j + 16 * kblk < Gp;
+          mfma(in ? *(const v4i*)(hp + j) : zero, in ? *(const v4i*)(bp + j) : zero, acc[mt][c]);
+        }
 #pragma unroll
-        for (int v = 0; v < 16; ++v)  // modular by design near the int32 limit: unsigned
+        for (int v = 0; v < kRegs; ++v)  // modular by design near the int32 limit: unsigned
           acc[mt][c][v] = (int)((uint32_t)acc[mt][c][v] << 7);
-        for (int j = 0; j < Gp; j += 32)
-          acc[mt][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(*(const v4i*)(lp + j), *(const v4i*)(bp + j),
-                                                             acc[mt][c], 0, 0, 0);
+        for (int j = 0; j < Gp; j += kStep) {
+          const bool in = j + 16 * kblk < Gp;
+          mfma(in ? *(const v4i*)(lp + j) : zero, in ? *(const v4i*)(bp + j) : zero, acc[mt][c]);
+        }
       }
     }
   }
   wait_all_but_newest_step();
 
-  // ---- main loop, software-pipelined by hand and branch-free.  The activation fragments of MFMA
-  // step s+1 are read from LDS while the MFMAs of step s run; the workgroup barrier sits before
-  // the LAST MFMA step of a k-step (whose int8 operands are already converted), so that the LDS
-  // reads of the next k-step (first activation fragments, the lane's packed codes, its group
-  // scales) are in flight behind MT*CT MFMAs instead of stalling the pipe.
-  uint4 wq[CT][2];  // this lane's packed codes of the current k-step: [tile][piece]
-  int sg[CT];       // and its group scales
-  auto read_w = [&](const int8_t* sb) {
-#pragma unroll
-    for (int c = 0; c < CT; ++c) {
-      wq[c][0] = *(const uint4*)(sb + w_off + c * 2048);
-      wq[c][1] = *(const uint4*)(sb + w_off + c * 2048 + 512);
-      sg[c] = 0;
-      if constexpr (MODE == kGroupReal || MODE == kGroupCvt)
-        sg[c] = (int)*(const uint16_t*)(sb + sg_off + c * 64);
-      else if constexpr (MODE != kPerChannel)
-        sg[c] = (int)sb[sg_off + c * 32];
-    }
-  };
-  auto read_a = [&](v4i (&a)[MT], const int8_t* sb, int s) {
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) a[mt] = *(const v4i*)(sb + a_off[s] + mt * 4096);
-  };
-  // MFMA step s uses piece s%2, dword pair s/2 of the lane's packed codes
-  auto make_b = [&](int c, int s) {
-    const uint4 pc = wq[c][s & 1];
-    const uint32_t d0 = (s >> 1) ? pc.z : pc.x, d1 = (s >> 1) ? pc.w : pc.y;
-    return convert_b<MODE>(d0, d1, sg[c]);
-  };
-  auto mfma_col = [&](const v4i (&a)[MT], const v4i b, int c) {
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-      acc[mt][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[mt], b, acc[mt][c], 0, 0, 0);
-  };
-  auto mfma_step = [&](const v4i (&a)[MT], int s) {
-#pragma unroll
-    for (int c = 0; c < CT; ++c) mfma_col(a, make_b(c, s), c);
-  };
-
   int stage = 0;
-  v4i a0[MT], a1[MT];
-  read_w(lds);
-  read_a(a0, lds, 0);
-  for (int t = 0; t < T; ++t) {
-    // k-step t+2 goes into the stage that was read during k-step t-1 (everyone is past the
-    // barrier inside it)
-    issue_dma(t + 2 < T ? t + 2 : T - 1, stage == 0 ? 2 : stage - 1);
-    const int8_t* sb = lds + stage * S::kStage;
-    read_a(a1, sb, 1);
-    mfma_step(a0, 0);
-    read_a(a0, sb, 2);
-    mfma_step(a1, 1);
-    read_a(a1, sb, 3);
-    mfma_step(a0, 2);
-    v4i b3[CT];
+  if constexpr (!k32) {
+    // ---- main loop, 16x16x64 form: a k-step is a fixed sequence of 2*TM slots (k-sub, row tile), TC
+    // MFMAs each.  Fragments are read kAhead slots (about 200 clocks of MFMAs) before their MFMAs
+    // into a rotating set of registers; the closing wait and barrier of the k-step sit before its
+    // last kAhead slots, whose fragment reads already go to the next stage, so that LDS latency at
+    // the k-step border hides behind MFMAs whose operands are in registers.  The DMA requests of
+    // k-step t+2 go out one per slot.  The wave's own packed codes and group scales of k-step t+1
+    // are read at mid-step, with no barrier (their DMA is this wave's own, issued a whole k-step
+    // earlier), which spreads the conversions over the whole k-step: the second k-sub's tile c in
+    // the first half, the next k-step's first k-sub's in the second half.  The compiler's scheduler
+    // would pull the reads next to their uses; a scheduling barrier after every slot keeps the
+    // order written here.
+    constexpr int kSlots = 2 * TM, kAhead = TC >= 4 ? 3 : 6, kBufs = kAhead < 4 ? 4 : 8;
+    constexpr int kCvtStride = (TM - 2) / (TC - 1);
+    static_assert(kDmaPerStep <= TM && kAhead < TM && 1 + (TC - 1) * kCvtStride < TM, "k-step schedule does not fit");
+    v4i wq[TC];  // this lane's packed codes of a k-step, one vector per channel tile
+    int sg[TC];    // and its group scales
+    auto read_w = [&](const int8_t* sb) {
 #pragma unroll
-    for (int c = 0; c < CT; ++c) b3[c] = make_b(c, 3);
-    // my DMA of k-step t+1 has landed (only the loads of k-step t+2 may still be in flight), my
-    // LDS reads of this stage are done; then everyone's
-    wait_all_but_newest_step();
-    stage = (stage == 2) ? 0 : stage + 1;
-    // first LDS reads of k-step t+1 (stale data after the last k-step: read, never used) ...
-    const int8_t* nb = lds + stage * S::kStage;
-    read_a(a0, nb, 0);
-    read_w(nb);
-    // ... in flight behind the last MFMA step of k-step t
+      for (int c = 0; c < TC; ++c) {
+        wq[c] = *(const v4i*)(sb + w_off + c * 1024);
+        sg[c] = 0;
+        if constexpr (MODE == kGroupReal || MODE == kGroupCvt)
+          sg[c] = (int)*(const uint16_t*)(sb + sg_off + c * 32);
+        else if constexpr (MODE != kPerChannel)
+          sg[c] = (int)sb[sg_off + c * 16];
+      }
+    };
+    // fragment of slot i = (k-sub i / TM, row tile i % TM)
+    auto read_a = [&](const int8_t* sb, int slot) {
+      return *(const v4i*)(sb + a_off[slot / TM] + (slot % TM) * 2048);
+    };
+    auto make_b = [&](int c, int s) {
+      return s ? convert_b<MODE>((uint32_t)wq[c][2], (uint32_t)wq[c][3], sg[c])
+             : convert_b<MODE>((uint32_t)wq[c][0], (uint32_t)wq[c][1], sg[c]);
+    };
+    v4i abuf[kBufs], b0[TC], b1[TC];
+    read_w(lds);
 #pragma unroll
-    for (int c = 0; c < CT; ++c) mfma_col(a1, b3[c], c);
+    for (int i = 0; i < kAhead; ++i) abuf[i] = read_a(lds, i);
+#pragma unroll
+    for (int c = 0; c < TC; ++c) b0[c] = make_b(c, 0);
+    for (int t = 0; t < T; ++t) {
+      // k-step t+2 goes into the stage that was read during k-step t-1 (everyone is past the
+      // barrier inside it)
+      const int dt = t + 2 < T ? t + 2 : T - 1;
+      const int dstage = stage == 0 ? 2 : stage - 1;
+      const int nstage = stage == 2 ? 0 : stage + 1;
+      const int8_t* sb = lds + stage * S::kStage;
+      const int8_t* nb = lds + nstage * S::kStage;
+#pragma unroll
+      for (int i = 0; i < kSlots; ++i) {
+        if (i == TM) {  // all of k-step t+2's requests are out: what else is in flight is older
+          asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kDmaPerStep) : "memory");
+          read_w(nb);
+        }
+        if (i == kSlots - kAhead) {
+          // my DMA of k-step t+1 has landed (only the loads of k-step t+2 may still be in flight), my
+          // LDS reads of this stage are done; then everyone's.  From here on the fragment reads go to
+          // the next k-step's stage (stale data after the last k-step: read, never used).
+          wait_all_but_newest_step();
+        }
+        abuf[(i + kAhead) % kBufs] = (i + kAhead < kSlots) ? read_a(sb, i + kAhead) : read_a(nb, i + kAhead - kSlots);
+        if (i < kDmaPerStep) issue_dma_piece(dt, dstage, i);
+#pragma unroll
+        for (int c = 0; c < TC; ++c) {
+          if (i == 1 + c * kCvtStride) b1[c] = make_b(c, 1);
+          if (i == TM + 1 + c * kCvtStride) b0[c] = make_b(c, 0);  // of k-step t+1 (tile c's last use: slot TM-1)
+        }
+#pragma unroll
+        for (int c = 0; c < TC; ++c) mfma(abuf[i % kBufs], i < TM ? b0[c] : b1[c], acc[i % TM][c]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      stage = nstage;
+    }
+  } else {
+    // ---- main loop, 32x32x32 form, software-pipelined by hand and branch-free.  The activation
+    // fragments of MFMA step s+1 are read from LDS while the MFMAs of step s run; the workgroup
+    // barrier sits before the LAST MFMA step of a k-step (whose int8 operands are already
+    // converted), so that the LDS reads of the next k-step (first activation fragments, the lane's
+    // packed codes, its group scales) are in flight behind TM*TC MFMAs instead of stalling the pipe.
+    v4i wq[TC][2];  // this lane's packed codes of the current k-step: [tile][piece]
+    int sg[TC];       // and its group scales
+    auto read_w = [&](const int8_t* sb) {
+#pragma unroll
+      for (int c = 0; c < TC; ++c) {
+        wq[c][0] = *(const v4i*)(sb + w_off + c * 2048);
+        wq[c][1] = *(const v4i*)(sb + w_off + c * 2048 + 512);
+        sg[c] = 0;
+        if constexpr (MODE == kGroupReal || MODE == kGroupCvt)
+          sg[c] = (int)*(const uint16_t*)(sb + sg_off + c * 64);
+        else if constexpr (MODE != kPerChannel)
+          sg[c] = (int)sb[sg_off + c * 32];
+      }
+    };
+    auto read_a = [&](v4i (&a)[TM], const int8_t* sb, int s) {
+#pragma unroll
+      for (int mt = 0; mt < TM; ++mt) a[mt] = *(const v4i*)(sb + a_off[s] + mt * 4096);
+    };
+    // MFMA step s uses piece s%2, dword pair s/2 of the lane's packed codes
+    auto make_b = [&](int c, int s) {
+      const v4i pc = wq[c][s & 1];
+      const uint32_t d0 = (uint32_t)((s >> 1) ? pc[2] : pc[0]), d1 = (uint32_t)((s >> 1) ? pc[3] : pc[1]);
+      return convert_b<MODE>(d0, d1, sg[c]);
+    };
+    auto mfma_col = [&](const v4i (&a)[TM], const v4i b, int c) {
+#pragma unroll
+      for (int mt = 0; mt < TM; ++mt) mfma(a[mt], b, acc[mt][c]);
+    };
+    auto mfma_step = [&](const v4i (&a)[TM], int s) {
+#pragma unroll
+      for (int c = 0; c < TC; ++c) mfma_col(a, make_b(c, s), c);
+    };
+    v4i a0[TM], a1[TM];
+    read_w(lds);
+    read_a(a0, lds, 0);
+    for (int t = 0; t < T; ++t) {
+      // k-step t+2 goes into the stage that was read during k-step t-1 (everyone is past the
+      // barrier inside it)
+      issue_dma(t + 2 < T ? t + 2 : T - 1, stage == 0 ? 2 : stage - 1);
+      const int8_t* sb = lds + stage * S::kStage;
+      read_a(a1, sb, 1);
+      mfma_step(a0, 0);
+      read_a(a0, sb, 2);
+      mfma_step(a1, 1);
+      read_a(a1, sb, 3);
+      mfma_step(a0, 2);
+      v4i b3[TC];
+#pragma unroll
+      for (int c = 0; c < TC; ++c) b3[c] = make_b(c, 3);
+      // my DMA of k-step t+1 has landed (only the loads of k-step t+2 may still be in flight), my
+      // LDS reads of this stage are done; then everyone's
+      wait_all_but_newest_step();
+      stage = (stage == 2) ? 0 : stage + 1;
+      // first LDS reads of k-step t+1 (stale data after the last k-step: read, never used) ...
+      const int8_t* nb = lds + stage * S::kStage;
+      read_a(a0, nb, 0);
+      read_w(nb);
+      // ... in flight behind the last MFMA step of k-step t
+#pragma unroll
+      for (int c = 0; c < TC; ++c) mfma_col(a1, b3[c], c);
+    }
   }
   // the clamped DMA requests of the last two k-steps may still be landing in the ring
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -273,13 +386,13 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
   if (p.k_splits > 1) {
     int32_t* part = p.part + (int64_t)split * M * N;
 #pragma unroll
-    for (int c = 0; c < CT; ++c) {
+    for (int c = 0; c < TC; ++c) {
       if (!nvalid[c]) continue;
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
+      for (int mt = 0; mt < TM; ++mt) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int m = m0 + mt * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+        for (int v = 0; v < kRegs; ++v) {
+          const int m = m0 + acc_row(mt, v);
           if (m < M) part[(int64_t)m * N + col[c]] = acc[mt][c][v];
         }
       }
@@ -287,31 +400,31 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
     return;
   }
 
-  // ---- fused Dequant epilogue.  Lane holds column n32 of each tile; register v of a 32x32 tile is
-  // row 8*(v/4) + 4*h + v%4.  The ring is free now (nothing reads it after the last barrier and
-  // every DMA has landed): each wave dequantises its patch into its own fp16 LDS region (row pitch
-  // padded by 16 B so the two lane halves hit different banks) and streams it out as full rows.
+  // ---- fused Dequant epilogue.  Every four accumulator registers of a lane are four consecutive
+  // rows of its column.  The ring is free now (nothing reads it after the last barrier and every
+  // DMA has landed): each wave dequantises its patch into its own fp16 LDS region (row pitch padded
+  // by 16 B) and streams it out as full rows.
   float* sa_lds = (float*)(lds + NW * S::kEpWave);
   for (int r = tid; r < S::kBM; r += NW * 64) sa_lds[r] = (m0 + r < M) ? p.s_a[m0 + r] : 0.0f;
-  float swv[CT];
+  float swv[TC];
 #pragma unroll
-  for (int c = 0; c < CT; ++c) swv[c] = nvalid[c] ? (float)p.s_w[col[c]] : 0.0f;
+  for (int c = 0; c < TC; ++c) swv[c] = nvalid[c] ? (float)p.s_w[col[c]] : 0.0f;
   __syncthreads();
   int8_t* ep = lds + wave * S::kEpWave;
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
+  for (int mt = 0; mt < TM; ++mt) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int r0 = mt * 32 + 8 * q + 4 * h;
+    for (int q = 0; q < kRegs / 4; ++q) {
+      const int r0 = acc_row(mt, 4 * q);
       const float4 sa4 = *(const float4*)(sa_lds + r0);
       const float sav[4] = {sa4.x, sa4.y, sa4.z, sa4.w};
 #pragma unroll
-      for (int c = 0; c < CT; ++c) {
+      for (int c = 0; c < TC; ++c) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           int x = acc[mt][c][4 * q + j];
           if constexpr (MODE == kPerChannel) x >>= 4;  // exact: the sum is a multiple of 16
-          *(_Float16*)(ep + (r0 + j) * S::kEpRow + (c * 32 + n32) * 2) = dequant(x, sav[j], swv[c]);
+          *(_Float16*)(ep + (r0 + j) * S::kEpRow + (c * kTile + lcol) * 2) = dequant(x, sav[j], swv[c]);
         }
       }
     }
@@ -332,13 +445,13 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
   }
   if (p.acc_out) {  // parity/debug output of the true accumulators: plain stores
 #pragma unroll
-    for (int c = 0; c < CT; ++c) {
+    for (int c = 0; c < TC; ++c) {
       if (!nvalid[c]) continue;
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
+      for (int mt = 0; mt < TM; ++mt) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int m = m0 + mt * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+        for (int v = 0; v < kRegs; ++v) {
+          const int m = m0 + acc_row(mt, v);
           if (m < M) {
             int x = acc[mt][c][v];
             if constexpr (MODE == kPerChannel) x >>= 4;

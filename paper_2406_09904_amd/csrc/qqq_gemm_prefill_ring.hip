@@ -202,12 +202,12 @@ __global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmPar
   const int small_off = kSmall + wave * 256;
 
   v4i acc[8][4];
-  uint4 wq[4];  // this lane's packed codes of a k-step, one vector per channel tile
+  v4i wq[4];  // this lane's packed codes of a k-step, one vector per channel tile
   int sg[4];    // and its group scales
   auto read_w = [&](const int8_t* sb) {
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      wq[c] = *(const uint4*)(sb + w_off + c * 1024);
+      wq[c] = *(const v4i*)(sb + w_off + c * 1024);
       sg[c] = 0;
       if constexpr (MODE != kPerChannel) sg[c] = (int)sb[small_off + c * 16 + r16];
     }
@@ -217,7 +217,8 @@ __global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmPar
     return *(const v4i*)(sb + a_off[slot >> 3] + (slot & 7) * 2048);
   };
   auto make_b = [&](int c, int s) {
-    return s ? convert_b<MODE>(wq[c].z, wq[c].w, sg[c]) : convert_b<MODE>(wq[c].x, wq[c].y, sg[c]);
+    return s ? convert_b<MODE>((uint32_t)wq[c][2], (uint32_t)wq[c][3], sg[c])
+             : convert_b<MODE>((uint32_t)wq[c][0], (uint32_t)wq[c][1], sg[c]);
   };
 
   // ---- prologue: k-steps 0 and 1 of the first tile in flight, wait for step 0
