@@ -693,15 +693,17 @@ def ceilings(torch, qqq, synth):
                         (W | C, "+ packed codes from LDS and their conversion"),
                         (D, "+ DMA ring refill, wait and barrier"),
                         (A | W | C, "all LDS reads and the conversion"),
-                        (A | W | C | D, "the whole k-loop")):
+                        (A | W | C | D, "the whole k-loop"),
+                        (qqq.PROBE_FORM_32X32X32, "32x32x32 form: MFMAs only"),
+                        (qqq.PROBE_FORM_32X32X32 | A | W | C | D, "32x32x32 form: the whole k-loop")):
         ms = min(timed_ms(torch, lambda i, parts=parts: qqq.probe_prefill_loop(src, region, steps, parts, wgs, sink),
                           1, 1, False) for _ in range(3))
-        ops = wgs * 8 * steps * 32 * 65536.0
+        ops = wgs * 8 * steps * 32 * 65536.0   # 128 x 64 x 128 multiply-accumulates per wave and k-step
         rows.append({"parts": name, "ms": round(ms, 3),
                      "frac_of_nominal": round(ops / ms / 1e9 / MFMA_I8_PEAK_TOPS, 4)})
     base = 1.0 / rows[0]["frac_of_nominal"]
     for r in rows:
-        r["time_per_mfma_vs_first_row"] = round(1.0 / r["frac_of_nominal"] / base, 3)
+        r["time_per_mac_vs_first_row"] = round(1.0 / r["frac_of_nominal"] / base, 3)
     # the same loop on constant bytes draws little power: the clock stays near nominal and the
     # fraction is the MFMA pipe's busy share, i.e. what the loop loses as a schedule
     src.fill_(0x12)

@@ -45,15 +45,16 @@ int qqq_debug_count_sg_violations(const int8_t* s_g, int64_t N, int64_t K, int s
  *     on the operand values, which is why the caller supplies them.  sink: 4 bytes, never written
  *     in practice.
  *   qqq_probe_prefill_loop: `workgroups` x 8 waves run `steps` k-steps of the persistent prefill
- *     kernel's per-channel k-loop (32 MFMAs per wave and k-step, the same LDS ring, fragment layout
- *     and DMA pieces) with the parts named by `parts` switched on; the others use operands that stay
+ *     kernel's per-channel k-loop (64 v_mfma_i32_16x16x64_i8 per wave and k-step, the same LDS ring,
+ *     fragment layout and DMA pieces) with the parts named by `parts` switched on; the others use operands that stay
  *     in registers.  src: workgroups x region_bytes bytes (16-byte aligned; region_bytes a multiple
  *     of the 51200-byte ring stage, at most 64 MiB): per stage 16 KiB of int8 activations (128 rows x
  *     128 k), 32 KiB of packed codes (32 tiles of 16 channels), 2 KiB ignored.  Workgroup b keeps to
  *     its own region; the ring starts as the region's first bytes and, with QQQ_PROBE_DMA, is refilled
  *     from the region cyclically, two k-steps ahead, with the kernel's wait and barrier.
  *     2 * 32^3 * 32 * 8 * steps operations per workgroup.  Supported combinations: 0, CONVERT,
- *     A_READS, A_READS|CONVERT, W_READS|CONVERT, DMA, A_READS|W_READS|CONVERT and all four.
+ *     A_READS, A_READS|CONVERT, W_READS|CONVERT, DMA, A_READS|W_READS|CONVERT and all four;
+ *     FORM_32X32X32 alone or with all four.
  *     This GPU runs MFMA-heavy kernels at its board power limit, so each part costs what its
  *     energy takes from the clock; the probe measures that on the caller's bytes.
  */
@@ -61,6 +62,7 @@ int qqq_debug_count_sg_violations(const int8_t* s_g, int64_t N, int64_t K, int s
 #define QQQ_PROBE_W_READS 2 /* packed codes read from LDS every k-step (4 KiB per wave); implies CONVERT */
 #define QQQ_PROBE_CONVERT 4 /* int4 -> int8 conversion redone every k-step (else hoisted) */
 #define QQQ_PROBE_DMA 8     /* global -> LDS DMA of the next k-steps, its wait and the workgroup barrier */
+#define QQQ_PROBE_FORM_32X32X32 16 /* the same wave patch as 4 x 2 tiles of v_mfma_i32_32x32x32_i8 (alone or with all parts) */
 int qqq_probe_prefill_loop(const void* src, size_t region_bytes, int steps, int parts, int workgroups,
                            int32_t* sink, void* stream);
 int qqq_probe_stream_read(const void* buf, size_t bytes, int workgroups, uint32_t* sink, void* stream);

@@ -414,7 +414,7 @@ def probe_mfma_i8(a_pool: torch.Tensor, b_pool: torch.Tensor, iters: int, workgr
                                    _ptr(sink, torch.int32), _stream()))
 
 
-PROBE_A_READS, PROBE_W_READS, PROBE_CONVERT, PROBE_DMA = 1, 2, 4, 8
+PROBE_A_READS, PROBE_W_READS, PROBE_CONVERT, PROBE_DMA, PROBE_FORM_32X32X32 = 1, 2, 4, 8, 16
 PROBE_LOOP_STAGE = 51200
 
 
