@@ -334,7 +334,7 @@ def sample_clock(torch, case):
     except Exception as ex:                         # noqa: BLE001 - a diagnostic, never fatal
         print("bench: clock sampling failed (%s)" % ex, file=sys.stderr)
         return None
-    time.sleep(0.5)
+    time.sleep(4.0)                                 # the power reading is an average over the last seconds
     idle = read()
     cap = tool(["rocm-smi", "--showmaxpower"], r"Max Graphics Package Power \(W\):\s*([0-9.]+)")
     return {"sclk_mhz_during_gemm": busy[0], "sclk_mhz_idle": idle[0], "nominal_mhz": 2400,
