@@ -207,29 +207,47 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
   // tables are padded with zeros to a multiple of 32 groups; where an MFMA takes 64, k-blocks past
   // the padded row feed zeros.
   if (MODE == kGroupBias && split == 0) {  // the whole correction goes to the first K split
+    // All operands of a pass are loaded before its MFMAs (TM + TC independent loads in flight): taken
+    // one (row tile, channel tile) pair at a time, the load-then-MFMA chains of a tile ran one memory
+    // latency after the other, 10-24 us per tile.
     const int Gp = (p.T + 31) & ~31;
     constexpr int kStep = k32 ? 32 : 64;
     const v4i zero = {0, 0, 0, 0};
+    const int8_t* bp[TC];
+    uint32_t roff[TM];
 #pragma unroll
-    for (int c = 0; c < TC; ++c) {
-      const int8_t* bp = p.bias_w + (int64_t)(nvalid[c] ? col[c] : N - 1) * Gp + 16 * kblk;
+    for (int c = 0; c < TC; ++c) bp[c] = p.bias_w + (int64_t)(nvalid[c] ? col[c] : N - 1) * Gp + 16 * kblk;
 #pragma unroll
-      for (int mt = 0; mt < TM; ++mt) {
-        int mrow = m0 + kTile * mt + lcol;
-        if (mrow > M - 1) mrow = M - 1;
-        const int8_t* lp = p.r_lo + (int64_t)mrow * Gp + 16 * kblk;
-        const int8_t* hp = p.r_hi + (int64_t)mrow * Gp + 16 * kblk;
-        for (int j = 0; j < Gp; j += kStep) {
-          const bool in = j + 16 * kblk < Gp;
-          mfma(in ? *(const v4i*)(hp + j) : zero, in ? *(const v4i*)(bp + j) : zero, acc[mt][c]);
-        }
+    for (int mt = 0; mt < TM; ++mt) {
+      int mrow = m0 + kTile * mt + lcol;
+      if (mrow > M - 1) mrow = M - 1;
+      roff[mt] = (uint32_t)(mrow - m0) * (uint32_t)Gp + 16u * kblk;
+    }
+    const int8_t* hbase = p.r_hi + (int64_t)m0 * Gp;
+    const int8_t* lbase = p.r_lo + (int64_t)m0 * Gp;
 #pragma unroll
-        for (int v = 0; v < kRegs; ++v)  // modular by design near the int32 limit: unsigned
-          acc[mt][c][v] = (int)((uint32_t)acc[mt][c][v] << 7);
-        for (int j = 0; j < Gp; j += kStep) {
-          const bool in = j + 16 * kblk < Gp;
-          mfma(in ? *(const v4i*)(lp + j) : zero, in ? *(const v4i*)(bp + j) : zero, acc[mt][c]);
-        }
+    for (int pass = 0; pass < 2; ++pass) {
+      const int8_t* rbase = pass ? lbase : hbase;
+      for (int j = 0; j < Gp; j += kStep) {
+        const bool in = j + 16 * kblk < Gp;
+        v4i bw[TC], ar[TM];
+#pragma unroll
+        for (int c = 0; c < TC; ++c) bw[c] = in ? *(const v4i*)(bp[c] + j) : zero;
+#pragma unroll
+        for (int mt = 0; mt < TM; ++mt) ar[mt] = in ? *(const v4i*)(rbase + roff[mt] + j) : zero;
+#pragma unroll
+        for (int mt = 0; mt < TM; ++mt)
+#pragma unroll
+          for (int c = 0; c < TC; ++c) mfma(ar[mt], bw[c], acc[mt][c]);
+      }
+      if (pass == 0) {
+#pragma unroll
+        for (int mt = 0; mt < TM; ++mt)
+#pragma unroll
+          for (int c = 0; c < TC; ++c)
+#pragma unroll
+            for (int v = 0; v < kRegs; ++v)  // modular by design near the int32 limit: unsigned
+              acc[mt][c][v] = (int)((uint32_t)acc[mt][c][v] << 7);
       }
     }
   }

@@ -238,8 +238,6 @@ __global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmPar
   read_w(lds);
 #pragma unroll
   for (int i = 0; i < kAhead; ++i) abuf[i] = read_a(lds, i);
-#pragma unroll
-  for (int c = 0; c < 4; ++c) b0[c] = make_b(c, 0);
   for (int it = 0; it < my_tiles; ++it) {
     int tm, tn;
     tile_coords(it, tm, tn);
@@ -256,32 +254,56 @@ __global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmPar
     // Rows of the tables are padded with zeros to a multiple of 32 groups; an MFMA takes 64, so
     // k-blocks past the padded row feed zeros.
     if constexpr (MODE == kGroupBias) {
+      // The operands of a pass are loaded in batches ahead of their MFMAs (4-8 independent loads in flight): taken one
+      // (row tile, channel tile) pair at a time, the 64 load-then-MFMA chains of a tile ran one memory
+      // latency after the other, 10-24 us per tile.
       const int Gp = (T + 31) & ~31;
       const v4i zero = {0, 0, 0, 0};
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
+      // offsets are recomputed where they are used: registers are scarce here (the next tile's
+      // first fragments and operands are already held)
+      const int nb0 = n_wave < N - 1 ? n_wave : N - 1;  // a wave past the ragged edge re-reads the last channel
+      auto boff = [&](int c) {
         int col = n_wave + c * 16 + r16;
         if (col > N - 1) col = N - 1;
-        const int8_t* bp = p.bias_w + (int64_t)col * Gp + 16 * kb;
+        return (uint32_t)(col - nb0) * (uint32_t)Gp + 16u * kb;
+      };
+      auto roff = [&](int mt) {
+        int mrow = m0 + 16 * mt + r16;
+        if (mrow > M - 1) mrow = M - 1;
+        return (uint32_t)(mrow - m0) * (uint32_t)Gp + 16u * kb;
+      };
+      const int8_t* bbase = p.bias_w + (int64_t)nb0 * Gp;
+      const int8_t* hbase = p.r_hi + (int64_t)m0 * Gp;
+      const int8_t* lbase = p.r_lo + (int64_t)m0 * Gp;
 #pragma unroll
-        for (int mt = 0; mt < 8; ++mt) {
-          int mrow = m0 + 16 * mt + r16;
-          if (mrow > M - 1) mrow = M - 1;
-          const int8_t* lp = p.r_lo + (int64_t)mrow * Gp + 16 * kb;
-          const int8_t* hp = p.r_hi + (int64_t)mrow * Gp + 16 * kb;
-          for (int j = 0; j < Gp; j += 64) {
-            const bool in = j + 16 * kb < Gp;
-            acc[mt][c] = __builtin_amdgcn_mfma_i32_16x16x64_i8(in ? *(const v4i*)(hp + j) : zero,
-                                                               in ? *(const v4i*)(bp + j) : zero, acc[mt][c], 0, 0, 0);
-          }
+      for (int pass = 0; pass < 2; ++pass) {
+        const int8_t* rbase = pass ? lbase : hbase;
+        for (int j = 0; j < Gp; j += 64) {
+          const bool in = j + 16 * kb < Gp;
+          v4i bw[4];
 #pragma unroll
-          for (int v = 0; v < 4; ++v)  // modular by design near the int32 limit: unsigned
-            acc[mt][c][v] = (int)((uint32_t)acc[mt][c][v] << 7);
-          for (int j = 0; j < Gp; j += 64) {
-            const bool in = j + 16 * kb < Gp;
-            acc[mt][c] = __builtin_amdgcn_mfma_i32_16x16x64_i8(in ? *(const v4i*)(lp + j) : zero,
-                                                               in ? *(const v4i*)(bp + j) : zero, acc[mt][c], 0, 0, 0);
+          for (int c = 0; c < 4; ++c) bw[c] = in ? *(const v4i*)(bbase + boff(c) + j) : zero;
+#pragma unroll
+          for (int half = 0; half < 2; ++half) {  // four row tiles at a time: registers are scarce here
+            v4i ar[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) ar[i] = in ? *(const v4i*)(rbase + roff(4 * half + i) + j) : zero;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+              for (int c = 0; c < 4; ++c)
+                acc[4 * half + i][c] =
+                    __builtin_amdgcn_mfma_i32_16x16x64_i8(ar[i], bw[c], acc[4 * half + i][c], 0, 0, 0);
           }
+        }
+        if (pass == 0) {
+#pragma unroll
+          for (int mt = 0; mt < 8; ++mt)
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+#pragma unroll
+              for (int v = 0; v < 4; ++v)  // modular by design near the int32 limit: unsigned
+                acc[mt][c][v] = (int)((uint32_t)acc[mt][c][v] << 7);
         }
       }
     }
@@ -293,6 +315,9 @@ __global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmPar
       const int nstage = stage == 2 ? 0 : stage + 1;
       const int8_t* sb = lds + stage * kStage;
       const int8_t* nb = lds + nstage * kStage;
+      // the first k-sub's operands, from the codes read after the previous k-step's barrier
+#pragma unroll
+      for (int c = 0; c < 4; ++c) b0[c] = make_b(c, 0);
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         if (i == 16 - kAhead) {
@@ -311,9 +336,6 @@ __global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmPar
           acc[i & 7][c] = __builtin_amdgcn_mfma_i32_16x16x64_i8(abuf[i & 3], i < 8 ? b0[c] : b1[c], acc[i & 7][c], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
       }
-      // the next k-step's first operands, from the codes read after the barrier
-#pragma unroll
-      for (int c = 0; c < 4; ++c) b0[c] = make_b(c, 0);
       stage = nstage;
     }
 
