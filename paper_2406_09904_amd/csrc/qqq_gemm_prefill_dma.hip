@@ -424,9 +424,13 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
   // by 16 B) and streams it out as full rows.
   float* sa_lds = (float*)(lds + NW * S::kEpWave);
   for (int r = tid; r < S::kBM; r += NW * 64) sa_lds[r] = (m0 + r < M) ? p.s_a[m0 + r] : 0.0f;
+  // Per-channel sums carry the factor 16 of the conversion.  Scaling by a power of two commutes with
+  // every rounding of the Dequant (int -> fp32, fp32 product, fp16 result), so the factor goes into
+  // the channel scale instead of a shift per accumulator.
+  constexpr float kAccScale = MODE == kPerChannel ? 0.0625f : 1.0f;
   float swv[TC];
 #pragma unroll
-  for (int c = 0; c < TC; ++c) swv[c] = nvalid[c] ? (float)p.s_w[col[c]] : 0.0f;
+  for (int c = 0; c < TC; ++c) swv[c] = nvalid[c] ? (float)p.s_w[col[c]] * kAccScale : 0.0f;
   __syncthreads();
   int8_t* ep = lds + wave * S::kEpWave;
 #pragma unroll
@@ -440,9 +444,8 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
       for (int c = 0; c < TC; ++c) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          int x = acc[mt][c][4 * q + j];
-          if constexpr (MODE == kPerChannel) x >>= 4;  // exact: the sum is a multiple of 16
-          *(_Float16*)(ep + (r0 + j) * S::kEpRow + (c * kTile + lcol) * 2) = dequant(x, sav[j], swv[c]);
+          *(_Float16*)(ep + (r0 + j) * S::kEpRow + (c * kTile + lcol) * 2) =
+              dequant(acc[mt][c][4 * q + j], sav[j], swv[c]);
         }
       }
     }

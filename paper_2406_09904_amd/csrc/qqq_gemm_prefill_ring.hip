@@ -2,7 +2,7 @@
 // list of 128 x 512 output tiles and the LDS ring keeps rotating across tile borders.
 //
 // Same k-step body as gemm_prefill_dma_kernel<.,4,2,8> (8 waves splitting N, 128 accumulator
-// registers per lane, v_mfma_i32_32x32x32_i8, three 50 KiB LDS stages fed by global->LDS DMA two
+// registers per lane, v_mfma_i32_16x16x64_i8, three 50 KiB LDS stages fed by global->LDS DMA two
 // k-steps ahead).  What persistence buys: the DMA stream is a cursor over (tile, k-step) that runs
 // two steps ahead of the MFMAs, so the first two k-steps of the NEXT tile are already in flight
 // while the current tile finishes and is written out — the per-tile pipeline fill (an HBM
@@ -345,10 +345,14 @@ __global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmPar
       const int8_t* fsb = lds + (stage == 0 ? 2 : stage - 1) * kStage;
       int8_t* patch = const_cast<int8_t*>(fsb) + wave * kEpWave;
       const int8_t* sd = side + (it & 1) * kSide;  // this tile's scales: [wave][256 B s_a, 256 B s_w]
+      // Per-channel sums carry the factor 16 of the conversion.  Scaling by a power of two commutes with
+      // every rounding of the Dequant (int -> fp32, fp32 product, fp16 result), so the factor goes
+      // into the channel scale instead of a shift per accumulator.
+      constexpr float kAccScale = MODE == kPerChannel ? 0.0625f : 1.0f;
       float swv[4];
 #pragma unroll
       for (int c = 0; c < 4; ++c)
-        swv[c] = (float)*(const _Float16*)(sd + wave * 512 + 256 + (c * 16 + r16) * 2);
+        swv[c] = (float)*(const _Float16*)(sd + wave * 512 + 256 + (c * 16 + r16) * 2) * kAccScale;
       const int cc = lane & 7;
       const int ncol = n_wave + cc * 8;
 #pragma unroll
@@ -363,10 +367,8 @@ __global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmPar
           for (int c = 0; c < 4; ++c) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-              int x = acc[mt][c][j];
-              if constexpr (MODE == kPerChannel) x >>= 4;  // exact: the sum is a multiple of 16
               *(_Float16*)(patch + (16 * half + 4 * kb + j) * kEpRow + (c * 16 + r16) * 2) =
-                  dequant(x, sav[j], swv[c]);
+                  dequant(acc[mt][c][j], sav[j], swv[c]);
             }
           }
         }
