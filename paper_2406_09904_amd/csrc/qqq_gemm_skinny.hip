@@ -98,15 +98,15 @@ __device__ __forceinline__ void load_batch_w(Batch<NT, MT, U>& b, const GemmPara
 // abase: the global a_q, or the workgroup's LDS copy in the fused kernel
 template <int NT, int MT, int U>
 __device__ __forceinline__ void load_batch_a(Batch<NT, MT, U>& b, const int8_t* abase, int tb,
-                                             int tstride, int t1, const uint32_t (&aoff)[MT]) {
+                                             int tstride, int t1, const uint32_t (&aoff)[MT][2]) {
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     const int t = min(tb + tstride * u, t1 - 1);
     const int8_t* at = abase + (int64_t)t * 128;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-      b.a[u][mt][0] = *(const v4i*)(at + aoff[mt]);
-      b.a[u][mt][1] = *(const v4i*)(at + aoff[mt] + 64u);  // second MFMA step of this k-step
+      b.a[u][mt][0] = *(const v4i*)(at + aoff[mt][0]);
+      b.a[u][mt][1] = *(const v4i*)(at + aoff[mt][1]);
     }
   }
 }
@@ -114,7 +114,7 @@ __device__ __forceinline__ void load_batch_a(Batch<NT, MT, U>& b, const int8_t* 
 template <int MODE, int NT, int MT, int U>
 __device__ __forceinline__ void load_batch(Batch<NT, MT, U>& b, const GemmParams& p,
                                            const int8_t* abase, int tb, int tstride, int t1, int ng,
-                                           uint32_t lane, const uint32_t (&aoff)[MT]) {
+                                           uint32_t lane, const uint32_t (&aoff)[MT][2]) {
   load_batch_w<MODE>(b, p, tb, tstride, t1, ng, lane);
   load_batch_a(b, abase, tb, tstride, t1, aoff);
   // keep every load of the batch ahead of the arithmetic that follows (the scheduler would
@@ -122,12 +122,47 @@ __device__ __forceinline__ void load_batch(Batch<NT, MT, U>& b, const GemmParams
   __builtin_amdgcn_sched_barrier(0);
 }
 
+// Row-major activation fetch.  An MFMA operand wants lane (row l%16, k-block l/16): taken straight from
+// memory that is 16 different rows per quarter wave, 16 cache-line look-ups for 256 bytes, and from
+// nine rows on it shows (8 -> 16 distinct rows: +1.0 us on a 20 us launch).  With `tr` set the batch
+// was loaded row-major instead (lane l: row l/8 of the first or second eight rows, 16-byte chunk l%8:
+// whole 128-byte lines per eight lanes) and each fragment pair takes a round trip through the
+// wave's own 2 KiB of LDS into operand order: chunk c of row r sits in slot c ^ ((r/2)%8), which
+// makes both the row-major writes and the operand-order reads conflict-free.  One wave's LDS
+// accesses are served in order, so no barrier is involved.
+struct ATranspose {
+  int8_t* tr;            // the wave's 2 KiB, or nullptr: fragments are already in operand order
+  uint32_t woff[2], roff[2];
+};
+__device__ __forceinline__ ATranspose make_a_transpose(int8_t* tr, uint32_t lane) {
+  ATranspose t;
+  t.tr = tr;
+  const uint32_t r = lane >> 3, c = lane & 7, nl = lane & 15, kc = lane >> 4;
+  t.woff[0] = r * 128 + ((c ^ ((r >> 1) & 7)) << 4);
+  t.woff[1] = (r + 8) * 128 + ((c ^ (((r + 8) >> 1) & 7)) << 4);
+  t.roff[0] = nl * 128 + ((kc ^ ((nl >> 1) & 7)) << 4);
+  t.roff[1] = nl * 128 + (((4 + kc) ^ ((nl >> 1) & 7)) << 4);
+  return t;
+}
+
 template <int MODE, int NT, int MT, int U>
 __device__ __forceinline__ void consume_batch(const Batch<NT, MT, U>& b, v4i (&acc)[MT][NT], int tb,
-                                              int tstride, int t1, int nl) {
+                                              int tstride, int t1, int nl, const ATranspose& at) {
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     if (tb + tstride * u >= t1) break;
+    v4i a[MT][2];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      a[mt][0] = b.a[u][mt][0];
+      a[mt][1] = b.a[u][mt][1];
+      if (at.tr) {  // wave-uniform
+        *(v4i*)(at.tr + at.woff[0]) = a[mt][0];
+        *(v4i*)(at.tr + at.woff[1]) = a[mt][1];
+        a[mt][0] = *(const v4i*)(at.tr + at.roff[0]);
+        a[mt][1] = *(const v4i*)(at.tr + at.roff[1]);
+      }
+    }
     int sgs[NT] = {};
     if constexpr (MODE != kPerChannel) spread_group_scales<NT, MODE>(b.sgv[u], nl, sgs);
 #pragma unroll
@@ -158,15 +193,14 @@ __device__ __forceinline__ void consume_batch(const Batch<NT, MT, U>& b, v4i (&a
         if constexpr (MODE == kGroupLinear) {
           // the group's partial sum of A*16*code, then (partial/16)*s_g: the same integer as
           // summing A*(code*s_g) because no product saturates when s_g <= 16
-          v4i part =
-              __builtin_amdgcn_mfma_i32_16x16x64_i8(b.a[u][mt][0], b0, (v4i){0, 0, 0, 0}, 0, 0, 0);
-          part = __builtin_amdgcn_mfma_i32_16x16x64_i8(b.a[u][mt][1], b1, part, 0, 0, 0);
+          v4i part = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[mt][0], b0, (v4i){0, 0, 0, 0}, 0, 0, 0);
+          part = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[mt][1], b1, part, 0, 0, 0);
 #pragma unroll
           for (int r = 0; r < 4; ++r)  // |part >> 4| <= 127*8*128 < 2^23 and 0 <= sg <= 16: the full-rate
             acc[mt][i][r] = __mul24(part[r] >> 4, sg) + acc[mt][i][r];  // 24-bit multiply(-add)
         } else {
-          acc[mt][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(b.a[u][mt][0], b0, acc[mt][i], 0, 0, 0);
-          acc[mt][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(b.a[u][mt][1], b1, acc[mt][i], 0, 0, 0);
+          acc[mt][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[mt][0], b0, acc[mt][i], 0, 0, 0);
+          acc[mt][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[mt][1], b1, acc[mt][i], 0, 0, 0);
         }
       }
     }
@@ -190,6 +224,7 @@ __global__ __launch_bounds__(W * 64) void gemm_skinny_kernel(const GemmParams p,
   constexpr int kSmemInts = (FUSED && kFusedLdsBytes / 4 > kRedInts) ? kFusedLdsBytes / 4 : kRedInts;
   __shared__ __attribute__((aligned(16))) int smem[kSmemInts];
   int* const red = smem;
+  __shared__ __attribute__((aligned(16))) int8_t a_tr[FUSED ? 16 : W * 2048];  // see ATranspose
   __shared__ int s_last;
   __shared__ uint32_t s_amax[kFusedMaxM][W];
   __shared__ float s_sa[kFusedMaxM];
@@ -312,10 +347,21 @@ __global__ __launch_bounds__(W * 64) void gemm_skinny_kernel(const GemmParams p,
     for (int i = 0; i < NT; ++i) acc[mt][i] = (v4i){0, 0, 0, 0};
 
   if (t0 + wave < t1) {  // wave-uniform
-    uint32_t aoff[MT];
+    // up to eight rows (and from the fused kernel's LDS copy) the fragments are fetched in operand
+    // order; beyond, row-major with the round trip through LDS
+    const bool row_major = !FUSED && (MT > 1 || M > 8);
+    const ATranspose at = make_a_transpose(row_major ? a_tr + wave * 2048 : nullptr, (uint32_t)lane);
+    uint32_t aoff[MT][2];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-      aoff[mt] = (uint32_t)min(mt * 16 + nl, M - 1) * (uint32_t)p.K + (uint32_t)kc * 16u;
+    for (int mt = 0; mt < MT; ++mt) {
+      if (row_major) {
+        aoff[mt][0] = (uint32_t)min(mt * 16 + (lane >> 3), M - 1) * (uint32_t)p.K + (uint32_t)(lane & 7) * 16u;
+        aoff[mt][1] = (uint32_t)min(mt * 16 + 8 + (lane >> 3), M - 1) * (uint32_t)p.K + (uint32_t)(lane & 7) * 16u;
+      } else {
+        aoff[mt][0] = (uint32_t)min(mt * 16 + nl, M - 1) * (uint32_t)p.K + (uint32_t)kc * 16u;
+        aoff[mt][1] = aoff[mt][0] + 64u;  // second MFMA step of this k-step
+      }
+    }
     int tb = t0 + wave;
     int more = (t1 - tb - 1) / kStep;  // batches after the first
     if constexpr (FUSED) {
@@ -325,35 +371,35 @@ __global__ __launch_bounds__(W * 64) void gemm_skinny_kernel(const GemmParams p,
       load_batch_a(b1, abase, tb + kStep, W, t1, aoff);
       __builtin_amdgcn_sched_barrier(0);
       for (; more >= 3; more -= 2) {  // one basic block: consume a batch, request the one after next
-        consume_batch<MODE>(b0, acc, tb, W, t1, nl);
+        consume_batch<MODE>(b0, acc, tb, W, t1, nl, at);
         load_batch<MODE>(b0, p, abase, tb + 2 * kStep, W, t1, ng, (uint32_t)lane, aoff);
-        consume_batch<MODE>(b1, acc, tb + kStep, W, t1, nl);
+        consume_batch<MODE>(b1, acc, tb + kStep, W, t1, nl, at);
         load_batch<MODE>(b1, p, abase, tb + 3 * kStep, W, t1, ng, (uint32_t)lane, aoff);
         tb += 2 * kStep;
       }
-      consume_batch<MODE>(b0, acc, tb, W, t1, nl);
+      consume_batch<MODE>(b0, acc, tb, W, t1, nl, at);
       if (more == 2) {
         load_batch<MODE>(b0, p, abase, tb + 2 * kStep, W, t1, ng, (uint32_t)lane, aoff);
-        consume_batch<MODE>(b1, acc, tb + kStep, W, t1, nl);
-        consume_batch<MODE>(b0, acc, tb + 2 * kStep, W, t1, nl);
+        consume_batch<MODE>(b1, acc, tb + kStep, W, t1, nl, at);
+        consume_batch<MODE>(b0, acc, tb + 2 * kStep, W, t1, nl, at);
       } else if (more == 1) {
-        consume_batch<MODE>(b1, acc, tb + kStep, W, t1, nl);
+        consume_batch<MODE>(b1, acc, tb + kStep, W, t1, nl, at);
       }
     } else {
       load_batch<MODE>(b0, p, abase, tb, W, t1, ng, (uint32_t)lane, aoff);
       for (; more >= 2; more -= 2) {  // one basic block: load the next batch, consume the current
         load_batch<MODE>(b1, p, abase, tb + kStep, W, t1, ng, (uint32_t)lane, aoff);
-        consume_batch<MODE>(b0, acc, tb, W, t1, nl);
+        consume_batch<MODE>(b0, acc, tb, W, t1, nl, at);
         load_batch<MODE>(b0, p, abase, tb + 2 * kStep, W, t1, ng, (uint32_t)lane, aoff);
-        consume_batch<MODE>(b1, acc, tb + kStep, W, t1, nl);
+        consume_batch<MODE>(b1, acc, tb + kStep, W, t1, nl, at);
         tb += 2 * kStep;
       }
       if (more == 1) {
         load_batch<MODE>(b1, p, abase, tb + kStep, W, t1, ng, (uint32_t)lane, aoff);
-        consume_batch<MODE>(b0, acc, tb, W, t1, nl);
-        consume_batch<MODE>(b1, acc, tb + kStep, W, t1, nl);
+        consume_batch<MODE>(b0, acc, tb, W, t1, nl, at);
+        consume_batch<MODE>(b1, acc, tb + kStep, W, t1, nl, at);
       } else {
-        consume_batch<MODE>(b0, acc, tb, W, t1, nl);
+        consume_batch<MODE>(b0, acc, tb, W, t1, nl, at);
       }
     }
   }
