@@ -8,8 +8,9 @@
 //   <4,1,8>  128 x 256, <4,1,4>  128 x 128, <2,1,4>  64 x 128: narrow tiles for mid-size M, where
 //            a few large tiles would leave most CUs idle
 //
-// Why a DMA ring on gfx950.  The int8 MFMA pipe retires a 32x32x32 tile in 32 clocks, so one
-// k-step (128 k) is 1-2 thousand clocks of MFMA per wave; a global load that misses L2 takes
+// Why a DMA ring on gfx950.  The int8 MFMA pipe retires 32x32x32 (or two 16x16x64) multiply-accumulates
+// in 32 clocks, so one k-step (128 k) is about a thousand clocks of MFMA per wave with the large wave
+// patch; a global load that misses L2 takes
 // several times that.  Registers cannot hold that much prefetch next to the accumulators, but the
 // 160 KiB LDS can: every wave issues the DMA loads for k-step t+2 before it computes k-step t, the
 // loads need no registers, and the only wait is "my DMA of k-step t+1 has landed" right before the
@@ -20,10 +21,11 @@
 // lane l fetches slot l%8 ^ (row/2)%8).  The LDS of gfx950 serves a 128-bit read 16 lanes at a time
 // over 64 banks: the 16 rows such a group reads must land in 16 different 16-byte bank groups, i.e.
 // rows of equal parity need different slots, which (r/2)%8 gives and r%8 does not (rows r and r+8
-// would collide: measured 125 instead of 240 bytes per clock and CU), then each wave's own 2*CT KiB of packed int4 codes exactly as they
-// lie in memory, then (per-group variant) each wave's 32*CT group scales of the k-step.
+// would collide: measured 125 instead of 240 bytes per clock and CU), then each wave's own 2*CT KiB
+// of packed int4 codes exactly as they lie in memory, then (per-group variant) each wave's 32*CT
+// group scales of the k-step.
 // Weights never cross waves: each wave converts its codes to int8 once per k-step (Sec. 3.3.1 /
-// 3.3.2 of the QQQ paper) and feeds MT MFMAs per converted fragment.
+// 3.3.2 of the QQQ paper) and feeds one MFMA per row tile from every converted fragment.
 #include "qqq_prefill_common.h"
 
 // The DMA helpers below name M0 as clobbered (they rewrite it before every use).  M0 is a
