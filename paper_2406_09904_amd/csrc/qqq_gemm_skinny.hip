@@ -21,7 +21,8 @@ template <int NT, int MT, int U>
 struct Batch {
   uint4 w[U][NT];
   v4i a[U][MT][2];
-  int sgv[U];  // the word of the k-step's group scales that holds this lane's scale of tile (lane/16) mod NT
+  int sgv[U][(NT + 3) / 4];  // the words of the k-step's group scales that hold this lane's scales of tiles
+                             // (lane/16) mod NT (and that plus 4 where a workgroup has eight tiles)
 };
 
 // The 16*NT group scales of one k-step of a wave's channel group are 4*NT contiguous words.  Lane
@@ -34,8 +35,8 @@ struct Batch {
 // instructions for four tiles, no scalar broadcasts, no LDS crossbar.
 // (The real-valued variant's scales are fp16: 8*NT words, two scales each.)
 template <int NT, int MODE>
-__device__ __forceinline__ int load_group_scales(const int8_t* gp, uint32_t lane) {
-  const uint32_t tile = (lane >> 4) & (uint32_t)(NT - 1), nl = lane & 15u;
+__device__ __forceinline__ int load_group_scales(const int8_t* gp, uint32_t lane, uint32_t tile0 = 0) {
+  const uint32_t tile = tile0 + ((lane >> 4) & (uint32_t)((NT < 4 ? NT : 4) - 1)), nl = lane & 15u;
   const uint32_t word = MODE == kGroupReal ? 8u * tile + (nl >> 1) : 4u * tile + (nl >> 2);
   return reinterpret_cast<const int*>(gp)[word];
 }
@@ -52,7 +53,7 @@ __device__ __forceinline__ void spread_group_scales(int sgv, int nl, int (&sg)[N
     sg[0] = (int)t[0];
     sg[1] = (int)t[1];
   } else {                         // rows hold tiles 0,1,2,3
-    static_assert(NT == 4, "channel tiles per workgroup");
+    static_assert(NT == 4, "channel tiles per word of scales");
     const auto h = __builtin_amdgcn_permlane32_swap(own, own, false, false);  // rows 0,1,0,1 | 2,3,2,3
     const auto lo = __builtin_amdgcn_permlane16_swap(h[0], h[0], false, false);
     const auto hi = __builtin_amdgcn_permlane16_swap(h[1], h[1], false, false);
@@ -89,9 +90,12 @@ __device__ __forceinline__ void load_batch_w(Batch<NT, MT, U>& b, const GemmPara
       const v4i raw = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(&wt[lane + 64u * i]));
       b.w[u][i] = make_uint4((uint32_t)raw[0], (uint32_t)raw[1], (uint32_t)raw[2], (uint32_t)raw[3]);
     }
-    if constexpr (MODE != kPerChannel)
-      b.sgv[u] = load_group_scales<NT, MODE>(
-          p.s_g + ((int64_t)t * p.N + (int64_t)ng * NT * 16) * (MODE == kGroupReal ? 2 : 1), lane);
+    if constexpr (MODE != kPerChannel) {
+#pragma unroll
+      for (int q = 0; q < (NT + 3) / 4; ++q)
+        b.sgv[u][q] = load_group_scales<NT, MODE>(
+            p.s_g + ((int64_t)t * p.N + (int64_t)ng * NT * 16) * (MODE == kGroupReal ? 2 : 1), lane, 4u * q);
+    }
   }
 }
 
@@ -164,7 +168,21 @@ __device__ __forceinline__ void consume_batch(const Batch<NT, MT, U>& b, v4i (&a
       }
     }
     int sgs[NT] = {};
-    if constexpr (MODE != kPerChannel) spread_group_scales<NT, MODE>(b.sgv[u], nl, sgs);
+    if constexpr (MODE != kPerChannel) {
+      if constexpr (NT <= 4) {
+        spread_group_scales<NT, MODE>(b.sgv[u][0], nl, sgs);
+      } else {  // eight tiles: two words, four tiles each
+        static_assert(NT == 8, "channel tiles per workgroup");
+        int lo4[4], hi4[4];
+        spread_group_scales<4, MODE>(b.sgv[u][0], nl, lo4);
+        spread_group_scales<4, MODE>(b.sgv[u][1], nl, hi4);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          sgs[i] = lo4[i];
+          sgs[4 + i] = hi4[i];
+        }
+      }
+    }
 #pragma unroll
     for (int i = 0; i < NT; ++i) {
       const uint32_t d[4] = {b.w[u][i].x, b.w[u][i].y, b.w[u][i].z, b.w[u][i].w};
@@ -491,6 +509,10 @@ static void choose_split(const GemmParams& p, int mt, int& nt, int& w, int& s) {
   // several row tiles: every workgroup re-reads all activations from L2, so the widest channel
   // group that keeps the CUs busy (rule below) also cuts those re-reads the most
   if (mt >= 2) nt = (p.N % 64 == 0) ? 4 : (p.N % 32 == 0) ? 2 : 1;
+  // up to 32 rows: 128 channels where enough workgroups remain.  Every workgroup reads all activations
+  // from L2 (from 9 rows on a third to two thirds of what it reads of the weights at 64 channels per
+  // workgroup): cfg5 M=16 20.9 -> 20.0 us; with few rows it is level or slightly ahead
+  if (mt <= 2 && p.N % 128 == 0) nt = 8;
   const int cus = num_cus();
   // Measured on MI355X: the widest channel group that still leaves about two workgroups for
   // every three CUs streams best, with 8 waves per workgroup and no K split (no atomics).
@@ -518,7 +540,7 @@ static int launch_mode(const GemmParams& p, hipStream_t st) {
     // fused activation quantisation: one row tile, 8 waves, default batch depth
     if (mt != 1 || p.M > kFusedMaxM || (int64_t)p.M * p.K > kFusedLdsBytes)
       return set_error(QQQ_ERR_SHAPE, "fused decode kernel: M=%d K=%d out of range", p.M, p.K);
-    if (nt == 4) return launch_one<MODE, 4, 1, 8, 1, true>(p, S, st);
+    if (nt >= 4) return launch_one<MODE, 4, 1, 8, 1, true>(p, S, st);
     if (nt == 2) return launch_one<MODE, 2, 1, 8, 2, true>(p, S, st);
     return launch_one<MODE, 1, 1, 8, 4, true>(p, S, st);
   }
@@ -527,11 +549,13 @@ static int launch_mode(const GemmParams& p, hipStream_t st) {
     // or 16 (NT=1) KiB per wave outstanding
     // (measured: the shallow setting streams better on every benchmark shape, so it is the default)
     const bool deep = g_tune_u > 1;
+    if (nt == 8) return launch_w<MODE, 8, 1, 1>(p, w, S, st);
     if (nt == 4) return deep ? launch_w<MODE, 4, 1, 2>(p, w, S, st) : launch_w<MODE, 4, 1, 1>(p, w, S, st);
     if (nt == 2) return deep ? launch_w<MODE, 2, 1, 4>(p, w, S, st) : launch_w<MODE, 2, 1, 2>(p, w, S, st);
     return deep ? launch_w<MODE, 1, 1, 8>(p, w, S, st) : launch_w<MODE, 1, 1, 4>(p, w, S, st);
   }
   if (mt == 2) {
+    if (nt >= 8) return launch_w<MODE, 8, 2, 1>(p, w, S, st);
     if (nt >= 4) return launch_w<MODE, 4, 2, 1>(p, w, S, st);
     if (nt >= 2) return launch_w<MODE, 2, 2, 1>(p, w, S, st);
     return launch_w<MODE, 1, 2, 2>(p, w, S, st);
