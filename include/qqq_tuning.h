@@ -110,7 +110,8 @@ int qqq_set_skinny_tuning(int channel_tiles, int k_slices, int waves, int depth)
  * Tuning/diagnostic knob (host state, not thread-safe) for the prefill path: 0 = automatic;
  * 10 = the DMA-ring kernel, one workgroup per tile, 128x512 tile on 8 waves; 15, 16, 17 = the same
  * kernel with the narrow tiles meant for mid-size M: 128x256 on 8 waves, 128x128 on 4 waves,
- * 64x128 on 4 waves; 13 = the persistent DMA-ring kernel (128x512 tiles, one workgroup per CU).
+ * 64x128 on 4 waves (its ring depth by the launch's workgroup count: six stages when there is at most one
+ * workgroup per CU, else three); 27 = 64x128 with the six-stage ring, 37 = with the three-stage ring; 13 = the persistent DMA-ring kernel (128x512 tiles, one workgroup per CU).
  * Other values act like 0.  Returns 0.
  */
 int qqq_set_prefill_tuning(int tune);

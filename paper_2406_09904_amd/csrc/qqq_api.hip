@@ -53,6 +53,10 @@ static int g_prefill_tune = 0;    // 0 = automatic, see qqq_set_prefill_tuning
 static int g_prefill_ksplit = 0;  // 0 = automatic
 void set_prefill_tuning(int tune) { g_prefill_tune = tune; }
 int get_prefill_tuning() { return g_prefill_tune; }
+// ring depth of the 4-wave per-tile shapes: 0 = by the launch's workgroup count, else forced
+int get_prefill_ring_depth() {
+  return g_prefill_tune == 27 ? 6 : g_prefill_tune == 37 ? 3 : 0;
+}
 void set_prefill_ksplit(int s) { g_prefill_ksplit = s; }
 int get_prefill_ksplit() { return g_prefill_ksplit; }
 
@@ -96,7 +100,7 @@ static size_t split_bytes(int64_t M, int64_t N) {
 struct TileCost { int shape, bm, bn; bool one_per_cu; double alone_us, saturated_us; };
 static const struct DispatchModel {
   TileCost tile[4] = {{0, 128, 512, true, 1.15, 1.33}, {3, 128, 256, true, 0.71, 0.78},
-                      {4, 128, 128, false, 0.63, 0.52}, {5, 64, 128, false, 0.45, 0.275}};
+                      {4, 128, 128, false, 0.63, 0.52}, {5, 64, 128, false, 0.39, 0.275}};
   double tile_fixed_ksteps = 4.0;
   double stream_tbs = 5.0;
   double launch_us = 2.4;
@@ -326,8 +330,8 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
     return rc != QQQ_OK ? rc : launch_splitk_reduce(p, mode, (hipStream_t)stream);
   };
   const int forced_split = get_prefill_ksplit();
-  if (tune == 10 || (tune >= 15 && tune <= 17))
-    return per_tile(tune >= 15 ? tune - 12 : 0, forced_split > 0 ? forced_split : 1);
+  if (tune == 10 || (tune >= 15 && tune <= 17) || tune == 27 || tune == 37)
+    return per_tile(tune >= 15 ? tune % 10 - 2 : 0, forced_split > 0 ? forced_split : 1);
   if (tune == 13) return launch_gemm_prefill_ring(p, mode, (hipStream_t)stream);
   {
     const PrefillPlan plan = plan_prefill(M, N, K, can_split, forced_split);

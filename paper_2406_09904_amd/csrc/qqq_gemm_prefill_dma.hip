@@ -34,11 +34,11 @@
 
 namespace qqq {
 
-template <int MODE, int MT, int CT, int NW>
+template <int MODE, int MT, int CT, int NW, int ST>
 __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const GemmParams p,
                                                                      const int tiles_m,
                                                                      const int tiles_n) {
-  using S = DmaShape<MT, CT, NW>;
+  using S = DmaShape<MT, CT, NW, ST>;
   __shared__ __attribute__((aligned(1024))) int8_t lds[S::kLds];
 
   const int tid = threadIdx.x;
@@ -139,10 +139,12 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
   };
   // DMA loads per wave per k-step
   constexpr int kDmaPerStep = S::kAPieces + S::kWChunks + (MODE != kPerChannel ? 1 : 0);
-  static_assert(kDmaPerStep <= 32, "wait count must fit the vmcnt field with room to spare");
-  // "everything but my newest k-step of DMA has landed, my LDS reads are done", then the barrier
+  // k-steps of DMA in flight behind the one the MFMAs are about to read (ring of ST stages: ST - 2)
+  constexpr int kFlight = ST - 2;
+  static_assert(kFlight * kDmaPerStep <= 48, "wait count must fit the vmcnt field with room to spare");
+  // "everything but my newest k-steps of DMA has landed, my LDS reads are done", then the barrier
   auto wait_all_but_newest_step = [&]() {
-    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(kDmaPerStep) : "memory");
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(kFlight * kDmaPerStep) : "memory");
   };
 
   // ---- MFMA form and fragment layout.
@@ -197,8 +199,8 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
 
   // ---- prologue: k-steps 0 and 1 in flight, wait for step 0.  DMA requests past the last k-step
   // re-fetch the last one (in bounds, never read), which keeps every k-step's wait count the same.
-  issue_dma(0, 0);
-  issue_dma(T > 1 ? 1 : 0, 1);
+#pragma unroll
+  for (int s = 0; s < ST - 1; ++s) issue_dma(s < T ? s : T - 1, s);
 
   // ---- biased per-group route: the conversion adds the constant (8*s_g - 128) to every weight,
   // which sums to sum_g Bc[n][g] * R[m][g] over a row.  The pre-pass stored -R = 128*Rh + Rl, so
@@ -257,6 +259,7 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
 
   int stage = 0;
   if constexpr (!k32) {
+    static_assert(ST == 3, "the slot schedule below is written for the three-stage ring");
     // ---- main loop, 16x16x64 form: a k-step is a fixed sequence of 2*TM slots (k-sub, row tile), TC
     // MFMAs each.  Fragments are read kAhead slots (about 200 clocks of MFMAs) before their MFMAs
     // into a rotating set of registers; the closing wait and barrier of the k-step sit before its
@@ -373,9 +376,9 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
     read_w(lds);
     read_a(a0, lds, 0);
     for (int t = 0; t < T; ++t) {
-      // k-step t+2 goes into the stage that was read during k-step t-1 (everyone is past the
+      // k-step t+ST-1 goes into the stage that was read during k-step t-1 (everyone is past the
       // barrier inside it)
-      issue_dma(t + 2 < T ? t + 2 : T - 1, stage == 0 ? 2 : stage - 1);
+      issue_dma(t + ST - 1 < T ? t + ST - 1 : T - 1, stage == 0 ? ST - 1 : stage - 1);
       const int8_t* sb = lds + stage * S::kStage;
       read_a(a1, sb, 1);
       mfma_step(a0, 0);
@@ -386,10 +389,10 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
       v4i b3[TC];
 #pragma unroll
       for (int c = 0; c < TC; ++c) b3[c] = make_b(c, 3);
-      // my DMA of k-step t+1 has landed (only the loads of k-step t+2 may still be in flight), my
-      // LDS reads of this stage are done; then everyone's
+      // my DMA of k-step t+1 has landed (only the loads of the k-steps after it may still be in
+      // flight), my LDS reads of this stage are done; then everyone's
       wait_all_but_newest_step();
-      stage = (stage == 2) ? 0 : stage + 1;
+      stage = (stage == ST - 1) ? 0 : stage + 1;
       // first LDS reads of k-step t+1 (stale data after the last k-step: read, never used) ...
       const int8_t* nb = lds + stage * S::kStage;
       read_a(a0, nb, 0);
@@ -486,21 +489,21 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
   }
 }
 
-template <int MODE, int MT, int CT, int NW>
+template <int MODE, int MT, int CT, int NW, int ST = 3>
 static int launch_dma(const GemmParams& p, hipStream_t st) {
-  using S = DmaShape<MT, CT, NW>;
+  using S = DmaShape<MT, CT, NW, ST>;
   const int tiles_m = (p.M + S::kBM - 1) / S::kBM;
   const int tiles_n = (p.N + S::kBN - 1) / S::kBN;
   const int64_t grid = (int64_t)tiles_m * tiles_n;
   if (grid > 0x7FFFFFFF) return set_error(QQQ_ERR_SHAPE, "prefill: grid too large");
   if (p.k_splits < 1 || p.k_splits > p.T || p.k_splits > 65535 || (p.k_splits > 1 && !p.part))
     return set_error(QQQ_ERR_SHAPE, "prefill: bad K split %d for %d k-steps", p.k_splits, p.T);
-  hipLaunchKernelGGL((gemm_prefill_dma_kernel<MODE, MT, CT, NW>), dim3((unsigned)grid, (unsigned)p.k_splits),
+  hipLaunchKernelGGL((gemm_prefill_dma_kernel<MODE, MT, CT, NW, ST>), dim3((unsigned)grid, (unsigned)p.k_splits),
                      dim3(NW * 64), 0, st, p, tiles_m, tiles_n);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return set_error(QQQ_ERR_HIP, "prefill gemm launch: %s", hipGetErrorString(e));
-  route_note("prefill per-tile tile=%dx%d waves=%d ksplit=%d mode=%d grid=%lld", S::kBM, S::kBN, NW, p.k_splits,
-             MODE, (long long)grid);
+  route_note("prefill per-tile tile=%dx%d waves=%d ring=%d ksplit=%d mode=%d grid=%lld", S::kBM, S::kBN, NW, ST,
+             p.k_splits, MODE, (long long)grid);
   return QQQ_OK;
 }
 
@@ -545,12 +548,23 @@ int launch_splitk_reduce(const GemmParams& p, int mode, hipStream_t st) {
   return QQQ_OK;
 }
 
+// The 64 x 128 shape comes with two ring depths.  Three stages leave room for three workgroups per
+// CU, which hide each other's memory latency; when the launch has at most one workgroup per CU
+// anyway, a six-stage ring (five k-steps of DMA in flight) hides it instead: 10-13 % on such launches
+// (M=128, K=5120, N=13824: 19.8 -> 17.3 us), 25 % slower where three-stage workgroups would share CUs.
+// (The 128 x 128 shape measured 2 % slower with six stages.)
+static bool lone_workgroups(const GemmParams& p, int bm, int bn) {
+  const int64_t wgs = (int64_t)((p.M + bm - 1) / bm) * ((p.N + bn - 1) / bn) * p.k_splits;
+  const int deep = get_prefill_ring_depth();
+  return deep == 0 ? wgs <= num_cus() : deep > 3;
+}
+
 template <int MODE>
 static int launch_shape(const GemmParams& p, int shape, hipStream_t st) {
   switch (shape) {
     case 3: return launch_dma<MODE, 4, 1, 8>(p, st);
     case 4: return launch_dma<MODE, 4, 1, 4>(p, st);
-    case 5: return launch_dma<MODE, 2, 1, 4>(p, st);
+    case 5: return lone_workgroups(p, 64, 128) ? launch_dma<MODE, 2, 1, 4, 6>(p, st) : launch_dma<MODE, 2, 1, 4>(p, st);
     default: return launch_dma<MODE, 4, 2, 8>(p, st);
   }
 }
@@ -570,10 +584,7 @@ int launch_gemm_prefill_dma(const GemmParams& p, int mode, int shape, hipStream_
     case kGroupReal: return launch_shape<kGroupReal>(p, shape, st);
     case kGroupCvt: return launch_dma<kGroupCvt, 4, 2, 8>(p, st);  // timing ablation: one shape
     case kGroupBias:  // the 8-wave shapes only (the others gain nothing from it)
-      if (shape == 3) return launch_dma<kGroupBias, 4, 1, 8>(p, st);
-      if (shape == 4) return launch_dma<kGroupBias, 4, 1, 4>(p, st);
-      if (shape == 5) return launch_dma<kGroupBias, 2, 1, 4>(p, st);
-      return launch_dma<kGroupBias, 4, 2, 8>(p, st);
+      return launch_shape<kGroupBias>(p, shape, st);
   }
   return set_error(QQQ_ERR_SHAPE, "unknown mode %d", mode);
 }

@@ -75,6 +75,7 @@ int launch_group_bias_prepass(const int8_t* a_q, const int8_t* s_g, int64_t M, i
 void set_skinny_tuning(int nt, int s, int w, int u);
 void set_prefill_tuning(int tune);
 int get_prefill_tuning();
+int get_prefill_ring_depth();
 int launch_gemm_prefill_dma(const GemmParams& p, int mode, int shape, hipStream_t st);
 int launch_gemm_prefill_ring(const GemmParams& p, int mode, hipStream_t st);
 int launch_splitk_reduce(const GemmParams& p, int mode, hipStream_t st);

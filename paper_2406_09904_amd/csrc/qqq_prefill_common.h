@@ -41,9 +41,9 @@ __device__ __forceinline__ v4i convert_b(uint32_t d0, uint32_t d1, int sg) {
   return (v4i){o[0], o[1], o[2], o[3]};
 }
 
-template <int MT, int CT, int NW>
+template <int MT, int CT, int NW, int ST = 3>
 struct DmaShape {
-  static constexpr int kBM = 32 * MT, kBN = NW * 32 * CT, kBK = 128, kStages = 3;
+  static constexpr int kBM = 32 * MT, kBN = NW * 32 * CT, kBK = 128, kStages = ST;
   static constexpr int kAStage = kBM * kBK;           // activations of one k-step
   static constexpr int kWWave = CT * 2048;            // packed codes of one wave and k-step
   static constexpr int kWStage = NW * kWWave;

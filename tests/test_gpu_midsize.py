@@ -63,7 +63,8 @@ def check(acc, y, o_acc, o_y):
     assert ulp_distance(y, o_y).max() <= 1
 
 
-@pytest.mark.parametrize("tune", [15, 16, 17])
+# 27 / 37: the 64x128 shape with its six-stage and its three-stage ring (17 picks by workgroup count)
+@pytest.mark.parametrize("tune", [15, 16, 17, 27, 37])
 @pytest.mark.parametrize("variant,hi,sg_max", [("pc", 0, 0), ("pg", 16, 16), ("pg", 127, 0), ("real", 0, 0)])
 def test_forced_narrow_tiles_on_ragged_shapes(tune, variant, hi, sg_max):
     for (M, K, N) in ((150, 640, 784), (65, 128, 16), (333, 256, 400)):   # ragged in M and N
