@@ -87,14 +87,17 @@ int qqq_set_kernel_override(int family);
 
 /*
  * Tuning/diagnostic knob (host state, not thread-safe): force how the per-group variant turns
- * code x s_g into int8.  0 = automatic (from sg_max and M), 1 = scale applied to each group's
+ * code x s_g into int8.  0 = automatic (from sg_max, M and a cost model), 1 = scale applied to each group's
  * partial sum (valid for s_g <= 16), 2 = per-weight saturating conversion (any s_g),
  * 3 = per-weight fp16 FMA conversion without saturation (valid for s_g <= 16).  Values 1-3 act on
  * qqq_gemm_w4a8_pergroup / qqq_linear_w4a8_pergroup (3 also keeps the prefill kernels off their
  * default integer route).  4 acts on qqq_gemm_w4a8_pergroup_f16scale on the prefill path only and exists
  * to be timed (the ablation of Sec. 4.5.2, Fig. 9): fp16 multiply, conventional round and
  * fp16->int16 conversion instructions, byte packing; two roundings, so it equals the default route
- * only where code*s is exact in fp16.  Returns the previous value.
+ * only where code*s is exact in fp16.  5 = the prefill kernels' biased integer route (byte-wise multiply
+ * of code + 8, the constant taken out through a pre-pass; valid for s_g <= 16) wherever it applies, also on the
+ * short launches where the automatic choice skips its pre-pass and converts with the fp16 FMA.  Returns the
+ * previous value.
  */
 int qqq_set_group_mode_override(int mode);
 

@@ -93,9 +93,13 @@ static size_t split_bytes(int64_t M, int64_t N) {
 //                 unsplit launch is given up: set so that on a 72-case grid no pick lost more than
 //                 13 % against the best forced choice.
 //   decode_*      time of the decode kernel for 17..64 rows: decode_base_us + c(M) * N*K/1e6 with
-//                 c linear in M per channel-group width (fit over M = 17..64 on the six layers).
-//   pergroup_*    the per-group prefill conversion relative to per-channel (per k-step factor)
-//                 and its pre-pass launch.
+//                 c linear in M per channel-group width, the width being the launcher's own choice
+//                 (fit over M = 17..64 on the six layers plus 8192 x 8192, 5120 x 5120).
+//   pergroup_*    the per-group prefill GEMM relative to the per-channel one of the same shape, for
+//                 its two clamp-free conversions: the biased integer route (a factor on the time
+//                 plus its pre-pass launch and per-tile correction) and the fp16-FMA route (a larger
+//                 factor, nothing else); fitted on ten shapes from M=64 to 1024, they cross where
+//                 the per-channel GEMM takes about 33 us.
 // A test times the automatic pick against every forced pick on a small grid (15 % bar).
 struct TileCost { int shape, bm, bn; bool one_per_cu; double alone_us, saturated_us; };
 static const struct DispatchModel {
@@ -108,11 +112,12 @@ static const struct DispatchModel {
   double margin_split = 0.88, margin_leave_large_tile = 0.95;
   int min_ksteps_per_split = 4;
   double decode_base_us = 5.0;
-  double decode_c64_lo[2] = {0.038, 0.0015}, decode_c64_hi[2] = {0.045, 0.0017};  // 64-channel groups: M <= 32, M > 32
-  double decode_c32_lo[2] = {0.04, 0.0031}, decode_c32_hi[2] = {0.12, 0.0023};    // 32-channel groups
-  double decode_few_groups = 1.25;           // fewer channel groups than CUs
+  double decode_c64_lo[2] = {0.038, 0.0015}, decode_c64_hi[2] = {0.045, 0.0017};  // 64- and 128-channel groups: M <= 32, M > 32
+  double decode_c32_lo[2] = {0.06, 0.0008}, decode_c32_hi[2] = {0.093, 0.0007};   // 32-channel groups
+  double decode_c16_lo[2] = {0.04, 0.0031}, decode_c16_hi[2] = {0.12, 0.0023};    // 16-channel groups
   double prefill_wins_by = 0.92;             // the prefill path must be this much cheaper at 17..64 rows
-  double pergroup_kstep_factor = 1.3, pergroup_prepass_us = 7.5, perchannel_extra_us = 2.5;
+  double pergroup_bias_factor = 1.13, pergroup_prepass_us = 7.5, pergroup_fma_factor = 1.36;
+  double perchannel_extra_us = 2.5;
 } kModel;
 
 // Tile shape and K split of the per-tile prefill kernel from the model: few rows want many small
@@ -165,6 +170,17 @@ static PrefillPlan plan_prefill(int64_t M, int64_t N, int64_t K, bool can_split,
   return best;
 }
 
+// Modelled time of the clamp-free per-group prefill GEMM and which conversion gives it: the biased integer
+// route pays a pre-pass launch, the fp16-FMA route more per k-step, so short launches take the latter.
+static double pergroup_prefill_us(const PrefillPlan& plan, int64_t M, int64_t N, bool* bias_route) {
+  const double reduce_us = plan.k_splits > 1 ? reduce_cost_us(plan.k_splits, M, N) : 0.0;
+  const double core = plan.us - reduce_us;
+  const double bias = core * kModel.pergroup_bias_factor + kModel.pergroup_prepass_us + reduce_us;
+  const double fma = core * kModel.pergroup_fma_factor + reduce_us;
+  if (bias_route) *bias_route = bias < fma;
+  return bias < fma ? bias : fma;
+}
+
 // Kernel family of a call: 1 = decode (split-K) kernel, 2 = prefill kernels.  Up to 16 rows the
 // decode kernel streams the weights at memory speed; beyond 64 it does not apply.  In between it
 // re-reads the activations once per 32 or 64 channels and its time grows with M, while the prefill
@@ -174,21 +190,17 @@ static int kernel_family(int64_t M, int64_t N, int64_t K, bool pergroup) {
   if (M <= kDecodeAlwaysMaxM) return 1;
   if (M > kSkinnyMaxM) return 2;
   const double nk = (double)N * (double)K * 1e-6;
-  double c;
-  if (N % 64 == 0 && (N / 64) * 3 >= 2 * num_cus()) {  // 64-channel groups (the launcher's own rule)
-    const double* f = M <= 32 ? kModel.decode_c64_lo : kModel.decode_c64_hi;
-    c = f[0] + f[1] * (double)M;
-  } else {                                               // 32-channel groups
-    const double* f = M <= 32 ? kModel.decode_c32_lo : kModel.decode_c32_hi;
-    c = f[0] + f[1] * (double)M;
-    if (N / 32 < num_cus()) c *= kModel.decode_few_groups;
-  }
+  const int nt = decode_channel_tiles(N, (int)((M + 15) / 16));  // the launcher's own rule
+  const double* f = nt >= 4 ? (M <= 32 ? kModel.decode_c64_lo : kModel.decode_c64_hi)
+                  : nt == 2 ? (M <= 32 ? kModel.decode_c32_lo : kModel.decode_c32_hi)
+                            : (M <= 32 ? kModel.decode_c16_lo : kModel.decode_c16_hi);
+  double c = f[0] + f[1] * (double)M;
+  // 16-channel groups in more than one round of workgroups: the last round counts as a whole one
+  const int64_t wgs = N / (16 * nt), cus = num_cus();
+  if (nt == 1 && wgs > cus) c *= (double)((wgs + cus - 1) / cus) * (double)cus / (double)wgs;
   const double decode_us = kModel.decode_base_us + c * nk;
   const PrefillPlan plan = plan_prefill(M, N, K, true, g_prefill_ksplit);
-  const double reduce_us = plan.k_splits > 1 ? reduce_cost_us(plan.k_splits, M, N) : 0.0;
-  const double prefill_us = pergroup ? (plan.us - reduce_us) * kModel.pergroup_kstep_factor + reduce_us +
-                                           kModel.pergroup_prepass_us
-                                     : plan.us + kModel.perchannel_extra_us;
+  const double prefill_us = pergroup ? pergroup_prefill_us(plan, M, N, nullptr) : plan.us + kModel.perchannel_extra_us;
   return prefill_us < kModel.prefill_wins_by * decode_us ? 2 : 1;
 }
 
@@ -349,8 +361,13 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
 
 static bool takes_bias_route(int mode, int64_t M, int64_t N, int64_t K) {
   // (the workspace holds the pre-pass buffers only above the rows that always take the decode kernel)
-  return mode == kGroupFused && M > kDecodeAlwaysMaxM && g_group_mode == 0 &&
-         kernel_family(M, N, K, true) == 2;
+  if (!(mode == kGroupFused && M > kDecodeAlwaysMaxM && (g_group_mode == 0 || g_group_mode == 5) &&
+        kernel_family(M, N, K, true) == 2))
+    return false;
+  if (g_group_mode == 5) return true;  // forced
+  bool bias = true;
+  pergroup_prefill_us(plan_prefill(M, N, K, true, g_prefill_ksplit), M, N, &bias);
+  return bias;
 }
 
 static bool fused_ok(int64_t M, int64_t K) {
@@ -527,7 +544,7 @@ int qqq_quantize_w4_pergroup(const void* w_fp16, int64_t N, int64_t K, int64_t l
 
 int qqq_set_group_mode_override(int mode) {
   const int old = g_group_mode;
-  if (mode >= 0 && mode <= 4) g_group_mode = mode;
+  if (mode >= 0 && mode <= 5) g_group_mode = mode;
   return old;
 }
 

@@ -503,20 +503,24 @@ static int launch_w(const GemmParams& p, int W, int S, hipStream_t st) {
 }
 
 // Shape of the launch: channel tiles per workgroup (nt), waves per workgroup (w), K slices (s).
-static void choose_split(const GemmParams& p, int mt, int& nt, int& w, int& s) {
-  nt = 1;
-  if (mt == 1) nt = (p.N % 64 == 0) ? 4 : (p.N % 32 == 0) ? 2 : 1;
-  // several row tiles: every workgroup re-reads all activations from L2, so the widest channel
-  // group that keeps the CUs busy (rule below) also cuts those re-reads the most
-  if (mt >= 2) nt = (p.N % 64 == 0) ? 4 : (p.N % 32 == 0) ? 2 : 1;
+// 16-channel tiles per workgroup for N channels and mt row tiles (also read by the dispatch model)
+int decode_channel_tiles(int64_t N, int mt) {
+  int nt = (N % 64 == 0) ? 4 : (N % 32 == 0) ? 2 : 1;
+  // (with several row tiles every workgroup re-reads all activations from L2, so the widest channel
+  // group that keeps the CUs busy, rule below, also cuts those re-reads the most)
   // up to 32 rows: 128 channels where enough workgroups remain.  Every workgroup reads all activations
   // from L2 (from 9 rows on a third to two thirds of what it reads of the weights at 64 channels per
   // workgroup): cfg5 M=16 20.9 -> 20.0 us; with few rows it is level or slightly ahead
-  if (mt <= 2 && p.N % 128 == 0) nt = 8;
-  const int cus = num_cus();
+  if (mt <= 2 && N % 128 == 0) nt = 8;
   // Measured on MI355X: the widest channel group that still leaves about two workgroups for
   // every three CUs streams best, with 8 waves per workgroup and no K split (no atomics).
-  while (nt > 1 && (int64_t)(p.N / (16 * nt)) * 3 < 2 * cus) nt >>= 1;
+  while (nt > 1 && (N / (16 * nt)) * 3 < 2 * (int64_t)num_cus()) nt >>= 1;
+  return nt;
+}
+
+static void choose_split(const GemmParams& p, int mt, int& nt, int& w, int& s) {
+  nt = decode_channel_tiles(p.N, mt);
+  const int cus = num_cus();
   w = (p.T >= 16) ? 8 : 4;
   // a workgroup with 32 KiB of weights or less (16 channels, K <= 4096) finishes sooner on 4 waves, each with
   // two batches of loads, than on 8 with one and twice the partial tiles to add (K = N = 4096, M=16: 4.85 -> 4.7 us

@@ -94,6 +94,21 @@ def test_linear_pergroup(M, K, N, hi, sg_max):
     assert np.array_equal(acc, acc2) and np.array_equal(y, y2)
 
 
+@pytest.mark.parametrize("M,K,N", [(70, 1024, 512), (200, 384, 528), (130, 2560, 1040)])
+def test_linear_pergroup_biased_route_on_short_launches(M, K, N):
+    """The biased integer conversion forced where the automatic choice would skip its pre-pass: the
+    quantiser writes the per-group row sums the correction needs."""
+    a = synth.activations_fp16(M, K, 19 * M + K + N)
+    w = synth.random_w_nat(N, K, 7 + N)
+    s_g = synth.group_scales(K, N, 8 + N, 1, 16)
+    s_w = synth.weight_scales_fp16(N, 9 + N, 0.001, 0.005)
+    o_acc, o_y = oracle_linear(a, w, s_w, s_g)
+    qqq.set_group_mode_override(5)
+    acc, y = run_linear(a, w, s_w, K, s_g=s_g, sg_max=16)
+    assert "mode=5" in qqq.last_route(), qqq.last_route()
+    check(acc, y, o_acc, o_y)
+
+
 @pytest.mark.parametrize("group_mode", [1, 2, 3])
 def test_linear_fused_every_group_route(group_mode):
     M, K, N = 3, 2560, 336            # fused: 7680 activations

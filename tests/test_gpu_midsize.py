@@ -20,6 +20,7 @@ def _reset():
     yield
     qqq.set_prefill_tuning(0)
     qqq.set_prefill_ksplit(0)
+    qqq.set_group_mode_override(0)
 
 
 def run(variant, a_q, s_a, w_nat, s_w, K, s_g=None, sg_max=0):
@@ -31,8 +32,13 @@ def run(variant, a_q, s_a, w_nat, s_w, K, s_g=None, sg_max=0):
     d_a, d_sa = to_dev(a_q, torch), to_dev(s_a, torch)
     if variant == "pc":
         y = qqq.qqq_gemm_w4a8_perchannel(d_a, d_sa, d_w, d_sw, ws, acc_out=acc)
-    elif variant == "pg":
+    elif variant in ("pg", "pgb"):
+        if variant == "pgb":   # the biased integer route, also where the automatic choice would skip its pre-pass
+            qqq.set_group_mode_override(5)
         y = qqq.qqq_gemm_w4a8_pergroup(d_a, d_sa, d_w, to_dev(s_g, torch), d_sw, ws, sg_max=sg_max, acc_out=acc)
+        if variant == "pgb":
+            assert "mode=5" in qqq.last_route(), qqq.last_route()
+            qqq.set_group_mode_override(0)
     else:
         y = qqq.qqq_gemm_w4a8_pergroup_f16scale(d_a, d_sa, d_w, to_dev(s_g, torch), d_sw, ws, acc_out=acc)
     torch.cuda.synchronize()
@@ -43,7 +49,7 @@ def reference(variant, a_q, s_a, w, s_w, K, N, seed, hi=16):
     if variant == "pc":
         s_g = None
         o_acc, _, o_y = orc.gemm_perchannel(a_q, s_a, w, s_w.view(np.uint16))
-    elif variant == "pg":
+    elif variant in ("pg", "pgb"):
         s_g = synth.group_scales(K, N, seed, 1, hi)
         o_acc, _, o_y = orc.gemm_pergroup(a_q, s_a, w, s_g, s_w.view(np.uint16))
     else:
@@ -65,7 +71,7 @@ def check(acc, y, o_acc, o_y):
 
 # 27 / 37: the 64x128 shape with its six-stage and its three-stage ring (17 picks by workgroup count)
 @pytest.mark.parametrize("tune", [15, 16, 17, 27, 37])
-@pytest.mark.parametrize("variant,hi,sg_max", [("pc", 0, 0), ("pg", 16, 16), ("pg", 127, 0), ("real", 0, 0)])
+@pytest.mark.parametrize("variant,hi,sg_max", [("pc", 0, 0), ("pg", 16, 16), ("pgb", 16, 16), ("pg", 127, 0), ("real", 0, 0)])
 def test_forced_narrow_tiles_on_ragged_shapes(tune, variant, hi, sg_max):
     for (M, K, N) in ((150, 640, 784), (65, 128, 16), (333, 256, 400)):   # ragged in M and N
         a_q, s_a, w, s_w = inputs(M, K, N, M + K + N)
@@ -77,7 +83,7 @@ def test_forced_narrow_tiles_on_ragged_shapes(tune, variant, hi, sg_max):
 # automatic choice: 64x128 tiles, 128x128, 128x256, and the large tile
 @pytest.mark.parametrize("M,K,N", [(96, 1024, 4096), (128, 640, 13824), (200, 512, 11008),
                                    (512, 384, 13824), (1024, 256, 8192), (1000, 256, 2064)])
-@pytest.mark.parametrize("variant", ["pc", "pg", "real"])
+@pytest.mark.parametrize("variant", ["pc", "pg", "pgb", "real"])
 def test_automatic_choice(M, K, N, variant):
     a_q, s_a, w, s_w = inputs(M, K, N, M + K + N + 1)
     s_g, o_acc, o_y = reference(variant, a_q, s_a, w, s_w, K, N, 9, 15)
@@ -85,7 +91,7 @@ def test_automatic_choice(M, K, N, variant):
 
 
 @pytest.mark.parametrize("tune,k_splits", [(15, 2), (16, 3), (17, 2), (17, 5), (10, 2), (17, 8)])
-@pytest.mark.parametrize("variant,hi,sg_max", [("pc", 0, 0), ("pg", 16, 16), ("pg", 127, 0), ("real", 0, 0)])
+@pytest.mark.parametrize("variant,hi,sg_max", [("pc", 0, 0), ("pg", 16, 16), ("pgb", 16, 16), ("pg", 127, 0), ("real", 0, 0)])
 def test_forced_k_split(tune, k_splits, variant, hi, sg_max):
     """K ranges of unequal length (k-steps not divisible by the split), ragged M and N, every
     conversion route; the biased per-group route puts its whole correction into the first split."""
@@ -130,7 +136,7 @@ def test_automatic_k_split_on_a_long_k_narrow_n_layer(variant):
     assert ulp_distance(y[im, jn], o_y).max() <= 1
 
 
-@pytest.mark.parametrize("variant,hi,sg_max", [("pc", 0, 0), ("pg", 16, 16), ("pg", 127, 0), ("real", 0, 0)])
+@pytest.mark.parametrize("variant,hi,sg_max", [("pc", 0, 0), ("pg", 16, 16), ("pgb", 16, 16), ("pg", 127, 0), ("real", 0, 0)])
 def test_forced_persistent_kernel(variant, hi, sg_max):
     """The persistent kernel (one workgroup per CU walking its tiles) on shapes with fewer tiles than
     CUs, ragged edges, K at its minimum of three k-steps; every element against the oracle.  The
