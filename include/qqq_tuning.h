@@ -16,10 +16,10 @@ extern "C" {
 
 /*
  * Which kernels the most recent GEMM or linear call of the calling thread enqueued, as a short
- * host string (never NULL), e.g. "decode nt=4 mt=1 waves=8 depth=1 kslices=1 fused=1 mode=0" or
- * "prefill persistent mode=0 tiles=7168 grid=256" or "prefill per-tile shape=5 ksplit=4 mode=5 +
- * reduce"; a preceding "quant_act + " or "group-bias pre-pass + " names the other launches of the
- * call.  For benchmarks and tests that must know which route they measured or compared.
+ * host string (never NULL), e.g. "decode nt=4 mt=1 waves=8 depth=1 kslices=1 fused=1 mode=0 grid=448" or
+ * "prefill persistent tile=128x512 mode=0 tiles=1792 grid=256" or "prefill per-tile tile=64x128 waves=4
+ * ring=6 ksplit=4 mode=5 grid=64 + k-split reduce"; a preceding "quant_act + " or "group-bias pre-pass + "
+ * names the other launches of the call.  For benchmarks and tests that must know which route they measured or compared.
  */
 const char* qqq_last_route(void);
 

@@ -349,11 +349,13 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
     const PrefillPlan plan = plan_prefill(M, N, K, can_split, forced_split);
     if (plan.shape != 0 || plan.k_splits > 1) return per_tile(plan.shape, plan.k_splits);
     if (mode == kGroupReal) return launch_gemm_prefill_dma(p, mode, 0, (hipStream_t)stream);
-    // Measured on MI355X: the persistent kernel is level with the per-tile one for the per-channel
-    // variant and 1-7 % ahead for the per-group variant whenever a CU walks more than one tile
-    // (the next tile's first k-steps load under the epilogue).
+    // Measured on MI355X (two boxes, 14 shapes with M >= 1024, both kernels in one process): with 64 k-steps
+    // or more the per-tile kernel is 2-6 % ahead for the per-channel variant and 1-3 % for the per-group one
+    // (K = 8192: 636 against 660 us on the 28672-channel layer; K = 21760: 455 against 483); with shorter K the
+    // persistent kernel is level or up to 2 % ahead whenever a CU walks more than one tile (the next tile's
+    // first k-steps load under the epilogue).
     const bool tiles_repeat = tiles > num_cus();
-    if (mode == kPerChannel || tiles_repeat)
+    if (p.T < 64 && (mode == kPerChannel || tiles_repeat))
       return launch_gemm_prefill_ring(p, mode, (hipStream_t)stream);
     return launch_gemm_prefill_dma(p, mode, 0, (hipStream_t)stream);
   }

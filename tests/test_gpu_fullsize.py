@@ -74,8 +74,9 @@ def test_full_size_workload(name):
         y = qqq.qqq_gemm_w4a8_perchannel(d_q, d_sa, d_w, d_sw, ws, acc_out=acc)
     route = qqq.last_route()
     print("%s: %s" % (name, route), flush=True)
-    if not pg and M >= 2048:     # the launch bench.py times there: several tiles per CU, one cursor
-        assert "prefill persistent" in route, route
+    if not pg and M >= 2048:     # the launch bench.py times there: several 128 x 512 tiles per CU, walked by the
+        # persistent kernel (one DMA cursor across tile borders) below 64 k-steps and tile by tile from there on
+        assert ("prefill persistent" in route) == (K < 8192) and "128x512" in route, route
     torch.cuda.synchronize()
 
     o_q, o_sa = orc.quant_act(a.view(np.uint16))
