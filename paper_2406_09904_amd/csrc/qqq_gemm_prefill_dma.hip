@@ -583,8 +583,7 @@ int launch_gemm_prefill_dma(const GemmParams& p, int mode, int shape, hipStream_
     case kGroupFused: return launch_shape<kGroupFused>(p, shape, st);
     case kGroupReal: return launch_shape<kGroupReal>(p, shape, st);
     case kGroupCvt: return launch_dma<kGroupCvt, 4, 2, 8>(p, st);  // timing ablation: one shape
-    case kGroupBias:  // the 8-wave shapes only (the others gain nothing from it)
-      return launch_shape<kGroupBias>(p, shape, st);
+    case kGroupBias: return launch_shape<kGroupBias>(p, shape, st);
   }
   return set_error(QQQ_ERR_SHAPE, "unknown mode %d", mode);
 }
