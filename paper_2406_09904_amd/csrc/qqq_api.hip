@@ -372,8 +372,13 @@ static bool takes_bias_route(int mode, int64_t M, int64_t N, int64_t K) {
   return bias;
 }
 
-static bool fused_ok(int64_t M, int64_t K) {
-  return g_override == 0 && g_fuse_quant && M >= 1 && M <= kFusedMaxM && M * K <= kFusedLdsBytes;
+// One launch that quantises and multiplies.  Every workgroup quantises all M rows for itself, which a
+// second launch (3.3-3.7 us) costs more than: always up to 8192 activations, up to 32768 with two rows, and
+// with three or four rows on the large layers only (measured on five layers: M=2 0.9-2.6 us ahead everywhere;
+// M=4 1.2 us ahead on 8192 x 28672, 0.3-1.0 us behind on the layers of 70 M weights and less).
+static bool fused_ok(int64_t M, int64_t N, int64_t K) {
+  if (!(g_override == 0 && g_fuse_quant && M >= 1 && M <= kFusedMaxM && M * K <= kFusedLdsBytes)) return false;
+  return M * K <= kFusedLdsSmall || M <= 2 || (double)N * (double)K >= 1.5e8;
 }
 
 // quant_act followed by the GEMM; for a few decode rows a single launch that does both
@@ -393,7 +398,7 @@ static int linear_common(const void* a_fp16, int64_t lda, const void* w_packed, 
   if (workspace_bytes < need)
     return set_error(QQQ_ERR_WORKSPACE, "linear: workspace %zu bytes < %zu needed", workspace_bytes, need);
   const size_t gemm_ws = align256(qqq_gemm_workspace_bytes(M, N, K));
-  if (fused_ok(M, K))
+  if (fused_ok(M, N, K))
     return gemm_common(nullptr, nullptr, w_packed, s_g, s_w, y, acc_out, M, N, K, workspace, gemm_ws,
                        stream, mode, a_fp16, lda);
   float* s_a = (float*)((char*)workspace + gemm_ws);

@@ -229,7 +229,7 @@ __device__ __forceinline__ void consume_batch(const Batch<NT, MT, U>& b, v4i (&a
 // scale, division, round half to even) into LDS before the k-loop, with the arithmetic of the
 // stand-alone pass, so a decode step is a single launch.  Every workgroup repeats the M*K
 // conversions, which is only worth it for a few rows; the A operands then come from LDS.
-template <int MODE, int NT, int MT, int W, int U, bool FUSED>
+template <int MODE, int NT, int MT, int W, int U, int FUSED>
 __global__ __launch_bounds__(W * 64) void gemm_skinny_kernel(const GemmParams p, const int NG,
                                                              const int S) {
   constexpr int kTiles = MT * NT;
@@ -239,7 +239,9 @@ __global__ __launch_bounds__(W * 64) void gemm_skinny_kernel(const GemmParams p,
   // one LDS buffer: the quantised activations during the k-loop (FUSED), the waves' partial
   // tiles after it
   constexpr int kRedInts = W * kElems;
-  constexpr int kSmemInts = (FUSED && kFusedLdsBytes / 4 > kRedInts) ? kFusedLdsBytes / 4 : kRedInts;
+  // FUSED: 0 = no, 1 = up to kFusedLdsSmall activations (M*K), 2 = up to kFusedLdsBytes
+  constexpr int kFusedBytes = FUSED == 2 ? kFusedLdsBytes : kFusedLdsSmall;
+  constexpr int kSmemInts = (FUSED && kFusedBytes / 4 > kRedInts) ? kFusedBytes / 4 : kRedInts;
   __shared__ __attribute__((aligned(16))) int smem[kSmemInts];
   int* const red = smem;
   __shared__ __attribute__((aligned(16))) int8_t a_tr[FUSED ? 16 : W * 2048];  // see ATranspose
@@ -282,9 +284,9 @@ __global__ __launch_bounds__(W * 64) void gemm_skinny_kernel(const GemmParams p,
   Batch<NT, MT, U> b0, b1;
   const int8_t* abase = p.a_q;
   if constexpr (FUSED) {
-    // host guarantees M <= kFusedMaxM and M*K <= kFusedLdsBytes
-    constexpr int kVPT = kFusedLdsBytes / 8 / kThreads;  // 128-bit fp16 vectors per thread
-    static_assert(kVPT >= 1 && kVPT * kThreads * 8 == kFusedLdsBytes, "fused path sized for 8 waves");
+    // host guarantees M <= kFusedMaxM and M*K <= kFusedBytes
+    constexpr int kVPT = kFusedBytes / 8 / kThreads;  // 128-bit fp16 vectors per thread
+    static_assert(kVPT >= 1 && kVPT * kThreads * 8 == kFusedBytes, "fused path sized for 8 waves");
     const int nvec = p.K >> 3;  // 128-bit vectors of 8 fp16 per row
     const int total = M * nvec;
     uint2* const aq_lds = reinterpret_cast<uint2*>(smem);
@@ -480,7 +482,7 @@ void set_skinny_tuning(int nt, int s, int w, int u) {
   g_tune_u = u;
 }
 
-template <int MODE, int NT, int MT, int W, int U, bool FUSED = false>
+template <int MODE, int NT, int MT, int W, int U, int FUSED = 0>
 static int launch_one(const GemmParams& p, int S, hipStream_t st) {
   const int NG = p.N / (16 * NT);
   const int64_t grid = (int64_t)NG * S;
@@ -489,7 +491,7 @@ static int launch_one(const GemmParams& p, int S, hipStream_t st) {
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return set_error(QQQ_ERR_HIP, "skinny gemm launch: %s", hipGetErrorString(e));
   route_note("decode nt=%d mt=%d waves=%d depth=%d kslices=%d fused=%d mode=%d grid=%lld", NT, MT, W, U, S,
-             (int)FUSED, MODE, (long long)grid);
+             FUSED ? 1 : 0, MODE, (long long)grid);
   return QQQ_OK;
 }
 
@@ -548,9 +550,15 @@ static int launch_mode(const GemmParams& p, hipStream_t st) {
     // fused activation quantisation: one row tile, 8 waves, default batch depth
     if (mt != 1 || p.M > kFusedMaxM || (int64_t)p.M * p.K > kFusedLdsBytes)
       return set_error(QQQ_ERR_SHAPE, "fused decode kernel: M=%d K=%d out of range", p.M, p.K);
-    if (nt >= 4) return launch_one<MODE, 4, 1, 8, 1, true>(p, S, st);
-    if (nt == 2) return launch_one<MODE, 2, 1, 8, 2, true>(p, S, st);
-    return launch_one<MODE, 1, 1, 8, 4, true>(p, S, st);
+    // two sizes of the quantising prologue: every thread loads (and holds) its share of the larger one
+    if ((int64_t)p.M * p.K <= kFusedLdsSmall) {
+      if (nt >= 4) return launch_one<MODE, 4, 1, 8, 1, 1>(p, S, st);
+      if (nt == 2) return launch_one<MODE, 2, 1, 8, 2, 1>(p, S, st);
+      return launch_one<MODE, 1, 1, 8, 4, 1>(p, S, st);
+    }
+    if (nt >= 4) return launch_one<MODE, 4, 1, 8, 1, 2>(p, S, st);
+    if (nt == 2) return launch_one<MODE, 2, 1, 8, 2, 2>(p, S, st);
+    return launch_one<MODE, 1, 1, 8, 4, 2>(p, S, st);
   }
   if (mt <= 1) {
     // k-steps per batch of loads: two batches are in flight, so "deep" keeps 4 (NT=4), 8 (NT=2)

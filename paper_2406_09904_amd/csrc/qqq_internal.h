@@ -84,7 +84,8 @@ void set_prefill_ksplit(int s);
 int get_prefill_ksplit();
 
 constexpr int kFusedMaxM = 4;          // rows the decode kernel quantises itself (fused path)
-constexpr int kFusedLdsBytes = 8192;   // most activations the fused path quantises: M*K int8 in LDS
+constexpr int kFusedLdsBytes = 32768;  // most activations the fused path quantises: M*K int8 in LDS
+constexpr int kFusedLdsSmall = 8192;   // the smaller of its two prologue sizes
 constexpr int kSkinnyMaxM = 64;  // rows the split-K kernel handles (4 MFMA row tiles)
 // rows up to which the decode kernel is always the automatic choice; from there to kSkinnyMaxM a
 // cost model decides between it and the prefill path's 64-row tiles (which read every activation

@@ -59,7 +59,7 @@ def check(acc, y, o_acc, o_y):
     assert d.max() <= 1, "fp16 output off by %d ulp" % int(d.max())
 
 
-# M <= 4 with M*K <= 8192 takes the fused kernel; the rest the two-kernel route
+# M <= 4 with M*K <= 8192, and M <= 2 with M*K <= 32768, take the fused kernel; the rest the two-kernel route
 SHAPES = [(1, 128, 16), (1, 4096, 1024), (2, 1152, 272), (3, 2688, 208), (4, 2048, 4096),
           (1, 8192, 48), (1, 5120, 13824), (2, 4096, 32), (2, 4224, 64), (1, 8320, 64),
           (3, 5120, 208), (1, 65536, 48), (5, 1024, 256), (16, 4096, 512), (70, 1024, 512),
@@ -107,6 +107,24 @@ def test_linear_pergroup_biased_route_on_short_launches(M, K, N):
     acc, y = run_linear(a, w, s_w, K, s_g=s_g, sg_max=16)
     assert "mode=5" in qqq.last_route(), qqq.last_route()
     check(acc, y, o_acc, o_y)
+
+
+@pytest.mark.parametrize("M,K,N", [(4, 8192, 18432), (3, 6144, 24576), (2, 16384, 64), (1, 32768, 48)])
+@pytest.mark.parametrize("pergroup", [False, True])
+def test_linear_fused_large_prologue(M, K, N, pergroup):
+    """The fused kernel's larger prologue (up to 32768 activations): two rows anywhere, three and four on
+    layers of 150 M weights and more."""
+    a = synth.activations_fp16(M, K, 23 * M + K + N)
+    w = synth.random_w_nat(N, K, 11 + N)
+    s_w = synth.weight_scales_fp16(N, 12 + N, 0.001, 0.005)
+    s_g = synth.group_scales(K, N, 13 + N, 1, 16) if pergroup else None
+    o_acc, o_y = oracle_linear(a, w, s_w, s_g)
+    acc, y = run_linear(a, w, s_w, K, s_g=s_g, sg_max=16)
+    assert "fused=1" in qqq.last_route(), qqq.last_route()
+    check(acc, y, o_acc, o_y)
+    acc2, y2 = run_linear(a, w, s_w, K, s_g=s_g, sg_max=16, fused=0)
+    assert "fused=0" in qqq.last_route(), qqq.last_route()
+    assert np.array_equal(acc, acc2) and np.array_equal(y, y2)
 
 
 @pytest.mark.parametrize("group_mode", [1, 2, 3])
