@@ -164,7 +164,7 @@ int qqq_gemm_w4a8_pergroup_f16scale(const int8_t* a_q, const float* s_a, const v
  * Linear layer in one call (Sec. 4.1 per-token activation quantisation feeding Sec. 3.3's W4A8
  * GEMM): the result is exactly that of qqq_quant_act followed by qqq_gemm_w4a8_perchannel /
  * qqq_gemm_w4a8_pergroup on the same inputs (acc_out bit-identical, y_fp16 bit-identical).
- * For a few decode rows (M <= 4 and M*K <= 8192; two rows up to M*K <= 32768; three or four rows
+ * For a few decode rows (M <= 4 and M*K <= 8192; two or three rows up to M*K <= 32768; four rows
  * up to there on layers of 150 M weights and more) a single kernel does both: every workgroup
  * quantises the rows into LDS before streaming its weights, which removes one launch from a
  * microsecond-scale step.  Otherwise the two kernels run back to back on `stream`, with the

@@ -373,12 +373,12 @@ static bool takes_bias_route(int mode, int64_t M, int64_t N, int64_t K) {
 }
 
 // One launch that quantises and multiplies.  Every workgroup quantises all M rows for itself, which a
-// second launch (3.3-3.7 us) costs more than: always up to 8192 activations, up to 32768 with two rows, and
-// with three or four rows on the large layers only (measured on five layers: M=2 0.9-2.6 us ahead everywhere;
-// M=4 1.2 us ahead on 8192 x 28672, 0.3-1.0 us behind on the layers of 70 M weights and less).
+// second launch (3.3-3.7 us) costs more than: always up to 8192 activations, up to 32768 with two or three
+// rows, and with four rows on the large layers only (measured on five layers: M=2 0.8-2.5 us ahead everywhere,
+// M=3 0.1-1.7 us; M=4 0.8 us ahead on 8192 x 28672, 0.2 us behind on the layers of 70 M weights and less).
 static bool fused_ok(int64_t M, int64_t N, int64_t K) {
   if (!(g_override == 0 && g_fuse_quant && M >= 1 && M <= kFusedMaxM && M * K <= kFusedLdsBytes)) return false;
-  return M * K <= kFusedLdsSmall || M <= 2 || (double)N * (double)K >= 1.5e8;
+  return M * K <= kFusedLdsSmall || M <= 3 || (double)N * (double)K >= 1.5e8;
 }
 
 // quant_act followed by the GEMM; for a few decode rows a single launch that does both

@@ -241,7 +241,9 @@ __global__ __launch_bounds__(W * 64) void gemm_skinny_kernel(const GemmParams p,
   constexpr int kRedInts = W * kElems;
   // FUSED: 0 = no, 1 = up to kFusedLdsSmall activations (M*K), 2 = up to kFusedLdsBytes
   constexpr int kFusedBytes = FUSED == 2 ? kFusedLdsBytes : kFusedLdsSmall;
-  constexpr int kSmemInts = (FUSED && kFusedBytes / 4 > kRedInts) ? kFusedBytes / 4 : kRedInts;
+  // (+ 16 bytes per row: see the fused prologue)
+  constexpr int kFusedInts = kFusedBytes / 4 + 4 * kFusedMaxM;
+  constexpr int kSmemInts = (FUSED && kFusedInts > kRedInts) ? kFusedInts : kRedInts;
   __shared__ __attribute__((aligned(16))) int smem[kSmemInts];
   int* const red = smem;
   __shared__ __attribute__((aligned(16))) int8_t a_tr[FUSED ? 16 : W * 2048];  // see ATranspose
@@ -349,7 +351,9 @@ __global__ __launch_bounds__(W * 64) void gemm_skinny_kernel(const GemmParams p,
             o.x = quant4(v[j].x, v[j].y, s_m);
             o.y = quant4(v[j].z, v[j].w, s_m);
           }
-          aq_lds[idx] = o;  // rows are contiguous in LDS: row m starts at byte m*K
+          // row m starts at byte m*(K+16): K is a multiple of all 64 banks, and an MFMA fragment read
+          // takes the same 16 bytes of up to four different rows at once, which the pad spreads over the banks
+          aq_lds[idx + 2 * vm[j]] = o;
         }
       }
     }
@@ -378,7 +382,7 @@ __global__ __launch_bounds__(W * 64) void gemm_skinny_kernel(const GemmParams p,
         aoff[mt][0] = (uint32_t)min(mt * 16 + (lane >> 3), M - 1) * (uint32_t)p.K + (uint32_t)(lane & 7) * 16u;
         aoff[mt][1] = (uint32_t)min(mt * 16 + 8 + (lane >> 3), M - 1) * (uint32_t)p.K + (uint32_t)(lane & 7) * 16u;
       } else {
-        aoff[mt][0] = (uint32_t)min(mt * 16 + nl, M - 1) * (uint32_t)p.K + (uint32_t)kc * 16u;
+        aoff[mt][0] = (uint32_t)min(mt * 16 + nl, M - 1) * ((uint32_t)p.K + (FUSED ? 16u : 0u)) + (uint32_t)kc * 16u;
         aoff[mt][1] = aoff[mt][0] + 64u;  // second MFMA step of this k-step
       }
     }

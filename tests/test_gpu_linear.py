@@ -59,7 +59,7 @@ def check(acc, y, o_acc, o_y):
     assert d.max() <= 1, "fp16 output off by %d ulp" % int(d.max())
 
 
-# M <= 4 with M*K <= 8192, and M <= 2 with M*K <= 32768, take the fused kernel; the rest the two-kernel route
+# M <= 4 with M*K <= 8192, and M <= 3 with M*K <= 32768, take the fused kernel; the rest the two-kernel route
 SHAPES = [(1, 128, 16), (1, 4096, 1024), (2, 1152, 272), (3, 2688, 208), (4, 2048, 4096),
           (1, 8192, 48), (1, 5120, 13824), (2, 4096, 32), (2, 4224, 64), (1, 8320, 64),
           (3, 5120, 208), (1, 65536, 48), (5, 1024, 256), (16, 4096, 512), (70, 1024, 512),
@@ -112,7 +112,7 @@ def test_linear_pergroup_biased_route_on_short_launches(M, K, N):
 @pytest.mark.parametrize("M,K,N", [(4, 8192, 18432), (3, 6144, 24576), (2, 16384, 64), (1, 32768, 48)])
 @pytest.mark.parametrize("pergroup", [False, True])
 def test_linear_fused_large_prologue(M, K, N, pergroup):
-    """The fused kernel's larger prologue (up to 32768 activations): two rows anywhere, three and four on
+    """The fused kernel's larger prologue (up to 32768 activations): two and three rows anywhere, four on
     layers of 150 M weights and more."""
     a = synth.activations_fp16(M, K, 23 * M + K + N)
     w = synth.random_w_nat(N, K, 11 + N)
