@@ -33,6 +33,13 @@ Readings taken where the paper is silent, ambiguous or at odds with itself:
   fp16_rne(fp32(max_k |W[n,k]|) / 7) from the ORIGINAL weights, code = clamp(rne(fp32(w / s)), -7, 7)
   (w is a float64 running value here; its quotient by the stored scale is rounded to fp32 first, which
   makes the rule coincide with the front-end's on weights that were never moved).
+* Per-group weights (Sec. 3.3.2 uses group 128 along the input channels; Sec. 3.2 does not say when a
+  group's scale is fixed while Eq. 4 keeps moving the weights).  Reading: when the sweep reaches the
+  first input channel of a group, the group's scale is taken from the weights as they stand then,
+  compensated by everything quantised before: s_Wg[g,n] = fp16_rne(fp32(max_{k in g} |W[n,k]|) / 7); the
+  channels of the group are quantised with it.  The per-channel scale s_Wc, the fused scale s*_Wg and
+  its integer form then follow from the codes and s_Wg by the front-end's own rule.  With a diagonal
+  Hessian nothing moves and all five outputs are the front-end's.
 
 Pins (tests/test_oracle_calib.py): the K = 2 closed form and an exact-rational evaluation of Eq. 4
 on tiny layers, diagonal Hessian = plain round-to-nearest, the Cholesky formulation as an
@@ -172,6 +179,64 @@ def gptq_quantize(w_bits, H, percdamp=0.01):
         # channel i leaves F: the inverse Hessian of the smaller set by eliminating row/column i
         Hinv[i + 1:, i + 1:] -= np.outer(Hinv[i + 1:, i], Hinv[i, i + 1:]) / d
     return codes, s_bits, codes.astype(np.float64) * s[:, None]
+
+
+def group_scales_now(W_group):
+    """fp16_rne(fp32(max_k |W[n,k]|) / 7) over one group of the running float64 weights, as fp16 bits [N]."""
+    amax = np.abs(np.asarray(W_group, np.float64)).max(axis=1).astype(np.float32)
+    return (amax / np.float32(7.0)).astype(np.float16).view(np.uint16)
+
+
+def gptq_quantize_pergroup(w_bits, H, group=128, percdamp=0.01):
+    """Eq. 4 channel by channel with per-group scales fixed when the sweep enters the group.
+    Returns (codes int8 [N,K], s_Wg fp16 bits [K/group, N], W_q float64 [N,K])."""
+    W = _f16(w_bits).astype(np.float64).copy()
+    N, K = W.shape
+    assert K % group == 0
+    H = np.array(H, np.float64, copy=True)
+    dead = np.diag(H) == 0.0
+    H[dead, dead] = 1.0
+    W[:, dead] = 0.0
+    H[np.arange(K), np.arange(K)] += percdamp * np.mean(np.diag(H))
+    Hinv = np.linalg.inv(H)
+    codes = np.zeros((N, K), np.int8)
+    s_wg = np.zeros((K // group, N), np.uint16)
+    W_q = np.zeros((N, K), np.float64)
+    s = None
+    for i in range(K):
+        if i % group == 0:
+            s_wg[i // group] = group_scales_now(W[:, i:i + group])
+            s = _f16(s_wg[i // group]).astype(np.float64)
+        w = W[:, i]
+        q = rtn_codes(w, s)
+        codes[:, i] = q.astype(np.int8)
+        W_q[:, i] = q * s
+        d = Hinv[i, i]
+        err = (w - q * s) / d
+        W[:, i + 1:] -= np.outer(err, Hinv[i, i + 1:])
+        Hinv[i + 1:, i + 1:] -= np.outer(Hinv[i + 1:, i], Hinv[i, i + 1:]) / d
+    return codes, s_wg, W_q
+
+
+def pergroup_scales_from_codes(codes, s_wg_bits, group=128):
+    """The front-end's rule (Sec. 3.3.2, Fig. 5 offline) for what follows the codes and group scales:
+    s_Wc[n] = fp16_rne(fp32(max_k |code * s_Wg|) / 127) with the product in fp32; s*_Wg = fp16_rne(fp32(s_Wg / s_Wc)),
+    capped at 18.203125 (0 where s_Wc is 0); integer form clamp(rne(s*_Wg), 1, 18).
+    Returns (s*_Wg fp16 bits [G,N], integer s* int8 [G,N], s_Wc fp16 bits [N])."""
+    codes = np.asarray(codes)
+    N, K = codes.shape
+    G = K // group
+    sg = _f16(s_wg_bits).astype(np.float32)                        # [G, N]
+    per_weight = np.repeat(sg.T, group, axis=1)                    # [N, K]
+    dmax = np.abs(codes.astype(np.float32) * per_weight).max(axis=1)
+    s_wc_bits = (dmax / np.float32(127.0)).astype(np.float16).view(np.uint16)
+    s_wc = _f16(s_wc_bits).astype(np.float32)
+    safe = np.where(s_wc == 0.0, np.float32(1.0), s_wc)
+    star = (sg / safe[None, :]).astype(np.float16)
+    star = np.where(star.astype(np.float32) > np.float32(18.203125), np.float16(18.203125), star)
+    star = np.where(s_wc[None, :] == 0.0, np.float16(0.0), star).astype(np.float16)
+    s_int = np.clip(np.rint(star.astype(np.float64)), 1.0, 18.0).astype(np.int8)
+    return star.view(np.uint16), s_int, s_wc_bits
 
 
 def codes_to_w_nat(codes):

@@ -216,3 +216,73 @@ def test_compensation_beats_round_to_nearest_in_the_hessian_norm():
     # the layer output itself: || X (W - Wq)^T ||^2 is what the Hessian norm measures
     X = x.view(np.float16).astype(np.float64)
     assert cal.hessian_error(W, wq, H) == pytest.approx(float(np.sum((X @ (W - wq).T) ** 2)), rel=1e-9)
+
+
+# ------------------------------------------------------------------ per-group compensation
+
+def test_pergroup_with_a_diagonal_hessian_is_the_front_end():
+    """Nothing moves, so codes, group scales and everything derived from them must be what the (C) front-end
+    oracle gives for the same weights: pins the sweep's scale rule and the derived scales at once."""
+    _, w = layer(4, 256, 24, 21)
+    wv = w.view(np.float16).copy()
+    wv[3, 128:] = 0                      # a group of zeros: scale 0, codes 0
+    wv[5, :] = 0                         # a channel of zeros: s_Wc 0, fused scale 0, integer form 1
+    w = wv.view(np.uint16)
+    H = np.diag(np.linspace(1.0, 3.0, 256))
+    codes, s_wg, _ = cal.gptq_quantize_pergroup(w, H, 128, percdamp=0.0)
+    star, s_int, s_wc = cal.pergroup_scales_from_codes(codes, s_wg, 128)
+    f_nat, f_wg, f_star, f_int, f_wc = orc.quantize_w4_pergroup(w, 128)
+    assert np.array_equal(cal.codes_to_w_nat(codes), f_nat)
+    assert np.array_equal(s_wg, f_wg) and np.array_equal(star, f_star)
+    assert np.array_equal(s_int, f_int) and np.array_equal(s_wc, f_wc)
+
+
+def test_pergroup_with_one_group_is_the_per_channel_sweep():
+    x, w = layer(300, 128, 10, 22, outliers=(7,), scale=6.0)
+    H = cal.hessian(x)
+    c_pc, s_pc, wq_pc = cal.gptq_quantize(w, H, percdamp=0.01)
+    c_pg, s_wg, wq_pg = cal.gptq_quantize_pergroup(w, H, 128, percdamp=0.01)
+    assert np.array_equal(c_pc, c_pg) and np.array_equal(s_pc, s_wg[0]) and np.array_equal(wq_pc, wq_pg)
+
+
+def test_pergroup_eq4_in_exact_rationals_on_a_tiny_layer():
+    """Groups of two channels; H_F inverted exactly at every step; the group scale re-derived from the exactly
+    compensated weights when the sweep enters the group."""
+    g = synth.rng(23)
+    K, N, group = 6, 3, 2
+    x = f16bits(g.standard_normal((3 * K, K)))
+    w = f16bits(g.standard_normal((N, K)) * 0.1)
+    H = cal.hessian(x)
+    codes, s_wg, _ = cal.gptq_quantize_pergroup(w, H, group, percdamp=0.0)
+    Hf = [[Fraction(float(H[i, j])) for j in range(K)] for i in range(K)]
+    for n in range(N):
+        wr = [Fraction(float(v)) for v in w.view(np.float16)[n]]
+        s = None
+        for i in range(K):
+            if i % group == 0:
+                amax = max(abs(v) for v in wr[i:i + group])
+                bits = (np.float32(float(amax)) / np.float32(7.0)).astype(np.float16).view(np.uint16)
+                assert bits == s_wg[i // group, n], (n, i)
+                s = float(bits.view(np.float16))
+            F = list(range(i, K))
+            inv = exact_inverse([[Hf[a][b] for b in F] for a in F])
+            q = float(cal.rtn_codes(float(wr[i]), s))
+            assert codes[n, i] == q, (n, i)
+            e = (wr[i] - Fraction(q) * Fraction(s)) / inv[0][0]
+            for pos, j in enumerate(F):
+                if j > i:
+                    wr[j] -= e * inv[pos][0]
+
+
+def test_pergroup_compensation_beats_group_wise_round_to_nearest():
+    g = synth.rng(24)
+    base = g.standard_normal((600, 12))
+    x = f16bits(base @ g.standard_normal((12, 256)) + 0.3 * g.standard_normal((600, 256)))
+    w = f16bits(g.standard_normal((16, 256)) * 0.05)
+    H = cal.hessian(x)
+    codes, s_wg, wq = cal.gptq_quantize_pergroup(w, H, 128, percdamp=0.01)
+    W = w.view(np.float16).astype(np.float64)
+    f_nat, f_wg, _, _, _ = orc.quantize_w4_pergroup(w, 128)
+    rtn = orc.w8_perchannel(f_nat, 256).astype(np.float64) * np.repeat(f_wg.view(np.float16).astype(np.float64).T, 128, axis=1)
+    assert np.abs(codes).max() <= 7
+    assert cal.hessian_error(W, wq, H) < 0.6 * cal.hessian_error(W, rtn, H)
