@@ -78,6 +78,22 @@ int qqq_gptq_quantize_w4_perchannel(const void* w_fp16, const double* H, int64_t
                                     double percdamp, uint32_t* w_nat, void* s_w_fp16, void* workspace,
                                     size_t workspace_bytes, void* stream);
 
+
+/*
+ * The same compensation with the per-group int4 quantiser of qqq_quantize_w4_pergroup (Sec. 3.3.2: groups of
+ * 128 input channels).  Sec. 3.2 does not say when a group's scale is fixed while Eq. 4 keeps moving the
+ * weights; here it is fixed when the sweep reaches the group's first channel, from the weights as they stand
+ * then (compensated by every channel quantised before): s_Wg[g,n] = fp16_rne(fp32(max_{k in g} |W[n,k]|) / 7),
+ * code = clamp(rne(fp32(w / s_Wg)), -7, 7).  After the sweep s_Wc, s*_Wg and its integer form follow from the
+ * codes and s_Wg exactly as in qqq_quantize_w4_pergroup, so with a diagonal H all outputs equal that call's.
+ *   group must be 128 and K a multiple of it; s_wg_fp16, s_star_fp16 [K/128, N] fp16, s_int [K/128, N] int8 or
+ *   NULL, s_wc_fp16 [N] fp16 (all written); the other arguments, the workspace and the cost as above.
+ */
+int qqq_gptq_quantize_w4_pergroup(const void* w_fp16, const double* H, int64_t N, int64_t K, int group,
+                                  double percdamp, uint32_t* w_nat, void* s_wg_fp16, void* s_star_fp16,
+                                  int8_t* s_int, void* s_wc_fp16, void* workspace, size_t workspace_bytes,
+                                  void* stream);
+
 #ifdef __cplusplus
 }
 #endif

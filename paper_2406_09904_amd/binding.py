@@ -29,6 +29,7 @@ SYMBOLS = [
     "qqq_debug_count_sg_violations", "qqq_probe_stream_read", "qqq_probe_mfma_i8", "qqq_probe_prefill_loop",
     "qqq_smoothing_workspace_bytes", "qqq_adaptive_smoothing", "qqq_channel_absmax", "qqq_smooth_apply",
     "qqq_fp16_gemm_nt", "qqq_hessian", "qqq_gptq_workspace_bytes", "qqq_gptq_quantize_w4_perchannel",
+    "qqq_gptq_quantize_w4_pergroup",
 ]
 
 _lib = None
@@ -64,6 +65,7 @@ def lib():
         L.qqq_gptq_workspace_bytes.argtypes = [i64, i64]
         L.qqq_gptq_workspace_bytes.restype = sz
         L.qqq_gptq_quantize_w4_perchannel.argtypes = [vp, vp, i64, i64, ctypes.c_double, vp, vp, vp, sz, vp]
+        L.qqq_gptq_quantize_w4_pergroup.argtypes = [vp, vp, i64, i64, ci, ctypes.c_double, vp, vp, vp, vp, vp, vp, sz, vp]
         L.qqq_probe_stream_read.argtypes = [vp, sz, ci, vp, vp]
         L.qqq_probe_mfma_i8.argtypes = [vp, vp, ci, ci, vp, vp]
         L.qqq_probe_prefill_loop.argtypes = [vp, sz, ci, ci, ci, vp, vp]
@@ -384,6 +386,26 @@ def qqq_gptq_quantize_w4_perchannel(w_fp16, H, percdamp=0.01):
                                                  _ptr(w_nat, torch.int32), _ptr(s_w, torch.float16), _ptr(work),
                                                  work.numel(), _stream()))
     return w_nat, s_w
+
+
+def qqq_gptq_quantize_w4_pergroup(w_fp16, H, percdamp=0.01, want_int=True):
+    """Sec. 3.2 with the group-128 quantiser of Sec. 3.3.2 on one layer: W [N,K] fp16, H [K,K] fp64 ->
+    (w_nat int32 [N,K/8], s_wg fp16 [K/128,N], s_star fp16 [K/128,N], s_int int8 [K/128,N] or None, s_wc fp16 [N])."""
+    N, K = _fp16_matrix(w_fp16)
+    dev = w_fp16.device
+    G = K // GROUP
+    w_nat = torch.empty((N, K // 8), dtype=torch.int32, device=dev)
+    s_wg = torch.empty((G, N), dtype=torch.float16, device=dev)
+    s_star = torch.empty((G, N), dtype=torch.float16, device=dev)
+    s_int = torch.empty((G, N), dtype=torch.int8, device=dev) if want_int else None
+    s_wc = torch.empty((N,), dtype=torch.float16, device=dev)
+    nbytes = int(lib().qqq_gptq_workspace_bytes(N, K))
+    work = torch.empty((max(nbytes, 16),), dtype=torch.uint8, device=dev)
+    _check(lib().qqq_gptq_quantize_w4_pergroup(_ptr(w_fp16), _ptr(H, torch.float64), N, K, GROUP, float(percdamp),
+                                               _ptr(w_nat, torch.int32), _ptr(s_wg, torch.float16),
+                                               _ptr(s_star, torch.float16), _ptr(s_int, torch.int8),
+                                               _ptr(s_wc, torch.float16), _ptr(work), work.numel(), _stream()))
+    return w_nat, s_wg, s_star, s_int, s_wc
 
 
 def last_route() -> str:

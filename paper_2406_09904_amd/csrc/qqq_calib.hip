@@ -313,6 +313,53 @@ __global__ __launch_bounds__(256) void gptq_eliminate_kernel(double* Hinv, int64
   Hinv[a * K + b] = Hinv[a * K + b] - t;
 }
 
+// Per-group weights (Sec. 3.3.2: groups of 128 input channels): when the sweep reaches a group's first
+// channel, the group's scale comes from the weights as they stand then, s = fp16(fp32(max |w|) / 7).
+// One thread per output channel.
+__global__ __launch_bounds__(256) void gptq_group_scale_kernel(const double* W64, int64_t N, int64_t K, int64_t i0,
+                                                               int group, uint16_t* s_row) {
+  const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (n >= N) return;
+  double amax = 0.0;
+  for (int k = 0; k < group; ++k) amax = fmax(amax, fabs(W64[n * K + i0 + k]));
+  s_row[n] = __builtin_bit_cast(uint16_t, (_Float16)((float)amax / 7.0f));
+}
+
+// After the sweep, what the front-end derives from codes and group scales (Sec. 3.3.2, Fig. 5 offline):
+// s_Wc[n] = fp16(max_k |code * s_Wg| / 127) with the product in fp32, s*_Wg = fp16(s_Wg / s_Wc) capped at
+// 18.203125 (0 where s_Wc is 0), integer form clamp(rne(s*_Wg), 1, 18).  One thread per output channel.
+__global__ __launch_bounds__(256) void gptq_group_finish_kernel(const uint32_t* w_nat, const uint16_t* s_wg, int64_t N,
+                                                                int64_t K, int group, uint16_t* s_wc, uint16_t* s_star,
+                                                                int8_t* s_int) {
+  const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (n >= N) return;
+  const int64_t G = K / group;
+  float dmax = 0.0f;
+  for (int64_t g = 0; g < G; ++g) {
+    int cmax = 0;
+    for (int j = 0; j < group / 8; ++j) {
+      const uint32_t word = w_nat[n * (K / 8) + g * (group / 8) + j];
+      for (int q = 0; q < 8; ++q) {
+        const int code = ((int)(word << (28 - 4 * q))) >> 28;  // sign-extended nibble
+        cmax = max(cmax, code < 0 ? -code : code);
+      }
+    }
+    dmax = fmaxf(dmax, (float)cmax * half_bits_to_float(s_wg[g * N + n]));
+  }
+  const uint16_t wcb = __builtin_bit_cast(uint16_t, (_Float16)(dmax / 127.0f));
+  s_wc[n] = wcb;
+  const float wc = half_bits_to_float(wcb);
+  for (int64_t g = 0; g < G; ++g) {
+    uint16_t star = 0;
+    if (wc != 0.0f) {
+      const _Float16 h = (_Float16)(half_bits_to_float(s_wg[g * N + n]) / wc);
+      star = __builtin_bit_cast(uint16_t, (float)h > 18.203125f ? (_Float16)18.203125f : h);
+    }
+    s_star[g * N + n] = star;
+    if (s_int) s_int[g * N + n] = (int8_t)fminf(fmaxf(__builtin_rintf(half_bits_to_float(star)), 1.0f), 18.0f);
+  }
+}
+
 static bool calib_shape_ok(int64_t M, int64_t N, int64_t K) {
   return M >= 1 && M <= 0x7FFFFFFF && N >= 16 && N % 16 == 0 && N <= 0x7FFFFFF0 && K >= 128 && K % 128 == 0 &&
          K <= 131072;
@@ -502,30 +549,27 @@ size_t qqq_gptq_workspace_bytes(int64_t N, int64_t K) {
   return align256c((size_t)K * K * 8) + align256c((size_t)N * K * 8) + 2 * align256c((size_t)K * 8) + 256;
 }
 
-int qqq_gptq_quantize_w4_perchannel(const void* w_fp16, const double* H, int64_t N, int64_t K, double percdamp,
-                                    uint32_t* w_nat, void* s_w_fp16, void* workspace, size_t workspace_bytes,
-                                    void* stream) {
+// what both sweeps share: argument checks, the working copies, damping and the inverse Hessian
+struct GptqWork { double *Hinv, *W64; };
+static int gptq_begin(const char* who, const void* w_fp16, const double* H, int64_t N, int64_t K, double percdamp,
+                      const uint32_t* w_nat, void* workspace, size_t workspace_bytes, hipStream_t st, GptqWork* out) {
   if (N < 1 || N > 65535 || K < 8 || K % 8 != 0 || K > 16384 || !(percdamp >= 0.0) || percdamp > 1e6)
-    return set_error(QQQ_ERR_SHAPE, "gptq: unsupported N=%lld K=%lld percdamp=%g (need N <= 65535, K%%8==0, K <= 16384, "
-                     "percdamp >= 0)", (long long)N, (long long)K, percdamp);
-  if (!w_fp16 || !H || !w_nat || !s_w_fp16 || !workspace) return set_error(QQQ_ERR_NULL, "gptq: null pointer argument");
+    return set_error(QQQ_ERR_SHAPE, "%s: unsupported N=%lld K=%lld percdamp=%g (need N <= 65535, K%%8==0, K <= 16384, "
+                     "percdamp >= 0)", who, (long long)N, (long long)K, percdamp);
+  if (!w_fp16 || !H || !w_nat || !workspace) return set_error(QQQ_ERR_NULL, "%s: null pointer argument", who);
   if (!aligned16c(w_fp16) || !aligned16c(workspace) || (reinterpret_cast<uintptr_t>(H) & 7u) ||
-      (reinterpret_cast<uintptr_t>(w_nat) & 3u) || (reinterpret_cast<uintptr_t>(s_w_fp16) & 1u))
-    return set_error(QQQ_ERR_SHAPE, "gptq: w_fp16 and workspace must be 16-byte, H 8-byte, w_nat 4-byte, s_w 2-byte aligned");
+      (reinterpret_cast<uintptr_t>(w_nat) & 3u))
+    return set_error(QQQ_ERR_SHAPE, "%s: w_fp16 and workspace must be 16-byte, H 8-byte, w_nat 4-byte aligned", who);
   const size_t need = qqq_gptq_workspace_bytes(N, K);
   if (workspace_bytes < need)
-    return set_error(QQQ_ERR_WORKSPACE, "gptq: workspace %zu bytes < %zu needed", workspace_bytes, need);
-  hipStream_t st = (hipStream_t)stream;
+    return set_error(QQQ_ERR_WORKSPACE, "%s: workspace %zu bytes < %zu needed", who, workspace_bytes, need);
   char* base = (char*)workspace;
   double* Hinv = (double*)base;
   double* W64 = (double*)(base + align256c((size_t)K * K * 8));
   double* row = (double*)((char*)W64 + align256c((size_t)N * K * 8));
   double* col = (double*)((char*)row + align256c((size_t)K * 8));
   double* dsum = (double*)((char*)col + align256c((size_t)K * 8));
-
-  // scales from the original weights (and round-to-nearest codes, overwritten channel by channel below)
-  int rc = launch_quant_weight(w_fp16, N, K, K, false, w_nat, (uint16_t*)s_w_fp16, nullptr, nullptr, nullptr, st);
-  if (rc != QQQ_OK) return rc;
+  int rc;
   if ((rc = fill_u32(dsum, 2, 0u, st)) != QQQ_OK) return rc;
   hipLaunchKernelGGL(gptq_prepare_kernel, dim3(2048), dim3(256), 0, st, H, (const _Float16*)w_fp16, N, K, Hinv, W64, dsum);
   if ((rc = check_launch("gptq_prepare")) != QQQ_OK) return rc;
@@ -537,15 +581,64 @@ int qqq_gptq_quantize_w4_perchannel(const void* w_fp16, const double* H, int64_t
     hipLaunchKernelGGL(gj_update_kernel, dim3(kb, (unsigned)K), dim3(256), 0, st, Hinv, K, p, row, col);
   }
   if ((rc = check_launch("gptq inverse")) != QQQ_OK) return rc;
-  for (int64_t i = 0; i < K; ++i) {  // Eq. 4, channel by channel
-    const int64_t trail = K - i - 1;
-    const unsigned tb = (unsigned)(trail > 0 ? (trail + 255) / 256 : 1);
-    hipLaunchKernelGGL(gptq_column_kernel, dim3(tb, (unsigned)N), dim3(256), 0, st, W64, Hinv, (const uint16_t*)s_w_fp16,
-                       N, K, i, w_nat);
-    if (trail > 0)
-      hipLaunchKernelGGL(gptq_eliminate_kernel, dim3(tb, (unsigned)trail), dim3(256), 0, st, Hinv, K, i);
-  }
+  out->Hinv = Hinv;
+  out->W64 = W64;
+  return QQQ_OK;
+}
+
+// channel i of Eq. 4 with the scales at `scales` [N], then channel i leaves F
+static void gptq_step(const GptqWork& wk, const uint16_t* scales, int64_t N, int64_t K, int64_t i, uint32_t* w_nat,
+                      hipStream_t st) {
+  const int64_t trail = K - i - 1;
+  const unsigned tb = (unsigned)(trail > 0 ? (trail + 255) / 256 : 1);
+  hipLaunchKernelGGL(gptq_column_kernel, dim3(tb, (unsigned)N), dim3(256), 0, st, wk.W64, wk.Hinv, scales, N, K, i,
+                     w_nat);
+  if (trail > 0)
+    hipLaunchKernelGGL(gptq_eliminate_kernel, dim3(tb, (unsigned)trail), dim3(256), 0, st, wk.Hinv, K, i);
+}
+
+int qqq_gptq_quantize_w4_perchannel(const void* w_fp16, const double* H, int64_t N, int64_t K, double percdamp,
+                                    uint32_t* w_nat, void* s_w_fp16, void* workspace, size_t workspace_bytes,
+                                    void* stream) {
+  if (!s_w_fp16) return set_error(QQQ_ERR_NULL, "gptq: null pointer argument");
+  if (reinterpret_cast<uintptr_t>(s_w_fp16) & 1u) return set_error(QQQ_ERR_SHAPE, "gptq: s_w must be 2-byte aligned");
+  hipStream_t st = (hipStream_t)stream;
+  GptqWork wk;
+  int rc = gptq_begin("gptq", w_fp16, H, N, K, percdamp, w_nat, workspace, workspace_bytes, st, &wk);
+  if (rc != QQQ_OK) return rc;
+  // scales from the original weights (and round-to-nearest codes, overwritten channel by channel below)
+  rc = launch_quant_weight(w_fp16, N, K, K, false, w_nat, (uint16_t*)s_w_fp16, nullptr, nullptr, nullptr, st);
+  if (rc != QQQ_OK) return rc;
+  for (int64_t i = 0; i < K; ++i) gptq_step(wk, (const uint16_t*)s_w_fp16, N, K, i, w_nat, st);  // Eq. 4, channel by channel
   return check_launch("gptq column");
+}
+
+int qqq_gptq_quantize_w4_pergroup(const void* w_fp16, const double* H, int64_t N, int64_t K, int group, double percdamp,
+                                  uint32_t* w_nat, void* s_wg_fp16, void* s_star_fp16, int8_t* s_int, void* s_wc_fp16,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+  if (group != QQQ_GROUP) return set_error(QQQ_ERR_SHAPE, "gptq_pergroup: group must be 128, got %d", group);
+  if (K % QQQ_GROUP != 0) return set_error(QQQ_ERR_SHAPE, "gptq_pergroup: K=%lld must be a multiple of 128", (long long)K);
+  if (!s_wg_fp16 || !s_star_fp16 || !s_wc_fp16) return set_error(QQQ_ERR_NULL, "gptq_pergroup: null pointer argument");
+  if ((reinterpret_cast<uintptr_t>(s_wg_fp16) | reinterpret_cast<uintptr_t>(s_star_fp16) |
+       reinterpret_cast<uintptr_t>(s_wc_fp16)) & 1u)
+    return set_error(QQQ_ERR_SHAPE, "gptq_pergroup: scale tables must be 2-byte aligned");
+  hipStream_t st = (hipStream_t)stream;
+  GptqWork wk;
+  int rc = gptq_begin("gptq_pergroup", w_fp16, H, N, K, percdamp, w_nat, workspace, workspace_bytes, st, &wk);
+  if (rc != QQQ_OK) return rc;
+  if ((rc = fill_u32(w_nat, (size_t)N * (size_t)(K / 8), 0u, st)) != QQQ_OK) return rc;
+  uint16_t* s_wg = (uint16_t*)s_wg_fp16;
+  const unsigned nb = (unsigned)((N + 255) / 256);
+  for (int64_t i = 0; i < K; ++i) {
+    uint16_t* s_row = s_wg + (i / QQQ_GROUP) * N;
+    if (i % QQQ_GROUP == 0)  // the sweep enters a group: its scale from the weights as they stand now
+      hipLaunchKernelGGL(gptq_group_scale_kernel, dim3(nb), dim3(256), 0, st, wk.W64, N, K, i, QQQ_GROUP, s_row);
+    gptq_step(wk, s_row, N, K, i, w_nat, st);
+  }
+  if ((rc = check_launch("gptq_pergroup column")) != QQQ_OK) return rc;
+  hipLaunchKernelGGL(gptq_group_finish_kernel, dim3(nb), dim3(256), 0, st, w_nat, s_wg, N, K, QQQ_GROUP,
+                     (uint16_t*)s_wc_fp16, (uint16_t*)s_star_fp16, s_int);
+  return check_launch("gptq_pergroup finish");
 }
 
 }  // extern "C"

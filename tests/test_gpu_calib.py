@@ -136,6 +136,80 @@ def test_diagonal_hessian_is_the_front_end_and_dead_channels_get_zero():
     assert np.array_equal(g_codes, o_codes)
 
 
+@pytest.mark.parametrize("M,K,N", [(256, 128, 32), (512, 256, 48), (300, 384, 16)])
+def test_hessian_based_compensation_pergroup(M, K, N):
+    """Group scales fixed from the compensated weights when the sweep enters a group (oracle's reading): codes,
+    group scales and the scales derived from them against the oracle, same bar as the per-channel sweep."""
+    x, w = correlated_layer(M, K, N, 171 + K)
+    H_o = cal.hessian(x)
+    codes, s_wg, wq = cal.gptq_quantize_pergroup(w, H_o, 128, 0.01)
+    d_H = qqq.qqq_hessian(dev16(x))
+    w_nat, g_wg, g_star, g_int, g_wc = qqq.qqq_gptq_quantize_w4_pergroup(dev16(w), d_H, 0.01)
+    torch.cuda.synchronize()
+    g_codes = orc.w8_perchannel(w_nat.cpu().numpy().view(np.uint32), K)
+    diff = np.argwhere(g_codes != codes)
+    W = w.view(np.float16).astype(np.float64)
+    if len(diff) == 0:       # identical sweeps: every derived table must be identical too
+        assert np.array_equal(f16_bits(g_wg), s_wg)
+        star, s_int, s_wc = cal.pergroup_scales_from_codes(codes, s_wg, 128)
+        assert np.array_equal(f16_bits(g_star), star) and np.array_equal(f16_bits(g_wc), s_wc)
+        assert np.array_equal(g_int.cpu().numpy(), s_int)
+    else:                    # allowed only at rounding ties of the running quotient, and then by one
+        assert len(diff) <= 2 and np.abs(g_codes.astype(int) - codes.astype(int)).max() == 1, diff[:10]
+    # the GPU's own tables follow from its own codes and group scales by the front-end's rule
+    star, s_int, s_wc = cal.pergroup_scales_from_codes(g_codes, f16_bits(g_wg), 128)
+    assert np.array_equal(f16_bits(g_star), star) and np.array_equal(f16_bits(g_wc), s_wc)
+    assert np.array_equal(g_int.cpu().numpy(), s_int)
+    g_wq = g_codes.astype(np.float64) * np.repeat(f16_bits(g_wg).view(np.float16).astype(np.float64).T, 128, axis=1)
+    f_nat, f_wg, _, _, _ = orc.quantize_w4_pergroup(w, 128)
+    rtn = orc.w8_perchannel(f_nat, K).astype(np.float64) * np.repeat(f_wg.view(np.float16).astype(np.float64).T, 128, axis=1)
+    assert cal.hessian_error(W, g_wq, H_o) < 0.8 * cal.hessian_error(W, rtn, H_o)
+    assert cal.hessian_error(W, g_wq, H_o) == pytest.approx(cal.hessian_error(W, wq, H_o), rel=1e-3)
+
+
+def test_pergroup_compensation_with_a_diagonal_hessian_is_the_front_end():
+    N, K = 32, 384
+    wv = synth.weights_fp16(N, K, 181).copy()
+    wv[4, 128:256] = 0                                   # a group of zeros
+    wv[9, :] = 0                                         # a channel of zeros
+    w = wv.view(np.uint16)
+    H = np.diag(np.linspace(0.5, 4.0, K))
+    got = qqq.qqq_gptq_quantize_w4_pergroup(dev16(w), torch.from_numpy(H).cuda(), 0.0)
+    ref = qqq.qqq_quantize_w4_pergroup(dev16(w))          # (w_nat, s_star, s_int, s_wc, s_wg)
+    torch.cuda.synchronize()
+    w_nat, s_wg, s_star, s_int, s_wc = got
+    assert torch.equal(w_nat, ref[0]) and torch.equal(s_star.view(torch.int16), ref[1].view(torch.int16))
+    assert torch.equal(s_int, ref[2]) and torch.equal(s_wc.view(torch.int16), ref[3].view(torch.int16))
+    assert torch.equal(s_wg.view(torch.int16), ref[4].view(torch.int16))
+    o_nat, o_wg, o_star, o_int, o_wc = orc.quantize_w4_pergroup(w, 128)
+    assert np.array_equal(w_nat.cpu().numpy().view(np.uint32), o_nat) and np.array_equal(f16_bits(s_wg), o_wg)
+
+
+def test_pergroup_compensation_feeds_the_per_group_gemm():
+    """Compensated per-group codes and their integer scales through repack and the per-group W4A8 GEMM: closer to
+    the fp64 product of the layer than the per-group front-end's round-to-nearest."""
+    M, K, N = 256, 512, 64
+    x, w = correlated_layer(M, K, N, 191)
+    d_x, d_w = dev16(x), dev16(w)
+    ref = cal.reference_product(x, w)
+    a_q, s_a = qqq.qqq_quant_act(d_x)
+
+    def run(w_nat, s_int, s_wc):
+        packed = qqq.qqq_pack_w4(w_nat, K)
+        y = qqq.qqq_gemm_w4a8_pergroup(a_q, s_a, packed, s_int, s_wc, qqq.new_workspace(M, N, K),
+                                       sg_max=18 | qqq.SG_SYMMETRIC_CODES)
+        torch.cuda.synchronize()
+        return float(np.sum((y.cpu().numpy().astype(np.float64) - ref) ** 2))
+
+    f_nat, _, f_int, f_wc, _ = qqq.qqq_quantize_w4_pergroup(d_w)
+    rtn = run(f_nat, f_int, f_wc)
+    H = qqq.qqq_hessian(d_x)
+    g_nat, _, _, g_int, g_wc = qqq.qqq_gptq_quantize_w4_pergroup(d_w, H, 0.01)
+    comp = run(g_nat, g_int, g_wc)
+    print("per-group layer output error: round-to-nearest %.4g, compensated %.4g" % (rtn, comp))
+    assert comp < rtn
+
+
 def test_offline_stage_feeds_the_hot_path():
     """Smoothing, then compensation, then repack, then the W4A8 GEMM on the smoothed activations: the
     layer output is closer to the fp64 product than plain round-to-nearest without smoothing."""
