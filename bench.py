@@ -502,6 +502,8 @@ def offline_stage_lines(torch, qqq, synth):
     H = qqq.qqq_hessian(x2)
     rows.append({"call": "qqq_gptq_quantize_w4_perchannel", "K": K2, "N": N2,
                  "ms": wall(lambda: qqq.qqq_gptq_quantize_w4_perchannel(w2, H, 0.01))})
+    rows.append({"call": "qqq_gptq_quantize_w4_pergroup", "K": K2, "N": N2,
+                 "ms": wall(lambda: qqq.qqq_gptq_quantize_w4_pergroup(w2, H, 0.01))})
     return rows
 
 
