@@ -422,8 +422,11 @@ def conversion_ablation(torch, qqq, wls, use_graph):
         qqq.qqq_gemm_w4a8_pergroup(c.a_q, c.s_a, c.w[i % c.copies], c.s_g[i % c.copies], c.s_w, c.ws,
                                    sg_max=18 | qqq.SG_SYMMETRIC_CODES, y=c.y)
 
-    rows.append({"route": "integer scale <= 18, codes promised in [-7,7] (the front-end's output): fp16 FMA route",
-                 "gemm_us": t(pg_sym18)})
+    rows.append({"route": "integer scale <= 18, codes promised in [-7,7] (the front-end's output): packed 16-bit "
+                          "multiply of 7 - code, bias and sign removal (default)", "gemm_us": t(pg_sym18)})
+    qqq.set_group_mode_override(3)
+    rows.append({"route": "integer scale <= 18, codes promised in [-7,7]: fp16 FMA route", "gemm_us": t(pg_sym18)})
+    qqq.set_group_mode_override(0)
     rows.append({"route": "integer scale, any: fp16 multiply, clamp, add, byte permute", "gemm_us": t(pg_any)})
     rows.append({"route": "real-valued scale: FastINT4toFP16 + FMA(128+1024) + permute + XOR (paper)",
                  "gemm_us": t(real)})

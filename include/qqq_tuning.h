@@ -95,7 +95,8 @@ int qqq_set_kernel_override(int family);
  * to be timed (the ablation of Sec. 4.5.2, Fig. 9): fp16 multiply, conventional round and
  * fp16->int16 conversion instructions, byte packing; two roundings, so it equals the default route
  * only where code*s is exact in fp16.  5 = the prefill kernels' biased integer route (byte-wise multiply
- * of code + 8, the constant taken out through a pre-pass; valid for s_g <= 16) wherever it applies, also on the
+ * of code + 8, or of 7 - code for scales up to 18 under the symmetric-code promise, the constant taken out
+ * through a pre-pass) wherever it applies, also on the
  * short launches where the automatic choice skips its pre-pass and converts with the fp16 FMA.  Returns the
  * previous value.
  */

@@ -212,7 +212,8 @@ static int group_mode(int sg_arg, int64_t M, int64_t N, int64_t K) {
   const bool decode = kernel_family(M, N, K, true) == 1;
   if (sg_max >= 1 && sg_max <= 16) mode = decode ? kGroupLinear : kGroupFused;
   else if (symmetric && sg_max >= 17 && sg_max <= 18) mode = decode ? kGroupLinear : kGroupFusedWide;
-  if (g_group_mode >= 1 && g_group_mode <= 3) mode = g_group_mode;
+  // (knob 3 asks for the fp16-FMA conversion: with scales of 17 and 18 that is its wide form)
+  if (g_group_mode >= 1 && g_group_mode <= 3) mode = (g_group_mode == 3 && mode == kGroupFusedWide) ? mode : g_group_mode;
   return mode;
 }
 
@@ -318,13 +319,15 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
   if (takes_bias_route(mode, M, N, K) && workspace && workspace_bytes >= qqq_gemm_workspace_bytes(M, N, K)) {
     int8_t *r_lo, *r_hi, *bc;
     bias_buffers(workspace, M, N, K, r_lo, r_hi, bc);
-    const int rc = launch_group_bias_prepass(a_q, s_g, M, N, K, r_lo, r_hi, bc, !row_sums_ready,
+    // (scales up to 18 with symmetric codes: bytes of (7 - code) * s_g instead of (code + 8) * s_g)
+    const bool wide = mode == kGroupFusedWide;
+    const int rc = launch_group_bias_prepass(a_q, s_g, M, N, K, r_lo, r_hi, bc, !row_sums_ready, wide ? 7 : 8,
                                              (hipStream_t)stream);
     if (rc != QQQ_OK) return rc;
     p.r_lo = r_lo;
     p.r_hi = r_hi;
     p.bias_w = bc;
-    mode = kGroupBias;
+    mode = wide ? kGroupBiasWide : kGroupBias;
   }
   // per-tile kernel, optionally with K split over several workgroups per tile (raw tiles into the
   // workspace's slabs, then the reduce kernel); the split needs a workspace of the queried size
@@ -363,7 +366,8 @@ static int gemm_common(const int8_t* a_q, const float* s_a, const void* w_packed
 
 static bool takes_bias_route(int mode, int64_t M, int64_t N, int64_t K) {
   // (the workspace holds the pre-pass buffers only above the rows that always take the decode kernel)
-  if (!(mode == kGroupFused && M > kDecodeAlwaysMaxM && (g_group_mode == 0 || g_group_mode == 5) &&
+  if (!((mode == kGroupFused || mode == kGroupFusedWide) && M > kDecodeAlwaysMaxM &&
+        (g_group_mode == 0 || g_group_mode == 5) &&
         kernel_family(M, N, K, true) == 2))
     return false;
   if (g_group_mode == 5) return true;  // forced

@@ -210,7 +210,7 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
   // entries straight from memory while the first two k-steps of DMA are in flight.  Rows of the
   // tables are padded with zeros to a multiple of 32 groups; where an MFMA takes 64, k-blocks past
   // the padded row feed zeros.
-  if (MODE == kGroupBias && split == 0) {  // the whole correction goes to the first K split
+  if (is_bias_mode(MODE) && split == 0) {  // the whole correction goes to the first K split
     // All operands of a pass are loaded before its MFMAs (TM + TC independent loads in flight): taken
     // one (row tile, channel tile) pair at a time, the load-then-MFMA chains of a tile ran one memory
     // latency after the other, 10-24 us per tile.
@@ -416,7 +416,8 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
 #pragma unroll
         for (int v = 0; v < kRegs; ++v) {
           const int m = m0 + acc_row(mt, v);
-          if (m < M) part[(int64_t)m * N + col[c]] = acc[mt][c][v];
+          // (the wide biased route accumulates the negated sums)
+          if (m < M) part[(int64_t)m * N + col[c]] = MODE == kGroupBiasWide ? -acc[mt][c][v] : acc[mt][c][v];
         }
       }
     }
@@ -432,7 +433,8 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
   // Per-channel sums carry the factor 16 of the conversion.  Scaling by a power of two commutes with
   // every rounding of the Dequant (int -> fp32, fp32 product, fp16 result), so the factor goes into
   // the channel scale instead of a shift per accumulator.
-  constexpr float kAccScale = MODE == kPerChannel ? 0.0625f : 1.0f;
+  // The wide biased route's sums are negated: the sign goes the same way.
+  constexpr float kAccScale = MODE == kPerChannel ? 0.0625f : (MODE == kGroupBiasWide ? -1.0f : 1.0f);
   float swv[TC];
 #pragma unroll
   for (int c = 0; c < TC; ++c) swv[c] = nvalid[c] ? (float)p.s_w[col[c]] * kAccScale : 0.0f;
@@ -481,6 +483,7 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
           if (m < M) {
             int x = acc[mt][c][v];
             if constexpr (MODE == kPerChannel) x >>= 4;
+            if constexpr (MODE == kGroupBiasWide) x = -x;
             p.acc_out[(int64_t)m * N + col[c]] = x;
           }
         }
@@ -584,6 +587,7 @@ int launch_gemm_prefill_dma(const GemmParams& p, int mode, int shape, hipStream_
     case kGroupReal: return launch_shape<kGroupReal>(p, shape, st);
     case kGroupCvt: return launch_dma<kGroupCvt, 4, 2, 8>(p, st);  // timing ablation: one shape
     case kGroupBias: return launch_shape<kGroupBias>(p, shape, st);
+    case kGroupBiasWide: return launch_shape<kGroupBiasWide>(p, shape, st);
   }
   return set_error(QQQ_ERR_SHAPE, "unknown mode %d", mode);
 }

@@ -253,7 +253,7 @@ __global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmPar
     // waits for them before the MFMAs below, so none is outstanding at the k-loop's counted waits.
     // Rows of the tables are padded with zeros to a multiple of 32 groups; an MFMA takes 64, so
     // k-blocks past the padded row feed zeros.
-    if constexpr (MODE == kGroupBias) {
+    if constexpr (is_bias_mode(MODE)) {
       // The operands of a pass are loaded in batches ahead of their MFMAs (4-8 independent loads in flight): taken one
       // (row tile, channel tile) pair at a time, the 64 load-then-MFMA chains of a tile ran one memory
       // latency after the other, 10-24 us per tile.
@@ -348,7 +348,8 @@ __global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmPar
       // Per-channel sums carry the factor 16 of the conversion.  Scaling by a power of two commutes with
       // every rounding of the Dequant (int -> fp32, fp32 product, fp16 result), so the factor goes
       // into the channel scale instead of a shift per accumulator.
-      constexpr float kAccScale = MODE == kPerChannel ? 0.0625f : 1.0f;
+      // (the wide biased route's sums are negated: the sign goes the same way)
+      constexpr float kAccScale = MODE == kPerChannel ? 0.0625f : (MODE == kGroupBiasWide ? -1.0f : 1.0f);
       float swv[4];
 #pragma unroll
       for (int c = 0; c < 4; ++c)
@@ -394,6 +395,7 @@ __global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmPar
               if (m < M) {
                 int x = acc[mt][c][v];
                 if constexpr (MODE == kPerChannel) x >>= 4;
+                if constexpr (MODE == kGroupBiasWide) x = -x;
                 p.acc_out[(int64_t)m * N + col] = x;
               }
             }
@@ -438,6 +440,7 @@ int launch_gemm_prefill_ring(const GemmParams& p, int mode, hipStream_t st) {
     case kGroupFusedWide:
     case kGroupFused: return launch_ring<kGroupFused>(p, st);
     case kGroupBias: return launch_ring<kGroupBias>(p, st);
+    case kGroupBiasWide: return launch_ring<kGroupBiasWide>(p, st);
     // conversion routes this kernel does not carry
     case kGroupReal:
     case kGroupCvt: return launch_gemm_prefill_dma(p, mode, 0, st);

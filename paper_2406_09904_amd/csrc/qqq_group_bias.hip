@@ -43,10 +43,11 @@ __device__ __forceinline__ void group_rowsum(const int8_t* __restrict__ a_q, int
   }
 }
 
-// Bc[n][g] = 8*s_g[g][n] - 128, zero for the padded groups: a transpose of [G][N] into [N][Gp]
+// Bc[n][g] = code_offset*s_g[g][n] - 128 (code_offset 8; 7 for the route of scales up to 18, whose bytes are
+// (7 - code) * s), zero for the padded groups: a transpose of [G][N] into [N][Gp]
 // through a 32 x 64 LDS tile, so that reads (along n) and writes (along g) are both contiguous
 __device__ __forceinline__ void group_bias_weights(const int8_t* __restrict__ s_g, int N, int G, int Gp,
-                                                   int8_t* __restrict__ bc, int tile_n, int tile_g) {
+                                                   int8_t* __restrict__ bc, int tile_n, int tile_g, int code_offset) {
   __shared__ int8_t tile[32][64 + 4];
   const int g0 = tile_g * 32, n0 = tile_n * 64;
   const int tid = threadIdx.x;
@@ -55,7 +56,7 @@ __device__ __forceinline__ void group_bias_weights(const int8_t* __restrict__ s_
   for (int pass = 0; pass < 8; ++pass) {
     const int r = pass * 4 + (tid >> 6), c = tid & 63;
     const int g = g0 + r, n = n0 + c;
-    tile[r][c] = (g < G && n < N) ? (int8_t)(8 * (int)s_g[(int64_t)g * N + n] - 128) : (int8_t)0;
+    tile[r][c] = (g < G && n < N) ? (int8_t)(code_offset * (int)s_g[(int64_t)g * N + n] - 128) : (int8_t)0;
   }
   __syncthreads();
   // 64 channels x 32 groups out: thread -> channel tid/4, 8 consecutive groups
@@ -78,24 +79,25 @@ __global__ __launch_bounds__(256) void group_bias_prepass_kernel(const int8_t* _
                                                                  int N, int K, int G, int Gp,
                                                                  int8_t* __restrict__ r_lo,
                                                                  int8_t* __restrict__ r_hi,
-                                                                 int8_t* __restrict__ bc) {
+                                                                 int8_t* __restrict__ bc, int code_offset) {
   if ((int)blockIdx.x < M) {
     group_rowsum(a_q, K, G, Gp, r_lo, r_hi, (int64_t)blockIdx.x);
   } else {
     const int t = (int)blockIdx.x - M, tiles_n = (N + 63) / 64;
-    group_bias_weights(s_g, N, G, Gp, bc, t % tiles_n, t / tiles_n);
+    group_bias_weights(s_g, N, G, Gp, bc, t % tiles_n, t / tiles_n, code_offset);
   }
 }
 
 // with_row_sums == false: the activation quantiser already wrote Rl/Rh (one-call linear path)
 int launch_group_bias_prepass(const int8_t* a_q, const int8_t* s_g, int64_t M, int64_t N, int64_t K,
-                              int8_t* r_lo, int8_t* r_hi, int8_t* bc, bool with_row_sums, hipStream_t st) {
+                              int8_t* r_lo, int8_t* r_hi, int8_t* bc, bool with_row_sums, int code_offset,
+                              hipStream_t st) {
   const int G = (int)(K / 128), Gp = (G + 31) & ~31;
   if (!with_row_sums) M = 0;
   const int64_t blocks = M + (int64_t)((N + 63) / 64) * (Gp / 32);
   if (blocks > 0x7FFFFFFF) return set_error(QQQ_ERR_SHAPE, "group bias pre-pass: grid too large");
   hipLaunchKernelGGL(group_bias_prepass_kernel, dim3((unsigned)blocks), dim3(256), 0, st, a_q, s_g, (int)M,
-                     (int)N, (int)K, G, Gp, r_lo, r_hi, bc);
+                     (int)N, (int)K, G, Gp, r_lo, r_hi, bc, code_offset);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return set_error(QQQ_ERR_HIP, "group bias pre-pass launch: %s", hipGetErrorString(e));
   route_note(with_row_sums ? "group-bias pre-pass" : "group-bias pre-pass (scales only)");

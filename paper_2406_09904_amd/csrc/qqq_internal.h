@@ -26,6 +26,9 @@ enum Mode : int {
   kGroupBias = 5,     // Sec. 3.3.2 with s_g <= 16, prefill: byte-wise integer multiply of code+8, sign by a
                       // top-bit flip; the constant 8*s_g - 128 per weight is taken out again through
                       // per-group row sums of the activations (see qqq_group_bias.hip)
+  kGroupBiasWide = 8, // the same byte-wise route for s_g <= 18 under the promise that no code is -8: bytes of
+                      // (7 - code) * s_g (<= 252), i.e. the NEGATED product plus (7*s_g - 128); the sign goes
+                      // into the Dequant's channel scale
   kGroupCvt = 6,      // ablation only (Sec. 4.5.2, Fig. 9): the real-valued scale through conventional
                       // conversion instructions instead of FastFP16toINT8
   kGroupReal = 4,     // Sec. 3.3.2 as printed: real-valued fp16 fused scale s*_Wg, one fp16 FMA with
@@ -72,7 +75,10 @@ int launch_pack(const uint32_t* w_nat, int64_t N, int64_t K, uint32_t* w_packed,
 int launch_gemm_skinny(const GemmParams& p, int mode, hipStream_t st);
 int decode_channel_tiles(int64_t N, int mt);  // 16-channel tiles per decode workgroup
 int launch_group_bias_prepass(const int8_t* a_q, const int8_t* s_g, int64_t M, int64_t N, int64_t K,
-                              int8_t* r_lo, int8_t* r_hi, int8_t* bc, bool with_row_sums, hipStream_t st);
+                              int8_t* r_lo, int8_t* r_hi, int8_t* bc, bool with_row_sums, int code_offset,
+                              hipStream_t st);
+// the two byte-wise integer routes of the per-group prefill GEMM
+constexpr bool is_bias_mode(int mode) { return mode == kGroupBias || mode == kGroupBiasWide; }
 void set_skinny_tuning(int nt, int s, int w, int u);
 void set_prefill_tuning(int tune);
 int get_prefill_tuning();
@@ -226,9 +232,12 @@ __device__ __forceinline__ uint32_t quant4(uint32_t w0, uint32_t w1, float s) {
 // Sec. 3.3.2, integer scale s <= 16, biased route: u = code + 8 per nibble, four u per dword scaled
 // by one 16-bit packed multiply (u*s <= 240 stays inside its byte), top bit flipped: each byte
 // is then code*s + (8s - 128) as int8.  7 VALU ops per 8 weights.
+// WIDE (s <= 18, no code is -8): the nibble XOR 7 is u = 7 - code in [0,14], u*s <= 252, and the byte is
+// -code*s + (7s - 128): the same seven instructions give the negated product.
+template <bool WIDE>
 __device__ __forceinline__ void unpack_group_bias(uint32_t x, uint32_t s2, int& lo, int& hi) {
-  const uint32_t ulo = (x ^ 0x88888888u) & 0x0F0F0F0Fu;
-  const uint32_t uhi = ((x >> 4) ^ 0x08080808u) & 0x0F0F0F0Fu;
+  const uint32_t ulo = (x ^ (WIDE ? 0x77777777u : 0x88888888u)) & 0x0F0F0F0Fu;
+  const uint32_t uhi = ((x >> 4) ^ (WIDE ? 0x07070707u : 0x08080808u)) & 0x0F0F0F0Fu;
   typedef unsigned short us2 __attribute__((ext_vector_type(2)));
   const us2 sv = __builtin_bit_cast(us2, s2);
   const us2 plo = __builtin_bit_cast(us2, ulo) * sv;

@@ -19,10 +19,10 @@ __device__ __forceinline__ v4i convert_b(uint32_t d0, uint32_t d1, int sg) {
     const h2 s2 = {hs, hs};
     unpack_group_clamp(d0, s2, o[0], o[1]);
     unpack_group_clamp(d1, s2, o[2], o[3]);
-  } else if constexpr (MODE == kGroupBias) {
+  } else if constexpr (is_bias_mode(MODE)) {
     const uint32_t s2 = (uint32_t)sg | ((uint32_t)sg << 16);
-    unpack_group_bias(d0, s2, o[0], o[1]);
-    unpack_group_bias(d1, s2, o[2], o[3]);
+    unpack_group_bias<MODE == kGroupBiasWide>(d0, s2, o[0], o[1]);
+    unpack_group_bias<MODE == kGroupBiasWide>(d1, s2, o[2], o[3]);
   } else if constexpr (MODE == kGroupReal || MODE == kGroupCvt) {
     // sg carries the fp16 bit pattern of the fused scale
     const h2 s2 = as_h2((uint32_t)sg | ((uint32_t)sg << 16));

@@ -194,5 +194,16 @@ def test_symmetric_codes_with_integer_scales_up_to_18(M, K, N):
             assert "mode=2" not in qqq.last_route(), qqq.last_route()
             assert np.array_equal(acc.cpu().numpy(), o_acc), (fam, qqq.last_route())
             assert ulp_distance(f16_bits(y), o_y).max() <= 1
+        if M > 16:       # both clamp-free prefill conversions: byte-wise integer (mode 8) and fp16 FMA (the mode 3 kernel)
+            qqq.set_kernel_override(2)
+            for knob, route in ((5, "mode=8"), (3, "mode=3")):
+                qqq.set_group_mode_override(knob)
+                acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
+                y = qqq.qqq_gemm_w4a8_pergroup(d_aq, d_sa, d_w, d_sg, d_sw, qqq.new_workspace(M, N, K),
+                                               sg_max=18 | qqq.SG_SYMMETRIC_CODES, acc_out=acc)
+                assert route in qqq.last_route(), qqq.last_route()
+                assert np.array_equal(acc.cpu().numpy(), o_acc), qqq.last_route()
+                assert ulp_distance(f16_bits(y), o_y).max() <= 1
     finally:
         qqq.set_kernel_override(0)
+        qqq.set_group_mode_override(0)

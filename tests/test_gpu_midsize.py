@@ -172,3 +172,30 @@ def test_persistent_kernel_with_more_tiles_than_cus(M, K, N, variant, hi, sg_max
     qqq.set_prefill_tuning(13)
     check(*run(variant, a_q, s_a, w, s_w, K, s_g=s_g, sg_max=sg_max), o_acc, o_y)
     assert "prefill persistent" in qqq.last_route(), qqq.last_route()
+
+
+@pytest.mark.parametrize("tune,k_splits", [(10, 1), (13, 1), (15, 1), (16, 1), (17, 1), (27, 1), (37, 1), (15, 2), (17, 3)])
+def test_wide_biased_route_through_every_prefill_kernel(tune, k_splits):
+    """Integer scales up to 18 with codes in [-7,7] (what the front-end emits): the byte-wise integer route forms
+    (7 - code) * s_g and the kernels carry the negated sums; forced through every tile shape, the persistent kernel
+    and K splits on ragged shapes, every element against the oracle."""
+    for (M, K, N) in ((150, 640, 784), (65, 384, 16), (333, 1408, 400)):
+        g = synth.rng(900 + M + tune)
+        w_nat = synth.codes_to_w_nat(g.integers(-7, 8, (N, K)).astype(np.int8))
+        s_g = g.integers(1, 19, (K // 128, N)).astype(np.int8)
+        s_g[0, :] = 18
+        a_q = synth.int8_activations(M, K, 901 + M)
+        s_a = synth.token_scales(M, 902 + M)
+        s_w = synth.weight_scales_fp16(N, 903 + M, 0.001, 0.01)
+        o_acc, _, o_y = orc.gemm_pergroup(a_q, s_a, w_nat, s_g, s_w.view(np.uint16))
+        qqq.set_prefill_tuning(tune)
+        qqq.set_prefill_ksplit(k_splits)
+        qqq.set_group_mode_override(5)
+        d_w = qqq.qqq_pack_w4(to_dev(w_nat, torch), K)
+        acc = torch.full((M, N), -12345, dtype=torch.int32, device="cuda")
+        y = qqq.qqq_gemm_w4a8_pergroup(to_dev(a_q, torch), to_dev(s_a, torch), d_w, to_dev(s_g, torch),
+                                       to_dev(s_w.view(np.uint16), torch), qqq.new_workspace(M, N, K),
+                                       sg_max=18 | qqq.SG_SYMMETRIC_CODES, acc_out=acc)
+        torch.cuda.synchronize()
+        assert "mode=8" in qqq.last_route(), qqq.last_route()
+        check(acc.cpu().numpy(), f16_bits(y), o_acc, o_y)
