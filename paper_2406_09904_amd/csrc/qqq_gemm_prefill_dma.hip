@@ -417,7 +417,7 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
         for (int v = 0; v < kRegs; ++v) {
           const int m = m0 + acc_row(mt, v);
           // (the wide biased route accumulates the negated sums)
-          if (m < M) part[(int64_t)m * N + col[c]] = MODE == kGroupBiasWide ? -acc[mt][c][v] : acc[mt][c][v];
+          if (m < M) part[(int64_t)m * N + col[c]] = MODE == kGroupBiasWide ? (int)(0u - (uint32_t)acc[mt][c][v]) : acc[mt][c][v];
         }
       }
     }
@@ -483,7 +483,7 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_prefill_dma_kernel(const Gemm
           if (m < M) {
             int x = acc[mt][c][v];
             if constexpr (MODE == kPerChannel) x >>= 4;
-            if constexpr (MODE == kGroupBiasWide) x = -x;
+            if constexpr (MODE == kGroupBiasWide) x = (int)(0u - (uint32_t)x);  // modular, like the sums
             p.acc_out[(int64_t)m * N + col[c]] = x;
           }
         }

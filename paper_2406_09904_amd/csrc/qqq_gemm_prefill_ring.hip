@@ -395,7 +395,7 @@ __global__ __launch_bounds__(512, 1) void gemm_prefill_ring_kernel(const GemmPar
               if (m < M) {
                 int x = acc[mt][c][v];
                 if constexpr (MODE == kPerChannel) x >>= 4;
-                if constexpr (MODE == kGroupBiasWide) x = -x;
+                if constexpr (MODE == kGroupBiasWide) x = (int)(0u - (uint32_t)x);  // modular, like the sums
                 p.acc_out[(int64_t)m * N + col] = x;
               }
             }
