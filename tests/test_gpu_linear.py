@@ -95,17 +95,22 @@ def test_linear_pergroup(M, K, N, hi, sg_max):
 
 
 @pytest.mark.parametrize("M,K,N", [(70, 1024, 512), (200, 384, 528), (130, 2560, 1040)])
-def test_linear_pergroup_biased_route_on_short_launches(M, K, N):
+@pytest.mark.parametrize("wide", [False, True])
+def test_linear_pergroup_biased_route_on_short_launches(M, K, N, wide):
     """The biased integer conversion forced where the automatic choice would skip its pre-pass: the
-    quantiser writes the per-group row sums the correction needs."""
+    quantiser writes the per-group row sums the correction needs.  wide: scales up to 18 with codes in
+    [-7,7], the route on 7 - code."""
     a = synth.activations_fp16(M, K, 19 * M + K + N)
-    w = synth.random_w_nat(N, K, 7 + N)
-    s_g = synth.group_scales(K, N, 8 + N, 1, 16)
+    if wide:
+        w = synth.codes_to_w_nat(synth.rng(7 + N).integers(-7, 8, (N, K)).astype(np.int8))
+    else:
+        w = synth.random_w_nat(N, K, 7 + N)
+    s_g = synth.group_scales(K, N, 8 + N, 1, 18 if wide else 16)
     s_w = synth.weight_scales_fp16(N, 9 + N, 0.001, 0.005)
     o_acc, o_y = oracle_linear(a, w, s_w, s_g)
     qqq.set_group_mode_override(5)
-    acc, y = run_linear(a, w, s_w, K, s_g=s_g, sg_max=16)
-    assert "mode=5" in qqq.last_route(), qqq.last_route()
+    acc, y = run_linear(a, w, s_w, K, s_g=s_g, sg_max=(18 | qqq.SG_SYMMETRIC_CODES) if wide else 16)
+    assert ("mode=8" if wide else "mode=5") in qqq.last_route(), qqq.last_route()
     check(acc, y, o_acc, o_y)
 
 
