@@ -190,7 +190,7 @@ static int kernel_family(int64_t M, int64_t N, int64_t K, bool pergroup) {
   if (M <= kDecodeAlwaysMaxM) return 1;
   if (M > kSkinnyMaxM) return 2;
   const double nk = (double)N * (double)K * 1e-6;
-  const int nt = decode_channel_tiles(N, (int)((M + 15) / 16));  // the launcher's own rule
+  const int nt = decode_channel_tiles(N, (int)((M + 15) / 16), true);  // the launcher's own rule
   const double* f = nt >= 4 ? (M <= 32 ? kModel.decode_c64_lo : kModel.decode_c64_hi)
                   : nt == 2 ? (M <= 32 ? kModel.decode_c32_lo : kModel.decode_c32_hi)
                             : (M <= 32 ? kModel.decode_c16_lo : kModel.decode_c16_hi);

@@ -510,22 +510,25 @@ static int launch_w(const GemmParams& p, int W, int S, hipStream_t st) {
 
 // Shape of the launch: channel tiles per workgroup (nt), waves per workgroup (w), K slices (s).
 // 16-channel tiles per workgroup for N channels and mt row tiles (also read by the dispatch model)
-int decode_channel_tiles(int64_t N, int mt) {
+int decode_channel_tiles(int64_t N, int mt, bool light_conversion) {
   int nt = (N % 64 == 0) ? 4 : (N % 32 == 0) ? 2 : 1;
   // (with several row tiles every workgroup re-reads all activations from L2, so the widest channel
   // group that keeps the CUs busy, rule below, also cuts those re-reads the most)
   // up to 32 rows: 128 channels where enough workgroups remain.  Every workgroup reads all activations
   // from L2 (from 9 rows on a third to two thirds of what it reads of the weights at 64 channels per
   // workgroup): cfg5 M=16 20.9 -> 20.0 us; with few rows it is level or slightly ahead
-  if (mt <= 2 && N % 128 == 0) nt = 8;
+  // (only with the light conversions, per-channel and group scale on partial sums: the per-weight fp16 routes
+  // need the second workgroup per CU to cover their arithmetic: real-valued scales, 8192 x 28672, M=1: 29.3 us
+  // with 128 channels, 26.8 with 64)
+  if (mt <= 2 && N % 128 == 0 && light_conversion) nt = 8;
   // Measured on MI355X: the widest channel group that still leaves about two workgroups for
   // every three CUs streams best, with 8 waves per workgroup and no K split (no atomics).
   while (nt > 1 && (N / (16 * nt)) * 3 < 2 * (int64_t)num_cus()) nt >>= 1;
   return nt;
 }
 
-static void choose_split(const GemmParams& p, int mt, int& nt, int& w, int& s) {
-  nt = decode_channel_tiles(p.N, mt);
+static void choose_split(const GemmParams& p, int mt, bool light_conversion, int& nt, int& w, int& s) {
+  nt = decode_channel_tiles(p.N, mt, light_conversion);
   const int cus = num_cus();
   w = (p.T >= 16) ? 8 : 4;
   // a workgroup with 32 KiB of weights or less (16 channels, K <= 4096) finishes sooner on 4 waves, each with
@@ -546,7 +549,7 @@ template <int MODE>
 static int launch_mode(const GemmParams& p, hipStream_t st) {
   const int mt = (p.M + 15) / 16;
   int nt, w, S;
-  choose_split(p, mt, nt, w, S);
+  choose_split(p, mt, MODE == kPerChannel || MODE == kGroupLinear, nt, w, S);
   if (g_tune_nt > 0 && p.N % (16 * g_tune_nt) == 0) nt = g_tune_nt;
   if (g_tune_s > 0 && g_tune_s <= p.T) S = g_tune_s;
   if (g_tune_w > 0) w = g_tune_w;

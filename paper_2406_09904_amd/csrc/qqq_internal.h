@@ -73,7 +73,7 @@ int launch_quant_weight(const void* w, int64_t N, int64_t K, int64_t ldw, bool g
 int launch_pack(const uint32_t* w_nat, int64_t N, int64_t K, uint32_t* w_packed, bool inverse,
                 hipStream_t st);
 int launch_gemm_skinny(const GemmParams& p, int mode, hipStream_t st);
-int decode_channel_tiles(int64_t N, int mt);  // 16-channel tiles per decode workgroup
+int decode_channel_tiles(int64_t N, int mt, bool light_conversion);  // 16-channel tiles per decode workgroup
 int launch_group_bias_prepass(const int8_t* a_q, const int8_t* s_g, int64_t M, int64_t N, int64_t K,
                               int8_t* r_lo, int8_t* r_hi, int8_t* bc, bool with_row_sums, int code_offset,
                               hipStream_t st);
